@@ -1,0 +1,187 @@
+/*
+ * ratsparse.h -- C ABI of the MI355X (gfx950) library for attention over an
+ * exponentially-decaying-memory KV cache under query-aware sparsity.
+ *
+ * The library covers the data-parallel hot path of the method: the gated decay
+ * recurrence that produces the augmented states (Sec. 2.1, Eq. 1), query-aware
+ * candidate selection (Sec. 2.2, Eq. 3) in its three evaluated forms (Quest pages,
+ * MoBA blocks, SnapKV tokens; App. A.1), and softmax attention over the selected
+ * states (Sec. 2.2, Eq. 4), with the dense path as the full-budget case.
+ *
+ * Conventions (all entry points)
+ *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned.
+ *     The library allocates nothing, frees nothing and keeps no pointer after a call
+ *     returns.  `const rs_shape *` is a HOST pointer, read during the call only.
+ *   - Tensors are C-contiguous, last dimension fastest.  `dtype` is the storage
+ *     type of q, k, v, both caches, page metadata and attention outputs (RS_F32 or
+ *     RS_BF16).  Gates, recurrence carries, block means, votes, scores and lse are
+ *     always float32; index lists are int32.  All arithmetic accumulates in float32.
+ *   - Query head h reads KV head h / (Hq / Hkv).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void *; NULL = the
+ *     default stream) and the call returns without waiting for it.  Arguments are
+ *     validated synchronously before anything is enqueued.
+ *   - Scratch memory is a caller buffer `ws` of at least <entry>_workspace_bytes()
+ *     bytes.  Its first RS_WS_CTRL_BYTES are control words that must be zero when a
+ *     call starts: zero them once with ratsparse_workspace_init(); every entry
+ *     point leaves them zero again when its kernels have finished.  One workspace
+ *     must not be used by two calls that can run at the same time.
+ *   - Return value: RS_OK or an error code below.  Nothing is printed or thrown.
+ *     A kernel-side failure of a bounded wait is recorded in the workspace and
+ *     reported by ratsparse_async_status().
+ *   - Outputs must not alias inputs.
+ */
+#ifndef RATSPARSE_H
+#define RATSPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    RS_OK = 0,
+    RS_INVALID_ARG = 1,         /* null / misaligned pointer, non-positive size, K out of range, T > Tcap */
+    RS_UNSUPPORTED = 2,         /* D not in {64,128}, page / block size not supported, dtype unknown */
+    RS_WORKSPACE_TOO_SMALL = 3, /* ws == NULL or ws_bytes below <entry>_workspace_bytes() */
+    RS_LAUNCH_FAILED = 4,       /* hipGetLastError() after a launch */
+    RS_ASYNC_TIMEOUT = 5        /* reported by ratsparse_async_status(): a bounded in-kernel wait expired */
+};
+
+enum { RS_F32 = 0, RS_BF16 = 1 };
+
+/* bytes at the start of every workspace reserved for control words */
+#define RS_WS_CTRL_BYTES 65536
+
+typedef struct rs_shape {
+    int32_t B;     /* batch */
+    int32_t Hq;    /* query heads */
+    int32_t Hkv;   /* KV heads, divides Hq */
+    int32_t D;     /* head dimension: 64 or 128 */
+    int32_t Tcap;  /* rows per (batch, KV head) of the caches (row stride); multiple of P */
+    int32_t P;     /* Quest page size in tokens: 16, 32, 64 or 128 (used by the page entry points) */
+    int32_t dtype; /* RS_F32 or RS_BF16 */
+} rs_shape;
+
+const char *ratsparse_status_string(int32_t status);
+const char *ratsparse_version(void);
+
+/* Zero the control words of a freshly allocated workspace (needed once). */
+int32_t ratsparse_workspace_init(void *ws, size_t ws_bytes, void *stream);
+
+/* Waits for `stream`, then returns RS_OK, or RS_ASYNC_TIMEOUT if a kernel that used
+ * `ws` gave up a bounded wait (its outputs are then undefined); clears the record. */
+int32_t ratsparse_async_status(void *ws, void *stream);
+
+/* ---- Exponentially decaying memory: Sec. 2.1, Eq. 1 --------------------------------
+ * For every (batch, KV head, channel):  s_t = g_t * s_{t-1} + (1 - g_t) * x_t  for the
+ * T_new tokens given, for x = k and x = v with the same gate, starting from the carry.
+ *   k, v   [B, Hkv, T_new, D] dtype      new keys / values
+ *   g      [B, Hkv, T_new, D] float32    gates in [0, 1]
+ *   state_k, state_v [B, Hkv, D] float32 in: s_{t0-1} (zeros for a fresh sequence);
+ *                                        out: the unrounded state after the last token
+ *   k_cache, v_cache [B, Hkv, Tcap, D] dtype   rows t0 .. t0+T_new-1 are written with
+ *                                        the states rounded to nearest-even
+ * T_new = 1 is the decode-time append.  Requires 0 <= t0, t0 + T_new <= Tcap.
+ * Evaluated as a chunked scan; the result equals the sequential recurrence up to
+ * float32 rounding order. */
+size_t rat_scan_workspace_bytes(const rs_shape *s, int64_t T_new);
+int32_t rat_scan(const rs_shape *s, const void *k, const void *v, const float *g,
+                 float *state_k, float *state_v, void *k_cache, void *v_cache, int64_t t0,
+                 int64_t T_new, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- Quest block representatives: App. A.1, Quest paragraph --------------------------
+ * Per page of P tokens and per channel, the minimum and maximum stored key.
+ *   k_cache [B, Hkv, Tcap, D] dtype
+ *   meta    [B, Hkv, Tcap/P, 2, D] dtype   row 0 = min, row 1 = max
+ * Recomputes every page that intersects [t_begin, t_end), over its tokens t < t_end
+ * (the tokens of a page that lie before t_begin are read too).  Use [0, T) after a
+ * prefill and [t, t+1) after appending token t. */
+int32_t quest_page_meta(const rs_shape *s, const void *k_cache, void *meta, int64_t t_begin,
+                        int64_t t_end, void *stream);
+
+/* ---- Quest page selection at decode: Sec. 2.2, Eq. 3; App. A.1 ------------------------
+ * score_p = sum_c max(q_c * min_{p,c}, q_c * max_{p,c}) over the Np = ceil(T_valid/P)
+ * pages; per (batch, query head) the K best pages, larger score first, lower index
+ * first among equal scores.  Pages 0 .. n_first-1 and the last n_local pages are
+ * always kept and count inside K.
+ *   q          [B, Hq, D] dtype
+ *   idx_out    [B, Hq, K] int32, ascending
+ *   scores_out [B, Hq, Np] float32 or NULL
+ * Requires 1 <= K <= Np and K >= number of always-kept pages. */
+size_t quest_select_decode_workspace_bytes(const rs_shape *s, int64_t T_valid);
+int32_t quest_select_decode(const rs_shape *s, const void *q, const void *meta,
+                            int64_t T_valid, int32_t K, int32_t n_first, int32_t n_local,
+                            int32_t *idx_out, float *scores_out, void *ws, size_t ws_bytes,
+                            void *stream);
+
+/* ---- Sparse evaluation at decode: Sec. 2.2, Eq. 4 (f = softmax) -----------------------
+ * y = softmax(scale * q K~_I^T) V~_I over the tokens t < T_valid of the selected pages.
+ * Three modes:
+ *   idx != NULL                 attend the K listed pages ([B, Hq, K] int32; entries < 0
+ *                               are skipped; each page at most once);
+ *   idx == NULL, meta != NULL   fused select-then-attend: selection exactly as
+ *                               quest_select_decode, unselected KV is never read;
+ *                               idx_out ([B, Hq, K] or NULL) receives the selection;
+ *   idx == NULL, meta == NULL   dense attention over all tokens t < T_valid (full budget).
+ *   out     [B, Hq, D] dtype
+ *   lse_out [B, Hq] float32 or NULL: log-sum-exp of the scaled logits */
+size_t sparse_attn_decode_workspace_bytes(const rs_shape *s, int64_t T_valid, int32_t K);
+int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache,
+                           const void *v_cache, int64_t T_valid, float scale,
+                           const int32_t *idx, int32_t K, const void *meta, int32_t n_first,
+                           int32_t n_local, void *out, float *lse_out, int32_t *idx_out,
+                           void *ws, size_t ws_bytes, void *stream);
+
+/* ---- MoBA routing at prefill: Sec. 2.2, Eq. 3; App. A.1, MoBA paragraph ----------------
+ * Block representative = mean of the stored keys of a block of `block` tokens (the
+ * tail block over its valid tokens).  Each query token t, in block b(t) = t / block,
+ * scores the blocks j < b(t) by q_t . mean_j; its own block and the first n_first
+ * blocks are always kept and count inside K.
+ *   q         [B, Hq, T, D] dtype
+ *   means_out [B, Hkv, ceil(T/block), D] float32
+ *   idx_out   [B, Hq, T, K] int32, ascending, padded with -1 when fewer than K exist
+ * block is a multiple of 16; ceil(T/block) <= 1024; 1 + n_first <= K <= 32. */
+size_t moba_select_prefill_workspace_bytes(const rs_shape *s, int64_t T, int32_t block);
+int32_t moba_select_prefill(const rs_shape *s, const void *q, const void *k_cache, int64_t T,
+                            int32_t block, int32_t K, int32_t n_first, float *means_out,
+                            int32_t *idx_out, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- Sparse evaluation at prefill: Sec. 2.2, Eq. 4 ------------------------------------
+ * For every query token t: softmax attention over the tokens i <= t of its listed
+ * blocks (idx [B, Hq, T, K] as written by moba_select_prefill), or causal dense
+ * attention when idx == NULL.
+ *   out     [B, Hq, T, D] dtype
+ *   lse_out [B, Hq, T] float32 or NULL */
+size_t sparse_attn_prefill_workspace_bytes(const rs_shape *s, int64_t T, int32_t block,
+                                           int32_t K);
+int32_t sparse_attn_prefill(const rs_shape *s, const void *q, const void *k_cache,
+                            const void *v_cache, int64_t T, int32_t block, float scale,
+                            const int32_t *idx, int32_t K, void *out, float *lse_out,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/* ---- SnapKV cache compression: App. A.1, SnapKV paragraph; Eq. 3 over single tokens ----
+ * The W observation queries sit at positions T-W .. T-1 and attend causally; the vote
+ * of a prefix position i < T-W is its attention probability summed over the W rows and
+ * over the query heads of its KV head's group; votes are max-pooled (window
+ * pool_kernel, odd, stride 1, clipped at the ends); per KV head the K_keep best
+ * positions are kept (lower index first among equal votes), in ascending order,
+ * followed by the W window rows.
+ *   q_win    [B, Hq, W, D] dtype
+ *   kc_out, vc_out [B, Hkv, Tcap_out, D] dtype: rows 0 .. K_keep+W-1 written
+ *   idx_out  [B, Hkv, K_keep] int32
+ *   votes_out [B, Hkv, T-W] float32 or NULL: the pooled votes
+ * Decoding afterwards: rat_scan appends into kc_out / vc_out from row K_keep+W, then
+ * dense sparse_attn_decode over them. */
+size_t snapkv_compress_workspace_bytes(const rs_shape *s, int64_t T, int32_t W);
+int32_t snapkv_compress(const rs_shape *s, const void *q_win, const void *k_cache,
+                        const void *v_cache, int64_t T, int32_t W, int32_t K_keep,
+                        int32_t pool_kernel, float scale, void *kc_out, void *vc_out,
+                        int64_t Tcap_out, int32_t *idx_out, float *votes_out, void *ws,
+                        size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

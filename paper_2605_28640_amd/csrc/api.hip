@@ -1,0 +1,372 @@
+// C ABI of the library: argument validation, workspace layout, kernel dispatch.
+#include <atomic>
+#include <chrono>
+#include <cstdlib>
+
+#include "common.h"
+
+namespace rs {
+// scan.hip
+int scan_chunk_tokens(int dtype, int D);
+void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
+                   float *state_v, void *k_cache, void *v_cache, int BH, long T_new, long t0, long Tcap,
+                   uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit, hipStream_t stream);
+// quest.hip
+void page_meta_dispatch(int dtype, int D, const void *k_cache, void *meta, int BH, long Tcap, int P,
+                        int p_begin, int n_pages, long t_end, hipStream_t stream);
+void score_select_dispatch(int dtype, int D, const void *q, const void *meta, float *scores, int32_t *idx_out,
+                           int B, int Hq, int Hkv, long Np_cap, int Np, int K, int n_first, int n_local,
+                           int splits, uint32_t *unit_ctr, hipStream_t stream);
+void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache, const void *v_cache,
+                            const int32_t *idx, void *out, float *lse_out, float *partial, int B, int Hq,
+                            int Hkv, long Tcap, int P, long T_valid, int K, float scale, int splits,
+                            uint32_t *unit_ctr, hipStream_t stream);
+// moba.hip / prefill.hip / snapkv.hip
+size_t moba_select_ws_bytes(const rs_shape *s, long T, int block);
+int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, long T, int block, int K,
+                         int n_first, float *means_out, int32_t *idx_out, char *ws, hipStream_t stream);
+size_t prefill_ws_bytes(const rs_shape *s, long T, int block, int K);
+int prefill_dispatch(const rs_shape *s, const void *q, const void *k_cache, const void *v_cache, long T,
+                     int block, float scale, const int32_t *idx, int K, void *out, float *lse_out, char *ws,
+                     hipStream_t stream);
+size_t snapkv_ws_bytes(const rs_shape *s, long T, int W);
+int snapkv_dispatch(const rs_shape *s, const void *q_win, const void *k_cache, const void *v_cache, long T,
+                    int W, int K_keep, int pool_kernel, float scale, void *kc_out, void *vc_out, long Tcap_out,
+                    int32_t *idx_out, float *votes_out, char *ws, hipStream_t stream);
+
+__global__ void fill_zero_kernel(uint32_t *p, long n)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+static std::atomic<int> g_spin_limit{1 << 22};
+static std::atomic<uint32_t> g_epoch{0};
+
+static uint32_t next_tag()
+{
+    // a fresh 32-bit tag per call: records left in a workspace by earlier calls, or
+    // whatever else the memory held, do not match it
+    uint32_t e = g_epoch.load();
+    if (e == 0) {
+        const uint64_t now = (uint64_t)std::chrono::steady_clock::now().time_since_epoch().count();
+        uint32_t seed = (uint32_t)(now ^ (now >> 32)) | 1u;
+        g_epoch.compare_exchange_strong(e, seed);
+    }
+    uint32_t t = g_epoch.fetch_add(0x9E3779B1u) + 0x9E3779B1u;
+    return t ? t : 0x5bd1e995u;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+static size_t esize(int dtype) { return dtype == RS_BF16 ? 2 : 4; }
+
+static int check_shape(const rs_shape *s, bool need_page)
+{
+    if (!s) return RS_INVALID_ARG;
+    if (s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->Tcap <= 0) return RS_INVALID_ARG;
+    if (s->Hq % s->Hkv != 0) return RS_INVALID_ARG;
+    if (s->dtype != RS_F32 && s->dtype != RS_BF16) return RS_UNSUPPORTED;
+    if (s->D != 64 && s->D != 128) return RS_UNSUPPORTED;
+    if (need_page) {
+        if (s->P != 16 && s->P != 32 && s->P != 64 && s->P != 128) return RS_UNSUPPORTED;
+        if (s->Tcap % s->P != 0) return RS_INVALID_ARG;
+    }
+    if ((long)s->B * s->Hq > kMaxUnits) return RS_UNSUPPORTED;
+    return RS_OK;
+}
+
+static int launch_status() { return hipGetLastError() == hipSuccess ? RS_OK : RS_LAUNCH_FAILED; }
+
+// work split heuristics: enough workgroups to cover 256 CUs several times over
+static int pick_splits(long units, long items, long min_items_per_split, long target_wgs)
+{
+    long s = (target_wgs + units - 1) / units;
+    const long cap = items / min_items_per_split;
+    if (s > cap) s = cap;
+    if (s < 1) s = 1;
+    if (s > 1024) s = 1024;
+    return (int)s;
+}
+
+static int env_int(const char *name, int dflt)
+{
+    const char *e = std::getenv(name);
+    return e ? std::atoi(e) : dflt;
+}
+
+struct DecodeLayout {
+    int Np, splits_score, splits_att_max;
+    size_t off_scores, off_idx, off_partial, total;
+};
+
+static DecodeLayout decode_layout(const rs_shape *s, long T_valid, int K)
+{
+    DecodeLayout L;
+    const long units = (long)s->B * s->Hq;
+    L.Np = (int)((T_valid + s->P - 1) / s->P);
+    L.splits_score = pick_splits(units, L.Np, 64, env_int("RATSPARSE_SCORE_WGS", 2048));
+    const long dense_tiles = (T_valid + 15) / 16;
+    L.splits_att_max = pick_splits(units, dense_tiles, 8, env_int("RATSPARSE_ATTEND_WGS", 2048));
+    size_t off = RS_WS_CTRL_BYTES;
+    L.off_scores = off;
+    off += align256((size_t)units * L.Np * 4);
+    L.off_idx = off;
+    off += align256((size_t)units * (K > 0 ? K : 1) * 4);
+    L.off_partial = off;
+    off += align256((size_t)units * L.splits_att_max * (s->D + 2) * 4);
+    L.total = off;
+    return L;
+}
+
+}  // namespace rs
+
+using namespace rs;
+
+extern "C" {
+
+const char *ratsparse_status_string(int32_t status)
+{
+    switch (status) {
+        case RS_OK: return "ok";
+        case RS_INVALID_ARG: return "invalid argument";
+        case RS_UNSUPPORTED: return "unsupported shape or dtype";
+        case RS_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case RS_LAUNCH_FAILED: return "kernel launch failed";
+        case RS_ASYNC_TIMEOUT: return "a bounded in-kernel wait expired";
+        default: return "unknown status";
+    }
+}
+
+const char *ratsparse_version(void) { return "ratsparse 0.1 (gfx950)"; }
+
+// test hook: bound of the scan's in-kernel wait, in polls
+void ratsparse_debug_set_spin_limit(int32_t polls) { g_spin_limit.store(polls < 0 ? 0 : polls); }
+
+int32_t ratsparse_workspace_init(void *ws, size_t ws_bytes, void *stream)
+{
+    if (!ws || !aligned16(ws)) return RS_INVALID_ARG;
+    if (ws_bytes < RS_WS_CTRL_BYTES) return RS_WORKSPACE_TOO_SMALL;
+    const long n = RS_WS_CTRL_BYTES / 4;
+    fill_zero_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>((uint32_t *)ws, n);
+    return launch_status();
+}
+
+int32_t ratsparse_async_status(void *ws, void *stream)
+{
+    if (!ws) return RS_INVALID_ARG;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return RS_LAUNCH_FAILED;
+    uint32_t flag = 0;
+    if (hipMemcpy(&flag, ws, 4, hipMemcpyDeviceToHost) != hipSuccess) return RS_LAUNCH_FAILED;
+    if (flag) {
+        fill_zero_kernel<<<1, 64, 0, (hipStream_t)stream>>>((uint32_t *)ws, 3);  // error word and scan counters
+        (void)hipStreamSynchronize((hipStream_t)stream);
+        return RS_ASYNC_TIMEOUT;
+    }
+    return RS_OK;
+}
+
+size_t rat_scan_workspace_bytes(const rs_shape *s, int64_t T_new)
+{
+    if (check_shape(s, false) != RS_OK || T_new <= 0) return 0;
+    const long chunk = scan_chunk_tokens(s->dtype, s->D);
+    const long n_chunks = (T_new + chunk - 1) / chunk;
+    return RS_WS_CTRL_BYTES + align256((size_t)s->B * s->Hkv * n_chunks * 2 * s->D * 8);
+}
+
+int32_t rat_scan(const rs_shape *s, const void *k, const void *v, const float *g, float *state_k,
+                 float *state_v, void *k_cache, void *v_cache, int64_t t0, int64_t T_new, void *ws,
+                 size_t ws_bytes, void *stream)
+{
+    int st = check_shape(s, false);
+    if (st != RS_OK) return st;
+    if (!k || !v || !g || !state_k || !state_v || !k_cache || !v_cache) return RS_INVALID_ARG;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(state_k) || !aligned16(state_v) ||
+        !aligned16(k_cache) || !aligned16(v_cache))
+        return RS_INVALID_ARG;
+    if (T_new <= 0 || t0 < 0 || t0 + T_new > s->Tcap) return RS_INVALID_ARG;
+    const long BH = (long)s->B * s->Hkv;
+    const long chunk = scan_chunk_tokens(s->dtype, s->D);
+    const long n_chunks = (T_new + chunk - 1) / chunk;
+    if (BH * n_chunks > 0x7fffffffL) return RS_UNSUPPORTED;
+    uint32_t *ctrl = nullptr;
+    uint64_t *rec = nullptr;
+    if (T_new > 8 && n_chunks > 1) {
+        if (!ws || !aligned16(ws) || ws_bytes < rat_scan_workspace_bytes(s, T_new)) return RS_WORKSPACE_TOO_SMALL;
+        ctrl = (uint32_t *)ws;
+        rec = (uint64_t *)((char *)ws + RS_WS_CTRL_BYTES);
+    }
+    scan_dispatch(s->dtype, s->D, k, v, g, state_k, state_v, k_cache, v_cache, (int)BH, T_new, t0, s->Tcap, ctrl,
+                  rec, next_tag(), g_spin_limit.load(), (hipStream_t)stream);
+    return launch_status();
+}
+
+int32_t quest_page_meta(const rs_shape *s, const void *k_cache, void *meta, int64_t t_begin, int64_t t_end,
+                        void *stream)
+{
+    int st = check_shape(s, true);
+    if (st != RS_OK) return st;
+    if (!k_cache || !meta || !aligned16(k_cache) || !aligned16(meta)) return RS_INVALID_ARG;
+    if (t_begin < 0 || t_end <= t_begin || t_end > s->Tcap) return RS_INVALID_ARG;
+    const int p_begin = (int)(t_begin / s->P);
+    const int p_end = (int)((t_end + s->P - 1) / s->P);
+    page_meta_dispatch(s->dtype, s->D, k_cache, meta, s->B * s->Hkv, s->Tcap, s->P, p_begin, p_end - p_begin, t_end,
+                       (hipStream_t)stream);
+    return launch_status();
+}
+
+static int check_select(const rs_shape *s, int64_t T_valid, int K, int n_first, int n_local)
+{
+    if (T_valid <= 0 || T_valid > s->Tcap) return RS_INVALID_ARG;
+    const long Np = (T_valid + s->P - 1) / s->P;
+    if (K < 1 || K > Np || n_first < 0 || n_local < 0) return RS_INVALID_ARG;
+    long forced = (long)n_first + n_local;
+    if (forced > Np) forced = Np;
+    if (forced > K) return RS_INVALID_ARG;
+    return RS_OK;
+}
+
+size_t quest_select_decode_workspace_bytes(const rs_shape *s, int64_t T_valid)
+{
+    if (check_shape(s, true) != RS_OK || T_valid <= 0) return 0;
+    return decode_layout(s, T_valid, 1).total;
+}
+
+int32_t quest_select_decode(const rs_shape *s, const void *q, const void *meta, int64_t T_valid, int32_t K,
+                            int32_t n_first, int32_t n_local, int32_t *idx_out, float *scores_out, void *ws,
+                            size_t ws_bytes, void *stream)
+{
+    int st = check_shape(s, true);
+    if (st != RS_OK) return st;
+    if (!q || !meta || !idx_out || !aligned16(q) || !aligned16(meta) || !aligned16(idx_out)) return RS_INVALID_ARG;
+    if (scores_out && !aligned16(scores_out)) return RS_INVALID_ARG;
+    st = check_select(s, T_valid, K, n_first, n_local);
+    if (st != RS_OK) return st;
+    const DecodeLayout L = decode_layout(s, T_valid, 1);
+    if (!ws || !aligned16(ws) || ws_bytes < L.total) return RS_WORKSPACE_TOO_SMALL;
+    char *w = (char *)ws;
+    float *scores = scores_out ? scores_out : (float *)(w + L.off_scores);
+    score_select_dispatch(s->dtype, s->D, q, meta, scores, idx_out, s->B, s->Hq, s->Hkv, s->Tcap / s->P, L.Np, K,
+                          n_first, n_local, L.splits_score, (uint32_t *)w + kCtrlUnit0, (hipStream_t)stream);
+    return launch_status();
+}
+
+size_t sparse_attn_decode_workspace_bytes(const rs_shape *s, int64_t T_valid, int32_t K)
+{
+    if (check_shape(s, true) != RS_OK || T_valid <= 0) return 0;
+    return decode_layout(s, T_valid, K).total;
+}
+
+int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache, const void *v_cache,
+                           int64_t T_valid, float scale, const int32_t *idx, int32_t K, const void *meta,
+                           int32_t n_first, int32_t n_local, void *out, float *lse_out, int32_t *idx_out, void *ws,
+                           size_t ws_bytes, void *stream)
+{
+    int st = check_shape(s, true);
+    if (st != RS_OK) return st;
+    if (!q || !k_cache || !v_cache || !out) return RS_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return RS_INVALID_ARG;
+    if (T_valid <= 0 || T_valid > s->Tcap) return RS_INVALID_ARG;
+    const bool listed = idx != nullptr, fused = !listed && meta != nullptr;
+    const long Np = (T_valid + s->P - 1) / s->P;
+    if (listed && (K < 1 || K > Np || !aligned16(idx))) return RS_INVALID_ARG;
+    if (fused) {
+        st = check_select(s, T_valid, K, n_first, n_local);
+        if (st != RS_OK) return st;
+        if (!aligned16(meta) || (idx_out && !aligned16(idx_out))) return RS_INVALID_ARG;
+    }
+    const int Kws = (listed || fused) ? K : 0;
+    const DecodeLayout L = decode_layout(s, T_valid, Kws);
+    if (!ws || !aligned16(ws) || ws_bytes < L.total) return RS_WORKSPACE_TOO_SMALL;
+    char *w = (char *)ws;
+    uint32_t *ctr_score = (uint32_t *)w + kCtrlUnit0;
+    uint32_t *ctr_att = ctr_score + kMaxUnits;
+    const long units = (long)s->B * s->Hq;
+    const int32_t *use_idx = idx;
+    if (fused) {
+        int32_t *sel = idx_out ? idx_out : (int32_t *)(w + L.off_idx);
+        score_select_dispatch(s->dtype, s->D, q, meta, (float *)(w + L.off_scores), sel, s->B, s->Hq, s->Hkv,
+                              s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score, ctr_score,
+                              (hipStream_t)stream);
+        if (launch_status() != RS_OK) return RS_LAUNCH_FAILED;
+        use_idx = sel;
+    }
+    const long tiles = use_idx ? (long)K * (s->P / 16) : (T_valid + 15) / 16;
+    int splits = pick_splits(units, tiles, 8, env_int("RATSPARSE_ATTEND_WGS", 2048));
+    if (splits > L.splits_att_max) splits = L.splits_att_max;
+    decode_attend_dispatch(s->dtype, s->D, q, k_cache, v_cache, use_idx, out, lse_out, (float *)(w + L.off_partial),
+                           s->B, s->Hq, s->Hkv, s->Tcap, s->P, T_valid, K, scale, splits, ctr_att,
+                           (hipStream_t)stream);
+    return launch_status();
+}
+
+size_t moba_select_prefill_workspace_bytes(const rs_shape *s, int64_t T, int32_t block)
+{
+    if (check_shape(s, false) != RS_OK || T <= 0 || block <= 0) return 0;
+    return moba_select_ws_bytes(s, T, block);
+}
+
+int32_t moba_select_prefill(const rs_shape *s, const void *q, const void *k_cache, int64_t T, int32_t block,
+                            int32_t K, int32_t n_first, float *means_out, int32_t *idx_out, void *ws,
+                            size_t ws_bytes, void *stream)
+{
+    int st = check_shape(s, false);
+    if (st != RS_OK) return st;
+    if (!q || !k_cache || !means_out || !idx_out) return RS_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(means_out) || !aligned16(idx_out)) return RS_INVALID_ARG;
+    if (T <= 0 || T > s->Tcap || block <= 0 || block % 16 != 0) return RS_INVALID_ARG;
+    const long Nb = (T + block - 1) / block;
+    if (Nb > 1024) return RS_UNSUPPORTED;
+    if (n_first < 0 || K < 1 + n_first || K > 32) return RS_INVALID_ARG;
+    if (!ws || !aligned16(ws) || ws_bytes < moba_select_ws_bytes(s, T, block)) return RS_WORKSPACE_TOO_SMALL;
+    return moba_select_dispatch(s, q, k_cache, T, block, K, n_first, means_out, idx_out, (char *)ws,
+                                (hipStream_t)stream);
+}
+
+size_t sparse_attn_prefill_workspace_bytes(const rs_shape *s, int64_t T, int32_t block, int32_t K)
+{
+    if (check_shape(s, false) != RS_OK || T <= 0 || block <= 0) return 0;
+    return prefill_ws_bytes(s, T, block, K);
+}
+
+int32_t sparse_attn_prefill(const rs_shape *s, const void *q, const void *k_cache, const void *v_cache, int64_t T,
+                            int32_t block, float scale, const int32_t *idx, int32_t K, void *out, float *lse_out,
+                            void *ws, size_t ws_bytes, void *stream)
+{
+    int st = check_shape(s, false);
+    if (st != RS_OK) return st;
+    if (!q || !k_cache || !v_cache || !out) return RS_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return RS_INVALID_ARG;
+    if (T <= 0 || T > s->Tcap || block <= 0 || block % 16 != 0) return RS_INVALID_ARG;
+    if (idx && (K < 1 || K > 32 || !aligned16(idx))) return RS_INVALID_ARG;
+    if (!ws || !aligned16(ws) || ws_bytes < prefill_ws_bytes(s, T, block, K)) return RS_WORKSPACE_TOO_SMALL;
+    return prefill_dispatch(s, q, k_cache, v_cache, T, block, scale, idx, K, out, lse_out, (char *)ws,
+                            (hipStream_t)stream);
+}
+
+size_t snapkv_compress_workspace_bytes(const rs_shape *s, int64_t T, int32_t W)
+{
+    if (check_shape(s, false) != RS_OK || T <= 0 || W <= 0) return 0;
+    return snapkv_ws_bytes(s, T, W);
+}
+
+int32_t snapkv_compress(const rs_shape *s, const void *q_win, const void *k_cache, const void *v_cache, int64_t T,
+                        int32_t W, int32_t K_keep, int32_t pool_kernel, float scale, void *kc_out, void *vc_out,
+                        int64_t Tcap_out, int32_t *idx_out, float *votes_out, void *ws, size_t ws_bytes,
+                        void *stream)
+{
+    int st = check_shape(s, false);
+    if (st != RS_OK) return st;
+    if (!q_win || !k_cache || !v_cache || !kc_out || !vc_out || !idx_out) return RS_INVALID_ARG;
+    if (!aligned16(q_win) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(kc_out) ||
+        !aligned16(vc_out) || !aligned16(idx_out) || (votes_out && !aligned16(votes_out)))
+        return RS_INVALID_ARG;
+    if (T <= 0 || T > s->Tcap || W <= 0 || W >= T) return RS_INVALID_ARG;
+    if (K_keep < 0 || K_keep > T - W || K_keep + W > Tcap_out) return RS_INVALID_ARG;
+    if (pool_kernel < 1 || pool_kernel % 2 == 0 || pool_kernel > 63) return RS_INVALID_ARG;
+    if (!ws || !aligned16(ws) || ws_bytes < snapkv_ws_bytes(s, T, W)) return RS_WORKSPACE_TOO_SMALL;
+    return snapkv_dispatch(s, q_win, k_cache, v_cache, T, W, K_keep, pool_kernel, scale, kc_out, vc_out, Tcap_out,
+                           idx_out, votes_out, (char *)ws, (hipStream_t)stream);
+}
+
+}  // extern "C"

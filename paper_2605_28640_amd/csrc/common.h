@@ -1,0 +1,157 @@
+// Device-side helpers shared by the gfx950 kernels: storage-type access (bf16 / f32),
+// wave64 shuffles and reductions, workspace control-word layout.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ratsparse.h"
+
+namespace rs {
+
+constexpr int kWave = 64;
+
+// ---- workspace control words (uint32 index into the first RS_WS_CTRL_BYTES) ----
+constexpr int kCtrlAsyncErr = 0;  // set to 1 by a kernel whose bounded wait expired
+constexpr int kCtrlTicket = 1;    // dynamic chunk ticket of the scan
+constexpr int kCtrlDone = 2;      // finished-workgroup counter of the scan
+constexpr int kCtrlUnit0 = 64;    // per-(batch, head) arrival counters start here
+constexpr int kCtrlWords = RS_WS_CTRL_BYTES / 4;
+constexpr int kMaxUnits = (kCtrlWords - kCtrlUnit0) / 2;
+
+struct bf16 {
+    uint16_t bits;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// round-to-nearest-even float32 -> bfloat16 bits (NaN kept quiet)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// 8 consecutive channels of one row: raw registers as loaded, and their float32 view
+template <typename ST>
+struct Row8;
+
+template <>
+struct Row8<bf16> {
+    struct raw_t {
+        uint4 r;
+    };
+    __device__ __forceinline__ static raw_t load_raw(const bf16 *p)
+    {
+        raw_t w;
+        w.r = *reinterpret_cast<const uint4 *>(p);
+        return w;
+    }
+    __device__ __forceinline__ static raw_t zero_raw()
+    {
+        raw_t w;
+        w.r = make_uint4(0u, 0u, 0u, 0u);
+        return w;
+    }
+    __device__ __forceinline__ static void unpack(const raw_t &w, float (&x)[8])
+    {
+        x[0] = __uint_as_float(w.r.x << 16);
+        x[1] = __uint_as_float(w.r.x & 0xffff0000u);
+        x[2] = __uint_as_float(w.r.y << 16);
+        x[3] = __uint_as_float(w.r.y & 0xffff0000u);
+        x[4] = __uint_as_float(w.r.z << 16);
+        x[5] = __uint_as_float(w.r.z & 0xffff0000u);
+        x[6] = __uint_as_float(w.r.w << 16);
+        x[7] = __uint_as_float(w.r.w & 0xffff0000u);
+    }
+    __device__ __forceinline__ static void load(const bf16 *p, float (&x)[8]) { unpack(load_raw(p), x); }
+    __device__ __forceinline__ static void store(bf16 *p, const float (&x)[8])
+    {
+        uint4 r;
+        r.x = f32_to_bf16_bits(x[0]) | (f32_to_bf16_bits(x[1]) << 16);
+        r.y = f32_to_bf16_bits(x[2]) | (f32_to_bf16_bits(x[3]) << 16);
+        r.z = f32_to_bf16_bits(x[4]) | (f32_to_bf16_bits(x[5]) << 16);
+        r.w = f32_to_bf16_bits(x[6]) | (f32_to_bf16_bits(x[7]) << 16);
+        *reinterpret_cast<uint4 *>(p) = r;
+    }
+};
+
+template <>
+struct Row8<float> {
+    struct raw_t {
+        float4 a, b;
+    };
+    __device__ __forceinline__ static raw_t load_raw(const float *p)
+    {
+        raw_t w;
+        w.a = *reinterpret_cast<const float4 *>(p);
+        w.b = *reinterpret_cast<const float4 *>(p + 4);
+        return w;
+    }
+    __device__ __forceinline__ static raw_t zero_raw()
+    {
+        raw_t w;
+        w.a = make_float4(0.f, 0.f, 0.f, 0.f);
+        w.b = w.a;
+        return w;
+    }
+    __device__ __forceinline__ static void unpack(const raw_t &w, float (&x)[8])
+    {
+        x[0] = w.a.x; x[1] = w.a.y; x[2] = w.a.z; x[3] = w.a.w;
+        x[4] = w.b.x; x[5] = w.b.y; x[6] = w.b.z; x[7] = w.b.w;
+    }
+    __device__ __forceinline__ static void load(const float *p, float (&x)[8]) { unpack(load_raw(p), x); }
+    __device__ __forceinline__ static void store(float *p, const float (&x)[8])
+    {
+        *reinterpret_cast<float4 *>(p) = make_float4(x[0], x[1], x[2], x[3]);
+        *reinterpret_cast<float4 *>(p + 4) = make_float4(x[4], x[5], x[6], x[7]);
+    }
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16 x) { return bf16_bits_to_f32(x.bits); }
+__device__ __forceinline__ void from_f32(float &d, float x) { d = x; }
+__device__ __forceinline__ void from_f32(bf16 &d, float x) { d.bits = (uint16_t)f32_to_bf16_bits(x); }
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+__device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, kWave); }
+__device__ __forceinline__ float shfl_up_f(float v, int d) { return __shfl_up(v, d, kWave); }
+__device__ __forceinline__ float shfl_f(float v, int src) { return __shfl(v, src, kWave); }
+
+// sum over aligned groups of `width` lanes (power of two); every lane gets the sum
+template <int width>
+__device__ __forceinline__ float group_sum(float v)
+{
+#pragma unroll
+    for (int m = width / 2; m >= 1; m >>= 1) v += shfl_xor_f(v, m);
+    return v;
+}
+
+__device__ __forceinline__ int wave_sum_i(int v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+// agent-scope relaxed 64-bit accesses that go past the per-XCD L2 (value+tag records)
+__device__ __forceinline__ void store_u64_agent(uint64_t *p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t load_u64_agent(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// order-preserving map float32 -> uint32 (larger float <=> larger key)
+__device__ __forceinline__ uint32_t float_to_key(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+}  // namespace rs

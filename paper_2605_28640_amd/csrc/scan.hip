@@ -1,0 +1,297 @@
+// Gated decay recurrence (Sec. 2.1, Eq. 1) as a single-pass chunked scan.
+//
+// s_t = g_t s_{t-1} + (1-g_t) x_t is a first-order linear recurrence: a run of tokens
+// acts on the incoming state as s -> A s + B, and two runs compose as
+// (A2, B2) o (A1, B1) = (A1 A2, A2 B1 + B2).  One workgroup owns one chunk of tokens of
+// one (batch, KV head) for all D channels:
+//   1. every lane loads NT consecutive tokens x 8 channels (16-byte loads) and keeps
+//      them in registers; it folds them into its (A, Bk, Bv);
+//   2. the row groups of a wave are scanned with wave shuffles, the waves of the
+//      workgroup through LDS;
+//   3. the chunk's incoming state comes from the previous chunk of the same head
+//      through a value+tag record in global memory (chunks are numbered by a ticket
+//      taken at start, so the predecessor is always already running); the chunk
+//      publishes its outgoing state before doing anything else;
+//   4. every lane replays its tokens from its incoming state out of registers and
+//      stores the rounded states into the cache.
+// Inputs are read once and outputs written once: 12 bytes per channel-token for a
+// bf16 cache.
+#include "common.h"
+
+namespace rs {
+
+template <typename ST, int D, int NT, int NW>
+__global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
+    const ST *__restrict__ k, const ST *__restrict__ v, const float *__restrict__ g,
+    float *__restrict__ state_k, float *__restrict__ state_v, ST *__restrict__ k_cache,
+    ST *__restrict__ v_cache, int BH, long T_new, long t0, long Tcap, int n_chunks,
+    uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit)
+{
+    constexpr int LPR = D / 8;       // lanes per row
+    constexpr int RPW = 64 / LPR;    // row groups per wave
+    constexpr int CHUNK = NW * RPW * NT;
+    using R = Row8<ST>;
+
+    __shared__ int s_ticket;
+    __shared__ float s_agg[NW][3][D];
+    __shared__ float s_carry[NW][2][D];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    const int rg = lane / LPR;
+    const int c0 = (lane % LPR) * 8;
+
+    int ticket = blockIdx.x;
+    if (n_chunks > 1) {
+        if (tid == 0) s_ticket = (int)atomicAdd(&ctrl[kCtrlTicket], 1u);
+        __syncthreads();
+        ticket = s_ticket;
+    }
+    const int j = ticket / BH;   // chunk index along T
+    const int bh = ticket % BH;  // consecutive tickets walk the heads first
+
+    const long tbase = (long)j * CHUNK + (long)(wave * RPW + rg) * NT;
+    const long in_row0 = (long)bh * T_new;
+
+    typename R::raw_t kr[NT], vr[NT];
+    float4 g0[NT], g1[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const long t = tbase + i;
+        if (t < T_new) {
+            const long off = (in_row0 + t) * D + c0;
+            kr[i] = R::load_raw(k + off);
+            vr[i] = R::load_raw(v + off);
+            g0[i] = *reinterpret_cast<const float4 *>(g + off);
+            g1[i] = *reinterpret_cast<const float4 *>(g + off + 4);
+        } else {  // past the end: the identity element (g = 1 keeps the state)
+            kr[i] = R::zero_raw();
+            vr[i] = R::zero_raw();
+            g0[i] = make_float4(1.f, 1.f, 1.f, 1.f);
+            g1[i] = g0[i];
+        }
+    }
+
+    // fold own tokens: state -> a * state + b
+    float a[8], bk[8], bv[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        a[c] = 1.f;
+        bk[c] = 0.f;
+        bv[c] = 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        float kx[8], vx[8];
+        R::unpack(kr[i], kx);
+        R::unpack(vr[i], vx);
+        const float gg[8] = {g0[i].x, g0[i].y, g0[i].z, g0[i].w, g1[i].x, g1[i].y, g1[i].z, g1[i].w};
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const float om = 1.f - gg[c];
+            a[c] *= gg[c];
+            bk[c] = fmaf(gg[c], bk[c], om * kx[c]);
+            bv[c] = fmaf(gg[c], bv[c], om * vx[c]);
+        }
+    }
+
+    // inclusive scan over the row groups of the wave
+#pragma unroll
+    for (int d = 1; d < RPW; d <<= 1) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const float pa = shfl_up_f(a[c], d * LPR);
+            const float pk = shfl_up_f(bk[c], d * LPR);
+            const float pv = shfl_up_f(bv[c], d * LPR);
+            if (rg >= d) {
+                bk[c] = fmaf(a[c], pk, bk[c]);
+                bv[c] = fmaf(a[c], pv, bv[c]);
+                a[c] *= pa;
+            }
+        }
+    }
+    if (rg == RPW - 1) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            s_agg[wave][0][c0 + c] = a[c];
+            s_agg[wave][1][c0 + c] = bk[c];
+            s_agg[wave][2][c0 + c] = bv[c];
+        }
+    }
+    // exclusive within the wave: what precedes this lane's tokens inside its wave
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        const float pa = shfl_up_f(a[c], LPR);
+        const float pk = shfl_up_f(bk[c], LPR);
+        const float pv = shfl_up_f(bv[c], LPR);
+        a[c] = (rg == 0) ? 1.f : pa;
+        bk[c] = (rg == 0) ? 0.f : pk;
+        bv[c] = (rg == 0) ? 0.f : pv;
+    }
+    __syncthreads();
+
+    if (tid < D) {
+        const int c = tid;
+        float A = 1.f, Bk = 0.f, Bv = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float aw = s_agg[w][0][c];
+            Bk = fmaf(aw, Bk, s_agg[w][1][c]);
+            Bv = fmaf(aw, Bv, s_agg[w][2][c]);
+            A *= aw;
+        }
+        float Sk, Sv;
+        if (j == 0) {
+            Sk = state_k[bh * D + c];
+            Sv = state_v[bh * D + c];
+        } else {
+            const uint64_t *p = rec + (((long)bh * n_chunks + (j - 1)) * 2) * D + c;
+            uint64_t w0 = 0, w1 = 0;
+            int spins = 0;
+            bool ok = false;
+            while (true) {
+                w0 = load_u64_agent(p);
+                w1 = load_u64_agent(p + D);
+                ok = ((uint32_t)(w0 >> 32) == tag) && ((uint32_t)(w1 >> 32) == tag);
+                if (ok || ++spins > spin_limit) break;
+                __builtin_amdgcn_s_sleep(2);
+            }
+            if (!ok) atomicExch(&ctrl[kCtrlAsyncErr], 1u);  // give up; outputs undefined
+            Sk = __uint_as_float((uint32_t)w0);
+            Sv = __uint_as_float((uint32_t)w1);
+        }
+        const float Ok = fmaf(A, Sk, Bk);
+        const float Ov = fmaf(A, Sv, Bv);
+        if (j == n_chunks - 1) {
+            state_k[bh * D + c] = Ok;
+            state_v[bh * D + c] = Ov;
+        } else {
+            uint64_t *p = rec + (((long)bh * n_chunks + j) * 2) * D + c;
+            store_u64_agent(p, ((uint64_t)tag << 32) | __float_as_uint(Ok));
+            store_u64_agent(p + D, ((uint64_t)tag << 32) | __float_as_uint(Ov));
+        }
+        float ck = Sk, cv = Sv;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            s_carry[w][0][c] = ck;
+            s_carry[w][1][c] = cv;
+            const float aw = s_agg[w][0][c];
+            ck = fmaf(aw, ck, s_agg[w][1][c]);
+            cv = fmaf(aw, cv, s_agg[w][2][c]);
+        }
+    }
+    __syncthreads();
+
+    // replay from the incoming state
+    float sk[8], sv[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        sk[c] = fmaf(a[c], s_carry[wave][0][c0 + c], bk[c]);
+        sv[c] = fmaf(a[c], s_carry[wave][1][c0 + c], bv[c]);
+    }
+    const long out_row0 = (long)bh * Tcap + t0;
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const long t = tbase + i;
+        if (t < T_new) {
+            float kx[8], vx[8];
+            R::unpack(kr[i], kx);
+            R::unpack(vr[i], vx);
+            const float gg[8] = {g0[i].x, g0[i].y, g0[i].z, g0[i].w, g1[i].x, g1[i].y, g1[i].z, g1[i].w};
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const float om = 1.f - gg[c];
+                sk[c] = fmaf(gg[c], sk[c], om * kx[c]);
+                sv[c] = fmaf(gg[c], sv[c], om * vx[c]);
+            }
+            const long off = (out_row0 + t) * D + c0;
+            R::store(k_cache + off, sk);
+            R::store(v_cache + off, sv);
+        }
+    }
+
+    if (n_chunks > 1 && tid == 0) {
+        const uint32_t total = (uint32_t)BH * (uint32_t)n_chunks;
+        if (atomicAdd(&ctrl[kCtrlDone], 1u) == total - 1u) {  // last one out resets the counters
+            atomicExch(&ctrl[kCtrlTicket], 0u);
+            atomicExch(&ctrl[kCtrlDone], 0u);
+        }
+    }
+}
+
+// few tokens (the decode-time append): one thread per (batch, head, channel)
+template <typename ST>
+__global__ __launch_bounds__(256) void rat_step_kernel(
+    const ST *__restrict__ k, const ST *__restrict__ v, const float *__restrict__ g,
+    float *__restrict__ state_k, float *__restrict__ state_v, ST *__restrict__ k_cache,
+    ST *__restrict__ v_cache, int BH, int D, long T_new, long t0, long Tcap)
+{
+    const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (long)BH * D) return;
+    const long bh = e / D;
+    const int c = (int)(e % D);
+    float sk = state_k[e], sv = state_v[e];
+    for (long t = 0; t < T_new; ++t) {
+        const long off = (bh * T_new + t) * D + c;
+        const float gg = g[off];
+        const float om = 1.f - gg;
+        sk = fmaf(gg, sk, om * to_f32(k[off]));
+        sv = fmaf(gg, sv, om * to_f32(v[off]));
+        const long o = (bh * Tcap + t0 + t) * D + c;
+        from_f32(k_cache[o], sk);
+        from_f32(v_cache[o], sv);
+    }
+    state_k[e] = sk;
+    state_v[e] = sv;
+}
+
+template <typename ST, int D>
+static int launch_scan(const void *k, const void *v, const float *g, float *state_k,
+                       float *state_v, void *k_cache, void *v_cache, int BH, long T_new, long t0,
+                       long Tcap, uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit,
+                       hipStream_t stream)
+{
+    constexpr int NT = sizeof(ST) == 2 ? 4 : 2;
+    constexpr int NW = 8;
+    constexpr int CHUNK = NW * (64 / (D / 8)) * NT;
+    const int n_chunks = (int)((T_new + CHUNK - 1) / CHUNK);
+    rat_scan_chunk_kernel<ST, D, NT, NW><<<dim3((unsigned)(BH * n_chunks)), dim3(NW * 64), 0, stream>>>(
+        (const ST *)k, (const ST *)v, g, state_k, state_v, (ST *)k_cache, (ST *)v_cache, BH, T_new,
+        t0, Tcap, n_chunks, ctrl, rec, tag, spin_limit);
+    return 0;
+}
+
+int scan_chunk_tokens(int dtype, int D)
+{
+    const int NT = dtype == RS_BF16 ? 4 : 2;
+    return 8 * (64 / (D / 8)) * NT;
+}
+
+// host entry used by the C ABI (arguments already validated)
+void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
+                   float *state_v, void *k_cache, void *v_cache, int BH, long T_new, long t0,
+                   long Tcap, uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit,
+                   hipStream_t stream)
+{
+    if (T_new <= 8) {
+        const long n = (long)BH * D;
+        const unsigned blocks = (unsigned)((n + 255) / 256);
+        if (dtype == RS_BF16)
+            rat_step_kernel<bf16><<<blocks, 256, 0, stream>>>((const bf16 *)k, (const bf16 *)v, g, state_k, state_v,
+                                                             (bf16 *)k_cache, (bf16 *)v_cache, BH, D, T_new, t0, Tcap);
+        else
+            rat_step_kernel<float><<<blocks, 256, 0, stream>>>((const float *)k, (const float *)v, g, state_k, state_v,
+                                                              (float *)k_cache, (float *)v_cache, BH, D, T_new, t0, Tcap);
+        return;
+    }
+    if (dtype == RS_BF16) {
+        if (D == 128) launch_scan<bf16, 128>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream);
+        else launch_scan<bf16, 64>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream);
+    } else {
+        if (D == 128) launch_scan<float, 128>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream);
+        else launch_scan<float, 64>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream);
+    }
+}
+
+}  // namespace rs

@@ -1,0 +1,177 @@
+"""GPU parity of the Quest decode path (page metadata, page selection, attention over the
+selected pages, fused select+attend, dense) against the float64 oracle, through the C ABI.
+Later stages are fed the oracle's rounded cache so that both sides start from the same
+stored bits."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import say, tdtype, to_dev, to_np
+from helpers import attn_close, topk_set_ok
+from paper_2605_28640_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _cache_from_oracle(w, T, Tcap):
+    """Oracle scan of the workload's prefill, rounded to the storage dtype."""
+    w = w.scaled(T=T)
+    k, v, g = synth.prefill(w)
+    ko, vo, _, _ = oracle.rat_scan(k, v, g)
+    kc = np.zeros((w.B, w.Hkv, Tcap, w.D), dtype=np.float32)
+    vc = np.zeros_like(kc)
+    if w.dtype == "bf16":
+        kc[:, :, :T], vc[:, :, :T] = oracle.round_to_bf16(ko), oracle.round_to_bf16(vo)
+    else:
+        kc[:, :, :T], vc[:, :, :T] = ko.astype(np.float32), vo.astype(np.float32)
+    return w, kc, vc
+
+
+def _forced(Np, n_first, n_local):
+    f = np.zeros(Np, dtype=bool)
+    f[:n_first] = True
+    if n_local:
+        f[Np - n_local:] = True
+    return f
+
+
+CASES = [
+    # workload, T_valid, Tcap, P, K, n_first, n_local
+    (synth.C1, 2048, 2048 + 16, 16, 16, 1, 1),
+    (synth.C1, 2041, 2048 + 16, 16, 16, 1, 1),                       # ragged last page
+    (synth.C2.scaled(Hq=8, Hkv=2), 4096 + 5, 4096 + 64, 16, 32, 1, 1),  # GQA, bf16, D=128
+    (synth.C3.scaled(B=2, Hq=2, Hkv=2), 8192, 8192, 64, 8, 1, 2),     # 64-token pages
+    (synth.C1.scaled(dtype="bf16"), 1000, 1024, 32, 5, 0, 0),          # D=64 bf16, nothing forced
+]
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_meta_select_attend(rs, case):
+    w, T, Tcap, P, K, n_first, n_local = CASES[case]
+    say("quest case", case, w.name, T, Tcap, P, K, n_first, n_local)
+    w, kc, vc = _cache_from_oracle(w, T, Tcap)
+    _, _, _, q = synth.decode_step(w, 0)
+    Np = -(-T // P)
+    scale = 1.0 / np.sqrt(w.D)
+    dt = tdtype(w.dtype)
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tcap, P, dt)
+    tkc, tvc, tq = to_dev(kc, w.dtype), to_dev(vc, w.dtype), to_dev(q, w.dtype)
+    meta = torch.zeros(w.B, w.Hkv, Tcap // P, 2, w.D, dtype=dt, device="cuda")
+    ws = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, T, Np))
+
+    # page metadata: bulk, bit-exact values
+    rs.quest_page_meta(s, tkc, meta, 0, T)
+    ometa = oracle.quest_page_meta(kc, P, T)
+    np.testing.assert_array_equal(to_np(meta), ometa)
+
+    # selection
+    idx = torch.full((w.B, w.Hq, K), -7, dtype=torch.int32, device="cuda")
+    scores = torch.zeros(w.B, w.Hq, Np, device="cuda")
+    rs.quest_select_decode(s, tq, meta, T, K, n_first, n_local, idx, scores, ws)
+    osc = oracle.quest_scores(q, ometa, Np)
+    np.testing.assert_allclose(to_np(scores), osc, rtol=2e-6, atol=1e-5)
+    oidx = oracle.quest_select(osc, K, n_first, n_local)
+    gidx = to_np(idx)
+    forced = _forced(Np, n_first, n_local)
+    same = 0
+    for b in range(w.B):
+        for h in range(w.Hq):
+            ok, why = topk_set_ok(osc[b, h], forced, K, gidx[b, h])
+            assert ok, (b, h, why)
+            same += np.array_equal(gidx[b, h], oidx[b, h])
+    say("  identical index lists:", same, "of", w.B * w.Hq)
+
+    # attention over the oracle's list
+    out = torch.zeros(w.B, w.Hq, w.D, dtype=dt, device="cuda")
+    lse = torch.zeros(w.B, w.Hq, device="cuda")
+    rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, to_dev(oidx), K, None, 0, 0, out, lse, None, ws)
+    oout, olse = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, oidx)
+    ok, worst = attn_close(to_np(out), oout, 2e-2 if w.dtype == "bf16" else 1e-4)
+    assert ok, worst
+    np.testing.assert_allclose(to_np(lse), olse, rtol=1e-4, atol=1e-4)
+
+    # fused select-then-attend, emitting its selection
+    out2 = torch.zeros_like(out)
+    idx2 = torch.full_like(idx, -7)
+    rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out2, None, idx2, ws)
+    np.testing.assert_array_equal(to_np(idx2), gidx)
+    oout2, _ = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, gidx)
+    assert attn_close(to_np(out2), oout2, 2e-2 if w.dtype == "bf16" else 1e-4)[0]
+    out3 = torch.zeros_like(out)
+    rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out3, None, None, ws)
+    assert torch.equal(out3, out2)  # same result when the selection is not emitted
+
+    # dense path, and full budget = dense
+    outd = torch.zeros_like(out)
+    rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, 0, None, 0, 0, outd, lse, None, ws)
+    od, odl = oracle.sparse_attn_decode(q, kc, vc, P, T, scale)
+    assert attn_close(to_np(outd), od, 2e-2 if w.dtype == "bf16" else 1e-4)[0]
+    np.testing.assert_allclose(to_np(lse), odl, rtol=1e-4, atol=1e-4)
+    outf = torch.zeros_like(out)
+    rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, Np, meta, n_first, n_local, outf, None, None, ws)
+    assert attn_close(to_np(outf), od, 2e-2 if w.dtype == "bf16" else 1e-4)[0]
+    torch.cuda.synchronize()
+    ws.async_status()
+
+
+def test_incremental_meta_equals_bulk(rs):
+    w, kc, vc = _cache_from_oracle(synth.C1.scaled(dtype="bf16"), 200, 256)
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, 256, 16, torch.bfloat16)
+    tkc = to_dev(kc, "bf16")
+    inc = torch.zeros(w.B, w.Hkv, 16, 2, w.D, dtype=torch.bfloat16, device="cuda")
+    rs.quest_page_meta(s, tkc, inc, 0, 150)
+    for t in range(150, 200):
+        rs.quest_page_meta(s, tkc, inc, t, t + 1)
+    bulk = torch.zeros_like(inc)
+    rs.quest_page_meta(s, tkc, bulk, 0, 200)
+    assert torch.equal(inc, bulk)
+    np.testing.assert_array_equal(to_np(bulk), oracle.quest_page_meta(kc, 16, 200))
+
+
+def test_exact_ties_take_the_lowest_index(rs):
+    B, H, D, P, Np = 1, 2, 128, 16, 300
+    r = np.random.default_rng(3)
+    base = synth.to_bf16_grid(r.standard_normal((B, H, 7, P, D)).astype(np.float32))
+    pick = r.integers(0, 7, Np)
+    kc = base[:, :, pick].reshape(B, H, Np * P, D)  # only 7 distinct pages: scores tie exactly
+    q = synth.to_bf16_grid(r.standard_normal((B, H, D)).astype(np.float32))
+    s = rs.make_shape(B, H, H, D, Np * P, P, torch.bfloat16)
+    meta = torch.zeros(B, H, Np, 2, D, dtype=torch.bfloat16, device="cuda")
+    rs.quest_page_meta(s, to_dev(kc, "bf16"), meta, 0, Np * P)
+    ws = rs.Workspace(rs.quest_select_decode_workspace_bytes(s, Np * P))
+    osc = oracle.quest_scores(q, oracle.quest_page_meta(kc, P, Np * P), Np)
+    for K in (1, 10, 64, 299, 300):
+        idx = torch.zeros(B, H, K, dtype=torch.int32, device="cuda")
+        rs.quest_select_decode(s, to_dev(q, "bf16"), meta, Np * P, K, 0, 0, idx, None, ws)
+        np.testing.assert_array_equal(to_np(idx), oracle.quest_select(osc, K, 0, 0))
+
+
+def test_listed_pages_with_skips_and_any_order(rs):
+    w, kc, vc = _cache_from_oracle(synth.C1.scaled(dtype="bf16"), 512, 512)
+    _, _, _, q = synth.decode_step(w, 1)
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, 512, 16, torch.bfloat16)
+    idx = np.array([[[31, 2, -1, 7, 19, 0], [5, -1, -1, 30, 1, 8]]], dtype=np.int32)
+    ws = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, 505, 6))
+    out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.bfloat16, device="cuda")
+    rs.sparse_attn_decode(s, to_dev(q, "bf16"), to_dev(kc, "bf16"), to_dev(vc, "bf16"), 505, 0.125,
+                          to_dev(idx), 6, None, 0, 0, out, None, None, ws)
+    want, _ = oracle.sparse_attn_decode(q, kc, vc, 16, 505, 0.125, idx)
+    assert attn_close(to_np(out), want)[0]
+
+
+def test_argument_errors_are_reported(rs):
+    s = rs.make_shape(1, 2, 2, 128, 256, 16, torch.bfloat16)
+    t = torch.zeros(1 << 16, dtype=torch.bfloat16, device="cuda")
+    i = torch.zeros(64, dtype=torch.int32, device="cuda")
+    ws = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, 256, 16))
+    with pytest.raises(rs.RatsparseError, match="invalid argument"):
+        rs.quest_select_decode(s, t, t, 256, 17, 1, 1, i, None, ws)  # K > Np
+    with pytest.raises(rs.RatsparseError, match="invalid argument"):
+        rs.quest_select_decode(s, t, t, 256, 2, 2, 2, i, None, ws)  # more forced pages than K
+    with pytest.raises(rs.RatsparseError, match="invalid argument"):
+        rs.sparse_attn_decode(s, t, t, t, 257, 1.0, None, 0, None, 0, 0, t, None, None, ws)  # T > Tcap
+    small = rs.Workspace(0)
+    big = rs.make_shape(4, 32, 32, 128, 65536, 16, torch.bfloat16)
+    with pytest.raises(rs.RatsparseError, match="workspace too small"):
+        rs.sparse_attn_decode(big, t, t, t, 65536, 1.0, None, 0, None, 0, 0, t, None, None, small)
