@@ -4,6 +4,7 @@
 #include <cstdlib>
 
 #include "common.h"
+#include "decode_fused.h"
 
 namespace rs {
 // scan.hip
@@ -14,13 +15,14 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
 // quest.hip
 void page_meta_dispatch(int dtype, int D, const void *k_cache, void *meta, int BH, long Tcap, int P,
                         int p_begin, int n_pages, long t_end, hipStream_t stream);
-void score_select_dispatch(int dtype, int D, const void *q, const void *meta, float *scores, int32_t *idx_out,
-                           int B, int Hq, int Hkv, long Np_cap, int Np, int K, int n_first, int n_local,
-                           int splits, uint32_t *unit_ctr, hipStream_t stream);
+int score_select_dispatch(int dtype, int D, const void *q, const void *meta, uint64_t *scores, float *scores_out,
+                          int32_t *idx_out, int B, int Hq, int Hkv, long Np_cap, int Np, int K, int n_first,
+                          int n_local, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit,
+                          hipStream_t stream);
 void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache, const void *v_cache,
-                            const int32_t *idx, void *out, float *lse_out, float *partial, int B, int Hq,
+                            const int32_t *idx, void *out, float *lse_out, uint64_t *partial, int B, int Hq,
                             int Hkv, long Tcap, int P, long T_valid, int K, float scale, int splits,
-                            uint32_t *unit_ctr, hipStream_t stream);
+                            uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit, hipStream_t stream);
 // moba.hip / prefill.hip / snapkv.hip
 size_t moba_select_ws_bytes(const rs_shape *s, long T, int block);
 int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, long T, int block, int K,
@@ -89,15 +91,31 @@ static int pick_splits(long units, long items, long min_items_per_split, long ta
     return (int)s;
 }
 
+static int num_cus()
+{
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
+}
+
 static int env_int(const char *name, int dflt)
 {
     const char *e = std::getenv(name);
     return e ? std::atoi(e) : dflt;
 }
 
+constexpr int kMaxAttSplits = 64;
+
 struct DecodeLayout {
     int Np, splits_score, splits_att_max;
-    size_t off_scores, off_idx, off_partial, total;
+    size_t off_scores, off_idx, off_idx_tagged, off_partial, off_trace, total;
 };
 
 static DecodeLayout decode_layout(const rs_shape *s, long T_valid, int K)
@@ -105,16 +123,21 @@ static DecodeLayout decode_layout(const rs_shape *s, long T_valid, int K)
     DecodeLayout L;
     const long units = (long)s->B * s->Hq;
     L.Np = (int)((T_valid + s->P - 1) / s->P);
-    L.splits_score = pick_splits(units, L.Np, 64, env_int("RATSPARSE_SCORE_WGS", 2048));
+    L.splits_score = pick_splits(units, L.Np, 64, env_int("RATSPARSE_SCORE_WGS", 512));
     const long dense_tiles = (T_valid + 15) / 16;
-    L.splits_att_max = pick_splits(units, dense_tiles, 8, env_int("RATSPARSE_ATTEND_WGS", 2048));
+    L.splits_att_max = pick_splits(units, dense_tiles, 8, env_int("RATSPARSE_ATTEND_WGS", 512));
+    if (L.splits_att_max < kMaxAttSplits) L.splits_att_max = kMaxAttSplits;
     size_t off = RS_WS_CTRL_BYTES;
     L.off_scores = off;
-    off += align256((size_t)units * L.Np * 4);
+    off += align256((size_t)units * L.Np * 8);
     L.off_idx = off;
     off += align256((size_t)units * (K > 0 ? K : 1) * 4);
+    L.off_idx_tagged = off;
+    off += align256((size_t)units * (K > 0 ? K : 1) * 8);
     L.off_partial = off;
-    off += align256((size_t)units * L.splits_att_max * (s->D + 2) * 4);
+    off += align256((size_t)units * L.splits_att_max * (s->D + 2) * 8);
+    L.off_trace = off;
+    if (env_int("RATSPARSE_TRACE", 0)) off += (size_t)4096 * 64 * 8;
     L.total = off;
     return L;
 }
@@ -245,9 +268,11 @@ int32_t quest_select_decode(const rs_shape *s, const void *q, const void *meta, 
     const DecodeLayout L = decode_layout(s, T_valid, 1);
     if (!ws || !aligned16(ws) || ws_bytes < L.total) return RS_WORKSPACE_TOO_SMALL;
     char *w = (char *)ws;
-    float *scores = scores_out ? scores_out : (float *)(w + L.off_scores);
-    score_select_dispatch(s->dtype, s->D, q, meta, scores, idx_out, s->B, s->Hq, s->Hkv, s->Tcap / s->P, L.Np, K,
-                          n_first, n_local, L.splits_score, (uint32_t *)w + kCtrlUnit0, (hipStream_t)stream);
+    st = score_select_dispatch(s->dtype, s->D, q, meta, (uint64_t *)(w + L.off_scores), scores_out, idx_out, s->B,
+                               s->Hq, s->Hkv, s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score,
+                               (uint32_t *)w + kCtrlUnit0, (uint32_t *)w + kCtrlAsyncErr, next_tag(),
+                               g_spin_limit.load(), (hipStream_t)stream);
+    if (st != RS_OK) return st;
     return launch_status();
 }
 
@@ -283,19 +308,56 @@ int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache
     uint32_t *ctr_att = ctr_score + kMaxUnits;
     const long units = (long)s->B * s->Hq;
     const int32_t *use_idx = idx;
+    const uint32_t tag = next_tag();
+    if (fused && !env_int("RATSPARSE_FUSED_TWO_LAUNCH", 0)) {
+        // one persistent launch: score -> select -> attend, handed over through tagged words
+        FusedParams prm;
+        prm.q = q; prm.meta = meta; prm.k_cache = k_cache; prm.v_cache = v_cache;
+        prm.out = out; prm.lse_out = lse_out; prm.idx_out = idx_out;
+        prm.scores = (uint64_t *)(w + L.off_scores);
+        prm.idx_tagged = (uint64_t *)(w + L.off_idx_tagged);
+        prm.partial = (uint64_t *)(w + L.off_partial);
+        prm.ctr_score = ctr_score; prm.ctr_att = ctr_att;
+        prm.ticket = (uint32_t *)w + kCtrlTicket; prm.done = (uint32_t *)w + kCtrlDone;
+        prm.err = (uint32_t *)w + kCtrlAsyncErr;
+        prm.Hq = s->Hq; prm.Hkv = s->Hkv; prm.units = (int)units;
+        prm.Tcap = s->Tcap; prm.Np_cap = s->Tcap / s->P; prm.T_valid = T_valid;
+        prm.P = s->P; prm.Np = L.Np; prm.K = K; prm.n_first = n_first; prm.n_local = n_local;
+        int ss = env_int("RATSPARSE_FUSED_SSCORE", 0), sa = env_int("RATSPARSE_FUSED_SATT", 0);
+        if (ss <= 0) ss = (L.Np + 511) / 512;                      // ~512 pages (256 KiB of bf16 metadata) per item
+        if (sa <= 0) sa = (int)(((long)K * (s->P / 16) + 31) / 32);  // ~32 tiles (256 KiB of bf16 K+V) per item
+        if (ss > L.Np) ss = L.Np;
+        if (sa > kMaxAttSplits) sa = kMaxAttSplits;
+        if (sa > K) sa = K;
+        prm.S_score = ss < 1 ? 1 : ss; prm.S_att = sa < 1 ? 1 : sa;
+        prm.reverse = env_int("RATSPARSE_FUSED_PINGPONG", 1) ? (int)(T_valid & 1) : 0;
+        prm.scale = scale; prm.tag = tag; prm.spin_limit = g_spin_limit.load();
+        prm.trace = env_int("RATSPARSE_TRACE", 0) ? (uint64_t *)(w + L.off_trace) : nullptr;
+        long items = units * (prm.S_score + prm.S_att);
+        // two 512-thread workgroups per CU: one streams while the other selects or merges
+        const int threads = env_int("RATSPARSE_FUSED_THREADS", 512) == 256 ? 256 : 512;
+        long grid = env_int("RATSPARSE_FUSED_GRID", 2 * num_cus());
+        if (grid > items) grid = items;
+        st = decode_fused_dispatch(s->dtype, s->D, prm, (int)grid, threads, (hipStream_t)stream);
+        if (st != RS_OK) return st;
+        return launch_status();
+    }
     if (fused) {
         int32_t *sel = idx_out ? idx_out : (int32_t *)(w + L.off_idx);
-        score_select_dispatch(s->dtype, s->D, q, meta, (float *)(w + L.off_scores), sel, s->B, s->Hq, s->Hkv,
-                              s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score, ctr_score,
-                              (hipStream_t)stream);
+        st = score_select_dispatch(s->dtype, s->D, q, meta, (uint64_t *)(w + L.off_scores), nullptr, sel, s->B,
+                                   s->Hq, s->Hkv, s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score,
+                                   ctr_score, (uint32_t *)w + kCtrlAsyncErr, tag, g_spin_limit.load(),
+                                   (hipStream_t)stream);
+        if (st != RS_OK) return st;
         if (launch_status() != RS_OK) return RS_LAUNCH_FAILED;
         use_idx = sel;
     }
     const long tiles = use_idx ? (long)K * (s->P / 16) : (T_valid + 15) / 16;
-    int splits = pick_splits(units, tiles, 8, env_int("RATSPARSE_ATTEND_WGS", 2048));
+    int splits = pick_splits(units, tiles, 8, env_int("RATSPARSE_ATTEND_WGS", 512));
     if (splits > L.splits_att_max) splits = L.splits_att_max;
-    decode_attend_dispatch(s->dtype, s->D, q, k_cache, v_cache, use_idx, out, lse_out, (float *)(w + L.off_partial),
-                           s->B, s->Hq, s->Hkv, s->Tcap, s->P, T_valid, K, scale, splits, ctr_att,
+    decode_attend_dispatch(s->dtype, s->D, q, k_cache, v_cache, use_idx, out, lse_out,
+                           (uint64_t *)(w + L.off_partial), s->B, s->Hq, s->Hkv, s->Tcap, s->P, T_valid, K, scale,
+                           splits, ctr_att, (uint32_t *)w + kCtrlAsyncErr, tag, g_spin_limit.load(),
                            (hipStream_t)stream);
     return launch_status();
 }

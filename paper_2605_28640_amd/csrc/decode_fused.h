@@ -1,0 +1,31 @@
+// Arguments of the persistent fused decode kernel (see decode_fused.hip).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rs {
+
+struct FusedParams {
+    const void *q, *meta, *k_cache, *v_cache;
+    void *out;
+    float *lse_out;
+    int32_t *idx_out;       // optional plain copy of the selection
+    uint64_t *scores;       // [units][Np] tagged
+    uint64_t *idx_tagged;   // [units][K] tagged
+    uint64_t *partial;      // [units][S_att][D + 2] tagged
+    uint32_t *ctr_score, *ctr_att, *ticket, *done, *err;
+    int Hq, Hkv, units;
+    long Tcap, Np_cap, T_valid;
+    int P, Np, K, n_first, n_local;
+    int S_score, S_att;
+    int reverse;            // walk the units from the last to the first
+    float scale;
+    uint32_t tag;
+    int spin_limit;
+    uint64_t *trace;  // optional timeline for tuning: [workgroup][64] of (time << 20 | item << 4 | phase)
+};
+
+int decode_fused_dispatch(int dtype, int D, const FusedParams &prm, int grid, int threads, hipStream_t stream);
+
+}  // namespace rs

@@ -1,0 +1,328 @@
+// Fused Quest decode (Sec. 2.2, Eq. 3-4; App. A.1): page scores, top-K page selection and
+// attention over the selected pages in ONE persistent launch, so unselected KV is never
+// read and no kernel boundary or cache flush sits between selection and attention.
+//
+// The grid is a fixed number of workgroups that pull work items by ticket:
+//   tickets [0, n_score)         score item  = (unit, slice of its pages): stream the page
+//                                min/max rows, publish one score per page; the unit's last
+//                                slice then gathers the unit's scores, runs the radix top-K
+//                                and publishes the ascending page list;
+//   tickets [n_score, n_total)   attend item = (unit, slice of its K pages): wait for the
+//                                unit's page list, stream the listed K/V pages with an
+//                                online softmax, publish a partial (m, l, o); the unit's
+//                                last slice folds in the other partials and writes y.
+// unit = (batch, query head).  Everything another workgroup must read in the same launch
+// travels as {tag : value} words (see select.h), so waiting is a bounded poll on data that
+// an already-running workgroup is producing: whoever waits holds a larger ticket than the
+// item it waits for, tickets are handed out in increasing order to running workgroups,
+// and the item with the smallest outstanding ticket never waits.
+#include "common.h"
+#include "select.h"
+#include "decode_fused.h"
+
+namespace rs {
+
+template <typename ST, int D, int kFusedThreads>
+__global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void decode_fused_kernel(const FusedParams P_)
+{
+    constexpr int kFusedWaves = kFusedThreads / 64;
+    constexpr int LPR = D / 8;
+    constexpr int RPW = 64 / LPR;
+    using R = Row8<ST>;
+    const FusedParams &a = P_;
+
+    __shared__ SelectShared<kFusedThreads> sh;
+    __shared__ float s_m[kFusedWaves], s_l[kFusedWaves];
+    __shared__ float s_o[kFusedWaves][D];
+    __shared__ int s_next;
+    extern __shared__ uint32_t s_keys[];  // Np keys for the selection
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int rg = lane / LPR;
+    const int cl = lane % LPR;
+    const int c0 = cl * 8;
+    const int n_score = a.units * a.S_score;
+    const int n_total = n_score + a.units * a.S_att;
+    const int G = a.Hq / a.Hkv;
+
+    int n_ev = 0;
+    auto mark = [&](int item_, int phase) {
+        if (a.trace && tid == 0 && n_ev < 64)
+            a.trace[(long)blockIdx.x * 64 + n_ev++] = (wall_clock64() << 24) | ((uint64_t)(item_ & 0xfffff) << 4) | (uint64_t)phase;
+    };
+    if (tid == 0) s_next = (int)atomicAdd(a.ticket, 1u);
+    __syncthreads();
+    int item = s_next;
+    while (item < n_total) {
+        __syncthreads();  // s_next has been read by everyone; LDS of the previous item is free
+        // The next ticket is taken late: during the last streaming step of an item that waits
+        // for nobody, after the waiting for one that does.  A ticket held but not yet started
+        // would make its waiters wait for the holder's whole current item.
+        bool fetched = false;
+        auto fetch_next = [&]() {
+            if (tid == 0 && !fetched) {
+                s_next = (int)atomicAdd(a.ticket, 1u);
+                fetched = true;
+            }
+        };
+        mark(item, 0);
+
+        if (item < n_score) {
+            // ------------------------------ score item ------------------------------
+            int unit = item / a.S_score;
+            const int slice = item % a.S_score;
+            if (a.reverse) unit = a.units - 1 - unit;
+            const int b = unit / a.Hq, h = unit % a.Hq, kvh = h / G;
+            const ST *mbase = (const ST *)a.meta + ((long)(b * a.Hkv + kvh) * a.Np_cap) * 2 * D;
+            uint64_t *srow = a.scores + (long)unit * a.Np;
+            float qv[8];
+            R::load((const ST *)a.q + (long)unit * D + c0, qv);
+
+            constexpr int UNR = 4;
+            constexpr int PPI = UNR * RPW * kFusedWaves;  // pages per workgroup step
+            const int per = (a.Np + a.S_score - 1) / a.S_score;
+            const int pb = slice * per;
+            const int pe = (pb + per < a.Np) ? pb + per : a.Np;
+            const bool sel_here = (slice == a.S_score - 1);
+            for (int base = pb + wave * (UNR * RPW) + rg; base < pe; base += PPI) {
+                if (!sel_here && base + PPI >= pe) fetch_next();
+                typename R::raw_t mn[UNR], mx[UNR];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    const int p = base + u * RPW;
+                    if (p < pe) {
+                        mn[u] = R::load_raw(mbase + ((long)p * 2) * D + c0);
+                        mx[u] = R::load_raw(mbase + ((long)p * 2 + 1) * D + c0);
+                    } else {
+                        mn[u] = R::zero_raw();
+                        mx[u] = R::zero_raw();
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    const int p = base + u * RPW;
+                    float lo[8], hi[8];
+                    R::unpack(mn[u], lo);
+                    R::unpack(mx[u], hi);
+                    float s = 0.f;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) s += fmaxf(qv[c] * lo[c], qv[c] * hi[c]);
+                    s = group_sum<LPR>(s);
+                    if (p < pe && cl == 0) publish_f32(&srow[p], s, a.tag);
+                }
+            }
+            mark(item, 1);
+            // the unit's last slice carries the largest ticket: every other slice is already
+            // running or done, so it can wait for their scores and run the selection
+            if (sel_here) {
+                gather_page_keys<kFusedThreads>(srow, a.Np, a.n_first, a.n_local, a.tag, a.spin_limit, a.err, nullptr,
+                                                s_keys);
+                uint64_t *dst = a.idx_tagged + (long)unit * a.K;
+                int32_t *plain = a.idx_out ? a.idx_out + (long)unit * a.K : nullptr;
+                const uint32_t tag = a.tag;
+                select_topk_lds<kFusedThreads>(s_keys, a.Np, a.K, sh, [dst, plain, tag](int pos, int p) {
+                    store_u64_agent(&dst[pos], ((uint64_t)tag << 32) | (uint32_t)p);
+                    if (plain) plain[pos] = p;
+                });
+                mark(item, 3);
+            }
+        } else {
+            // ------------------------------ attend item -----------------------------
+            const int it = item - n_score;
+            int unit = it / a.S_att;
+            const int slice = it % a.S_att;
+            if (a.reverse) unit = a.units - 1 - unit;
+            const int b = unit / a.Hq, h = unit % a.Hq, kvh = h / G;
+            const ST *kb = (const ST *)a.k_cache + (long)(b * a.Hkv + kvh) * a.Tcap * D;
+            const ST *vb = (const ST *)a.v_cache + (long)(b * a.Hkv + kvh) * a.Tcap * D;
+            const uint64_t *sel = a.idx_tagged + (long)unit * a.K;
+
+            constexpr int TR = 16;
+            constexpr int RPL = TR / RPW;
+            constexpr int TPI = 2;
+            float qv[8];
+            R::load((const ST *)a.q + (long)unit * D + c0, qv);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) qv[c] *= a.scale;
+
+            const int tiles_per_page = a.P / TR;
+            const int n_tiles = a.K * tiles_per_page;
+            const int per = (n_tiles + a.S_att - 1) / a.S_att;
+            const int tb = slice * per;
+            const int te = (tb + per < n_tiles) ? tb + per : n_tiles;
+
+            float m = -INFINITY, l = 0.f;
+            float o[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) o[c] = 0.f;
+
+            const bool finish = (slice == a.S_att - 1);  // largest ticket of the unit: folds the others
+            for (int t = tb + wave * TPI; t < te; t += kFusedWaves * TPI) {
+                if (!finish && t + kFusedWaves * TPI >= te) fetch_next();
+                long row0[TPI];
+                typename R::raw_t kr[TPI][RPL], vr[TPI][RPL];
+                uint64_t wsel[TPI];
+#pragma unroll
+                for (int u = 0; u < TPI; ++u)
+                    wsel[u] = (t + u < te) ? load_u64_agent(&sel[(t + u) / tiles_per_page]) : 0ull;
+#pragma unroll
+                for (int u = 0; u < TPI; ++u) {
+                    row0[u] = a.T_valid;
+                    if (t + u < te) {
+                        uint32_t page = (uint32_t)wsel[u];
+                        if ((uint32_t)(wsel[u] >> 32) != a.tag) {  // the selection is still being written
+                            int spins = 0;
+                            uint64_t w2 = wsel[u];
+                            while ((uint32_t)(w2 >> 32) != a.tag) {
+                                if (++spins > a.spin_limit) {
+                                    atomicExch(a.err, 1u);
+                                    break;
+                                }
+                                __builtin_amdgcn_s_sleep(2);
+                                w2 = load_u64_agent(&sel[(t + u) / tiles_per_page]);
+                            }
+                            page = (uint32_t)w2;
+                            if ((uint32_t)(w2 >> 32) != a.tag) page = 0xffffffffu;  // gave up: skip
+                        }
+                        if (page < (uint32_t)a.Np) row0[u] = (long)page * a.P + ((t + u) % tiles_per_page) * TR;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < TPI; ++u) {
+#pragma unroll
+                    for (int i = 0; i < RPL; ++i) {
+                        const long row = row0[u] + i * RPW + rg;
+                        if (row < a.T_valid) {
+                            kr[u][i] = R::load_raw(kb + row * D + c0);
+                            vr[u][i] = R::load_raw(vb + row * D + c0);
+                        } else {
+                            kr[u][i] = R::zero_raw();
+                            vr[u][i] = R::zero_raw();
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < TPI; ++u) {
+                    float s[RPL];
+                    float mt = m;
+#pragma unroll
+                    for (int i = 0; i < RPL; ++i) {
+                        float x[8];
+                        R::unpack(kr[u][i], x);
+                        float d = 0.f;
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) d = fmaf(qv[c], x[c], d);
+                        d = group_sum<LPR>(d);
+                        const long row = row0[u] + i * RPW + rg;
+                        s[i] = (row < a.T_valid) ? d : -INFINITY;
+                        mt = fmaxf(mt, s[i]);
+                    }
+                    if (mt != -INFINITY) {
+                        const float corr = __expf(m - mt);
+                        l *= corr;
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) o[c] *= corr;
+#pragma unroll
+                        for (int i = 0; i < RPL; ++i) {
+                            const float p = __expf(s[i] - mt);
+                            l += p;
+                            float x[8];
+                            R::unpack(vr[u][i], x);
+#pragma unroll
+                            for (int c = 0; c < 8; ++c) o[c] = fmaf(p, x[c], o[c]);
+                        }
+                        m = mt;
+                    }
+                }
+            }
+
+            mark(item, 5);
+            // merge the row groups of the wave, then the waves through LDS
+#pragma unroll
+            for (int mask = LPR; mask < 64; mask <<= 1) {
+                const float m2 = shfl_xor_f(m, mask);
+                const float l2 = shfl_xor_f(l, mask);
+                const float mn = fmaxf(m, m2);
+                const float a1 = (m == -INFINITY) ? 0.f : __expf(m - mn);
+                const float a2 = (m2 == -INFINITY) ? 0.f : __expf(m2 - mn);
+                l = l * a1 + l2 * a2;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const float o2 = shfl_xor_f(o[c], mask);
+                    o[c] = o[c] * a1 + o2 * a2;
+                }
+                m = mn;
+            }
+            if (rg == 0) {
+                if (cl == 0) {
+                    s_m[wave] = m;
+                    s_l[wave] = l;
+                }
+#pragma unroll
+                for (int c = 0; c < 8; ++c) s_o[wave][c0 + c] = o[c];
+            }
+            __syncthreads();
+            float M = -INFINITY, L = 0.f, O = 0.f;
+            if (tid < D) {
+#pragma unroll
+                for (int w = 0; w < kFusedWaves; ++w) M = fmaxf(M, s_m[w]);
+#pragma unroll
+                for (int w = 0; w < kFusedWaves; ++w) {
+                    const float aw = (s_m[w] == -INFINITY) ? 0.f : __expf(s_m[w] - M);
+                    L += s_l[w] * aw;
+                    O += s_o[w][tid] * aw;
+                }
+            }
+            if (!finish) {
+                uint64_t *part = a.partial + ((long)unit * a.S_att + slice) * (D + 2);
+                if (tid < D) {
+                    publish_f32(&part[2 + tid], O, a.tag);
+                    if (tid == 0) {
+                        publish_f32(&part[0], M, a.tag);
+                        publish_f32(&part[1], L, a.tag);
+                    }
+                }
+            } else if (a.S_att > 1 && tid < D) {
+                merge_partials(a.partial + (long)unit * a.S_att * (D + 2), a.S_att - 1, D + 2, tid, a.tag, a.spin_limit,
+                               a.err, M, L, O);
+            }
+            mark(item, 6);
+            if (finish && tid < D) {
+                const float inv = (L > 0.f) ? 1.f / L : 0.f;
+                from_f32(((ST *)a.out)[(long)unit * D + tid], O * inv);
+                if (tid == 0 && a.lse_out) a.lse_out[unit] = (L > 0.f) ? M + __logf(L) : -INFINITY;
+            }
+        }
+        fetch_next();
+        __syncthreads();
+        item = s_next;
+    }
+
+    if (tid == 0) {
+        if (atomicAdd(a.done, 1u) == gridDim.x - 1u) {  // last workgroup out resets the counters
+            atomicExch(a.ticket, 0u);
+            atomicExch(a.done, 0u);
+        }
+    }
+}
+
+template <typename ST, int D, int NT>
+static int launch_fused(const FusedParams &prm, int grid, hipStream_t stream)
+{
+    if (prm.Np > 15360) return RS_UNSUPPORTED;  // keys must fit 60 KiB of LDS
+    decode_fused_kernel<ST, D, NT><<<grid, NT, (size_t)prm.Np * 4, stream>>>(prm);
+    return RS_OK;
+}
+
+int decode_fused_dispatch(int dtype, int D, const FusedParams &prm, int grid, int threads, hipStream_t stream)
+{
+    if (threads == 512) {
+        if (dtype == RS_BF16) return D == 128 ? launch_fused<bf16, 128, 512>(prm, grid, stream) : launch_fused<bf16, 64, 512>(prm, grid, stream);
+        return D == 128 ? launch_fused<float, 128, 512>(prm, grid, stream) : launch_fused<float, 64, 512>(prm, grid, stream);
+    }
+    if (dtype == RS_BF16) return D == 128 ? launch_fused<bf16, 128, 256>(prm, grid, stream) : launch_fused<bf16, 64, 256>(prm, grid, stream);
+    return D == 128 ? launch_fused<float, 128, 256>(prm, grid, stream) : launch_fused<float, 64, 256>(prm, grid, stream);
+}
+
+}  // namespace rs

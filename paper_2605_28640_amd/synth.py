@@ -11,6 +11,7 @@ storage dtype (bf16 values have a zero low half).
 """
 from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, replace
+from functools import lru_cache
 import os
 
 import numpy as np
@@ -87,10 +88,15 @@ def _gate(rng, shape):
     return (np.float32(1.0) / (np.float32(1.0) + np.exp(-x))).astype(np.float32)
 
 
+@lru_cache(maxsize=None)
+def _q_dir(config_id, D, unit, seed):
+    d = _rng(seed, config_id, _T_QDIR, unit).standard_normal(D)
+    return (d * np.sqrt(D) / np.linalg.norm(d)).astype(np.float32)
+
+
 def q_dir(w, b, kvh, seed=BASE_SEED):
     """Retrieval direction of one KV head: N(0, I) rescaled to norm sqrt(D)."""
-    d = _rng(seed, w.config_id, _T_QDIR, b * w.Hkv + kvh).standard_normal(w.D)
-    return (d * np.sqrt(w.D) / np.linalg.norm(d)).astype(np.float32)
+    return _q_dir(w.config_id, w.D, b * w.Hkv + kvh, seed)
 
 
 def needle_positions(w, b, kvh, seed=BASE_SEED):
