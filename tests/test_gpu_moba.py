@@ -1,0 +1,94 @@
+"""GPU parity of MoBA routing (block means, gate scores, top-K blocks) and of the block-sparse
+/ dense causal prefill attention against the float64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import say, to_dev, to_np
+from helpers import attn_close, topk_set_ok
+from paper_2605_28640_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(w, T, Tcap):
+    w = w.scaled(T=T)
+    k, v, g = synth.prefill(w)
+    ko, vo, _, _ = oracle.rat_scan(k, v, g)
+    kc = np.zeros((w.B, w.Hkv, Tcap, w.D), dtype=np.float32)
+    vc = np.zeros_like(kc)
+    kc[:, :, :T], vc[:, :, :T] = oracle.round_to_bf16(ko), oracle.round_to_bf16(vo)
+    q = synth.prefill_queries(w)
+    return w, q, kc, vc
+
+
+CASES = [
+    # workload, T, Tcap, block, K, n_first
+    (synth.C4.scaled(B=1, Hq=2, Hkv=2), 2048, 2048, 512, 3, 0),
+    (synth.C4.scaled(B=1, Hq=4, Hkv=2), 1000, 1024, 64, 4, 1),      # GQA, ragged tail block, first block kept
+    (synth.C4.scaled(B=2, Hq=2, Hkv=2, D=64), 777, 800, 128, 2, 0),  # D=64, T not a multiple of anything
+    (synth.C4.scaled(B=1, Hq=2, Hkv=1), 512, 512, 16, 8, 0),         # small blocks inside one row tile
+]
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_moba_select_and_sparse_prefill(rs, case):
+    w, T, Tcap, block, K, n_first = CASES[case]
+    say("moba case", case, T, Tcap, block, K, n_first)
+    w, q, kc, vc = _setup(w, T, Tcap)
+    Nb = -(-T // block)
+    scale = 1.0 / np.sqrt(w.D)
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tcap, 16, torch.bfloat16)
+    tq, tkc, tvc = to_dev(q, "bf16"), to_dev(kc, "bf16"), to_dev(vc, "bf16")
+    means = torch.zeros(w.B, w.Hkv, Nb, w.D, device="cuda")
+    idx = torch.full((w.B, w.Hq, T, K), -9, dtype=torch.int32, device="cuda")
+    ws = rs.Workspace(max(rs.moba_select_prefill_workspace_bytes(s, T, block),
+                          rs.sparse_attn_prefill_workspace_bytes(s, T, block, max(K, Nb))))
+    rs.moba_select_prefill(s, tq, tkc, T, block, K, n_first, means, idx, ws)
+    omeans = oracle.moba_block_means(kc, T, block)
+    np.testing.assert_allclose(to_np(means), omeans, rtol=1e-5, atol=1e-6)
+    oidx, osc = oracle.moba_select(q, omeans, T, block, K, n_first, want_scores=True)
+    gidx = to_np(idx)
+    same = 0
+    for b in range(w.B):
+        for h in range(w.Hq):
+            for t in range(T):
+                own = t // block
+                take = min(K, own + 1)
+                sc = np.where(np.isnan(osc[b, h, t, :own + 1]), 0.0, osc[b, h, t, :own + 1])
+                forced = np.zeros(own + 1, bool)
+                forced[own] = True
+                forced[:n_first] = True
+                row = gidx[b, h, t]
+                assert np.all(row[take:] == -1), (b, h, t, row)
+                ok, why = topk_set_ok(sc, forced, take, row[:take])
+                assert ok, (b, h, t, why, row)
+                same += np.array_equal(row, oidx[b, h, t])
+    say("  rows with identical block lists:", same, "of", w.B * w.Hq * T)
+
+    # block-sparse attention over the GPU's own routing
+    out = torch.zeros(w.B, w.Hq, T, w.D, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(w.B, w.Hq, T, device="cuda")
+    rs.sparse_attn_prefill(s, tq, tkc, tvc, T, block, scale, idx, K, out, lse, ws)
+    oout, olse = oracle.sparse_attn_prefill(q, kc, vc, T, block, scale, gidx)
+    ok, worst = attn_close(to_np(out), oout)
+    assert ok, worst
+    np.testing.assert_allclose(to_np(lse), olse, rtol=2e-3, atol=2e-3)
+    say("  sparse prefill worst relative row error", worst)
+
+    # dense causal path, and enough blocks = dense
+    outd = torch.zeros_like(out)
+    rs.sparse_attn_prefill(s, tq, tkc, tvc, T, block, scale, None, 0, outd, lse, ws)
+    od, odl = oracle.sparse_attn_prefill(q, kc, vc, T, block, scale)
+    ok, worst = attn_close(to_np(outd), od)
+    assert ok, worst
+    np.testing.assert_allclose(to_np(lse), odl, rtol=2e-3, atol=2e-3)
+    if Nb <= 32:
+        idx_all = torch.full((w.B, w.Hq, T, Nb), -9, dtype=torch.int32, device="cuda")
+        rs.moba_select_prefill(s, tq, tkc, T, block, Nb, n_first, means, idx_all, ws)
+        outf = torch.zeros_like(out)
+        rs.sparse_attn_prefill(s, tq, tkc, tvc, T, block, scale, idx_all, Nb, outf, None, ws)
+        assert attn_close(to_np(outf), od)[0]
+    torch.cuda.synchronize()
+    ws.async_status()
