@@ -1,7 +1,374 @@
-// placeholder until the SnapKV kernels land
+// SnapKV cache compression (App. A.1, SnapKV paragraph; Sec. 2.2, Eq. 3 over single tokens):
+// the W observation queries at the end of the prompt attend causally; each prefix position
+// collects its attention probability summed over the window and over the query heads of its
+// KV head's group; the votes are max-pooled; per KV head the K_keep best positions are kept
+// (ascending), followed by the window rows.
+//
+// The [G*W x T] score matrix of a KV head is a dense contraction, done on the matrix cores
+// (v_mfma_f32_32x32x16_bf16) in two sweeps over the keys: sweep 1 forms S^T = K Q^T so that
+// a lane owns one query row and gets its softmax max / sum cheaply; sweep 2 forms S = Q K^T
+// so that a lane owns one key column and its vote is an in-lane sum over the query rows.
 #include "common.h"
+
 namespace rs {
-size_t snapkv_ws_bytes(const rs_shape *, long, int) { return RS_WS_CTRL_BYTES; }
-int snapkv_dispatch(const rs_shape *, const void *, const void *, const void *, long, int, int, int, float, void *,
-                    void *, long, int32_t *, float *, char *, hipStream_t) { return RS_UNSUPPORTED; }
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kSnapKeysPerWg = 1024;  // keys per workgroup
+constexpr int kSnapKT = 32;           // keys per step
+
+// sweep 1 (STATS = true): partial (max, sum) per (row, key chunk)
+// sweep 2 (STATS = false): votes per key from the final log-sum-exp of each row
+template <int D, bool STATS>
+__global__ __launch_bounds__(256) void snapkv_sweep_kernel(const bf16 *__restrict__ q_win,
+                                                           const bf16 *__restrict__ k_cache, float *stats,
+                                                           const float *__restrict__ lse, float *votes, int Hq,
+                                                           int Hkv, long T, long Tcap, int W, int n_chunks,
+                                                           float scale)
+{
+    constexpr int NC = D / 16;
+    constexpr int KS = D + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t sK[kSnapKT * KS];
+    __shared__ float s_vote[4][kSnapKT];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lq = lane & 31, h = lane >> 5;
+    const int chunk = blockIdx.x;
+    const int bk = blockIdx.y;  // b * Hkv + kvh
+    const int b = bk / Hkv, kvh = bk % Hkv;
+    const int G = Hq / Hkv;
+    const int R = G * W;  // query rows of this KV head
+    const long L = T - W;
+    const bf16 *kb = k_cache + (long)bk * Tcap * D;
+    const long kc0 = (long)chunk * kSnapKeysPerWg;
+    const long kc1 = (kc0 + kSnapKeysPerWg < T) ? kc0 + kSnapKeysPerWg : T;
+    const int n_row_tiles = (R + 127) / 128;
+
+    for (int rt = 0; rt < n_row_tiles; ++rt) {
+        // this lane's query row (sweep 1: its column of S^T; sweep 2: operand row)
+        const int r = rt * 128 + wave * 32 + lq;
+        const bool r_ok = r < R;
+        const int g = r_ok ? r / W : 0, w = r_ok ? r % W : 0;
+        bf16x8 qf[NC];
+        {
+            const bf16 *qrow = q_win + ((long)(b * Hq + kvh * G + g) * W + w) * D;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) qf[c] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * c + 8 * h);
+        }
+        const long pos = L + w;  // absolute position of the query: keys <= pos are visible
+        float m = -INFINITY, l = 0.f;
+        // sweep 2: log-sum-exp and position of the 16 query rows this lane sees in S
+        float lse_v[16];
+        int w_v[16];
+        if (!STATS) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = rt * 128 + wave * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+                lse_v[v] = (rr < R) ? lse[(long)bk * R + rr] : INFINITY;  // exp(s - inf) = 0 for padding rows
+                w_v[v] = (rr < R) ? rr % W : 0;
+            }
+        }
+
+        for (long k0 = kc0; k0 < kc1; k0 += kSnapKT) {
+            __syncthreads();
+            constexpr int CHUNKS = kSnapKT * D / 8;
+#pragma unroll
+            for (int i = 0; i < (CHUNKS + 255) / 256; ++i) {
+                const int ch = i * 256 + tid;
+                if (ch < CHUNKS) {
+                    const int key = ch / (D / 8), d0 = (ch % (D / 8)) * 8;
+                    uint4 kk = make_uint4(0u, 0u, 0u, 0u);
+                    if (k0 + key < kc1) kk = *reinterpret_cast<const uint4 *>(kb + (k0 + key) * D + d0);
+                    *reinterpret_cast<uint4 *>(&sK[key * KS + d0]) = kk;
+                }
+            }
+            __syncthreads();
+            f32x16 sacc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&sK[lq * KS + 16 * c + 8 * h]);
+                if (STATS) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], sacc, 0, 0, 0);  // [key][row]
+                else sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[c], kf, sacc, 0, 0, 0);        // [row][key]
+            }
+            if (STATS) {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const long key = k0 + 8 * (v / 4) + 4 * h + (v % 4);
+                    const bool ok = r_ok && key < kc1 && key <= pos;
+                    sacc[v] = ok ? sacc[v] * scale : -INFINITY;
+                    mx = fmaxf(mx, sacc[v]);
+                }
+                mx = fmaxf(mx, shfl_xor_f(mx, 32));
+                const float m_new = fmaxf(m, mx);
+                const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+                float psum = 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) psum += __expf(sacc[v] - m_safe);
+                psum += shfl_xor_f(psum, 32);
+                l = l * ((m == -INFINITY) ? 0.f : __expf(m - m_safe)) + psum;
+                m = m_new;
+            } else {
+                const long key = k0 + lq;  // this lane's key column
+                float vsum = 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const bool ok = key <= L + w_v[v];  // causal inside the window (always true for prefix keys)
+                    vsum += ok ? __expf(sacc[v] * scale - lse_v[v]) : 0.f;
+                }
+                vsum += shfl_xor_f(vsum, 32);
+                if (h == 0) s_vote[wave][lq] = vsum;
+                __syncthreads();
+                if (tid < kSnapKT) {
+                    const long kk = k0 + tid;
+                    if (kk < L && kk < kc1) {
+                        const float tot = (s_vote[0][tid] + s_vote[1][tid]) + (s_vote[2][tid] + s_vote[3][tid]);
+                        float *dst = votes + (long)bk * L + kk;
+                        *dst = (rt == 0) ? tot : *dst + tot;
+                    }
+                }
+            }
+        }
+        if (STATS && r_ok && h == 0) {
+            float *st = stats + (((long)bk * n_chunks + chunk) * R + r) * 2;
+            st[0] = m;
+            st[1] = l;
+        }
+    }
+}
+
+// log-sum-exp of each row over its key chunks
+__global__ void snapkv_lse_kernel(const float *__restrict__ stats, float *__restrict__ lse, int R, int n_chunks,
+                                  long rows_total)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows_total) return;
+    const long bk = i / R;
+    const int r = (int)(i % R);
+    float M = -INFINITY;
+    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, stats[((bk * n_chunks + c) * R + r) * 2]);
+    float Ls = 0.f;
+    for (int c = 0; c < n_chunks; ++c) {
+        const float mc = stats[((bk * n_chunks + c) * R + r) * 2];
+        if (mc != -INFINITY) Ls += stats[((bk * n_chunks + c) * R + r) * 2 + 1] * __expf(mc - M);
+    }
+    lse[i] = M + __logf(Ls);
+}
+
+__global__ void snapkv_pool_kernel(const float *__restrict__ votes, float *__restrict__ pooled, long L, int kernel,
+                                   long total)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const long row = i / L, p = i % L;
+    const int half = kernel / 2;
+    const long lo = (p - half < 0) ? 0 : p - half;
+    const long hi = (p + half > L - 1) ? L - 1 : p + half;
+    float m = votes[row * L + lo];
+    for (long j = lo + 1; j <= hi; ++j) m = fmaxf(m, votes[row * L + j]);
+    pooled[i] = m;
+}
+
+// ------------------------------------------------------------------------------------
+// top-K_keep of L pooled votes per (batch, KV head), one 1024-thread workgroup each.
+// Radix select over the order-preserving keys in global memory (they stay in L2), then an
+// ordered compaction: each wave owns a contiguous range and ranks with ballots.
+// ------------------------------------------------------------------------------------
+constexpr int kTokThreads = 1024;
+
+__global__ __launch_bounds__(kTokThreads) void snapkv_select_kernel(const float *__restrict__ pooled,
+                                                                    int32_t *__restrict__ idx_out, long L, int K_keep)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_remaining;
+    __shared__ int s_wgt[kTokThreads / 64], s_weq[kTokThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long bk = blockIdx.x;
+    const float *src = pooled + bk * L;
+    int32_t *dst = idx_out + bk * K_keep;
+    if (K_keep == 0) return;
+    if (tid == 0) {
+        s_prefix = 0u;
+        s_remaining = K_keep;
+    }
+#pragma nounroll
+    for (int pass = 3; pass >= 0; --pass) {
+        if (tid < 256) hist[tid] = 0u;
+        __syncthreads();
+        const uint32_t prefix = s_prefix;
+        const int shift = pass * 8;
+        const uint32_t himask = (pass == 3) ? 0u : (0xffffffffu << (shift + 8));
+        int run_bin = -1, run_cnt = 0;
+        for (long p = tid; p < L; p += kTokThreads) {
+            const uint32_t key = float_to_key(src[p]);
+            const int bin = ((key & himask) == prefix) ? (int)((key >> shift) & 255u) : -1;
+            if (bin != run_bin) {
+                if (run_bin >= 0) atomicAdd(&hist[run_bin], (uint32_t)run_cnt);
+                run_bin = bin;
+                run_cnt = 0;
+            }
+            ++run_cnt;
+        }
+        if (run_bin >= 0) atomicAdd(&hist[run_bin], (uint32_t)run_cnt);
+        __syncthreads();
+        if (tid < 64) {
+            const uint32_t h0 = hist[tid * 4], h1 = hist[tid * 4 + 1], h2 = hist[tid * 4 + 2], h3 = hist[tid * 4 + 3];
+            const int own = (int)(h0 + h1 + h2 + h3);
+            int suf = own;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int o = __shfl_down(suf, d, 64);
+                if (tid + d < 64) suf += o;
+            }
+            const int above = suf - own;
+            const int rem = s_remaining;
+            if (above < rem && rem <= suf) {
+                int acc = above, bin = tid * 4;
+                const uint32_t hh[4] = {h0, h1, h2, h3};
+                for (int bb = 3; bb >= 0; --bb) {
+                    if (acc + (int)hh[bb] >= rem) {
+                        bin = tid * 4 + bb;
+                        break;
+                    }
+                    acc += (int)hh[bb];
+                }
+                s_prefix = prefix | ((uint32_t)bin << shift);
+                s_remaining = rem - acc;
+            }
+        }
+        __syncthreads();
+    }
+    const uint32_t kth = s_prefix;
+    const int take_eq = s_remaining;
+
+    // wave w owns positions [w * per, (w + 1) * per), walked 64 at a time in order
+    const long per = ((L + kTokThreads / 64 - 1) / (kTokThreads / 64) + 63) / 64 * 64;
+    const long p0 = wave * per;
+    const long p1 = (p0 + per < L) ? p0 + per : L;
+    const long n_it = (p1 > p0) ? (p1 - p0 + 63) / 64 : 0;  // uniform over the wave
+    int n_gt = 0, n_eq = 0;
+    for (long it = 0; it < n_it; ++it) {
+        const long p = p0 + it * 64 + lane;
+        const bool in = p < p1;
+        const uint32_t key = in ? float_to_key(src[p]) : 0u;
+        n_gt += __popcll(__ballot(in && key > kth));
+        n_eq += __popcll(__ballot(in && key == kth));
+    }
+    if (lane == 0) {
+        s_wgt[wave] = n_gt;
+        s_weq[wave] = n_eq;
+    }
+    __syncthreads();
+    int gt_before = 0, eq_before = 0;
+    for (int w2 = 0; w2 < wave; ++w2) {
+        gt_before += s_wgt[w2];
+        eq_before += s_weq[w2];
+    }
+    for (long it = 0; it < n_it; ++it) {
+        const long p = p0 + it * 64 + lane;
+        const bool in = p < p1;
+        const uint32_t key = in ? float_to_key(src[p]) : 0u;
+        const bool is_gt = in && key > kth, is_eq = in && key == kth;
+        const uint64_t bg = __ballot(is_gt), be = __ballot(is_eq);
+        const int gt_lane = __builtin_amdgcn_mbcnt_hi((uint32_t)(bg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bg, 0u));
+        const int eq_lane = __builtin_amdgcn_mbcnt_hi((uint32_t)(be >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)be, 0u));
+        const int eq_rank = eq_before + eq_lane;  // rank among all positions equal to the K-th vote
+        if (is_gt || (is_eq && eq_rank < take_eq)) {
+            const int eq_taken = (eq_rank < take_eq) ? eq_rank : take_eq;  // equal positions before this one that are kept
+            dst[gt_before + gt_lane + (is_eq ? eq_rank : eq_taken)] = (int32_t)p;
+        }
+        gt_before += __popcll(bg);
+        eq_before += __popcll(be);
+    }
+}
+
+// copy the kept rows, then the window rows: one 16-byte chunk per thread
+template <typename ST>
+__global__ void snapkv_gather_kernel(const ST *__restrict__ k_cache, const ST *__restrict__ v_cache,
+                                     const int32_t *__restrict__ idx, ST *__restrict__ kc_out, ST *__restrict__ vc_out,
+                                     long T, long Tcap, long Tcap_out, int W, int K_keep, int D, long total)
+{
+    const int cpr = D * (int)sizeof(ST) / 16;  // chunks per row
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const long rows = K_keep + W;
+    const long bk = i / (rows * cpr);
+    const long rem = i % (rows * cpr);
+    const long r = rem / cpr;
+    const int c = (int)(rem % cpr);
+    const long srow = (r < K_keep) ? idx[bk * K_keep + r] : (T - W) + (r - K_keep);
+    const uint4 *ks = reinterpret_cast<const uint4 *>(k_cache + (bk * Tcap + srow) * D) + c;
+    const uint4 *vs = reinterpret_cast<const uint4 *>(v_cache + (bk * Tcap + srow) * D) + c;
+    reinterpret_cast<uint4 *>(kc_out + (bk * Tcap_out + r) * D)[c] = *ks;
+    reinterpret_cast<uint4 *>(vc_out + (bk * Tcap_out + r) * D)[c] = *vs;
+}
+
+static size_t al256s(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct SnapLayout {
+    int n_chunks, R;
+    size_t off_stats, off_lse, off_votes, off_pooled, total;
+};
+
+static SnapLayout snap_layout(const rs_shape *s, long T, int W)
+{
+    SnapLayout L;
+    const long BK = (long)s->B * s->Hkv;
+    L.R = (s->Hq / s->Hkv) * W;
+    L.n_chunks = (int)((T + kSnapKeysPerWg - 1) / kSnapKeysPerWg);
+    size_t o = RS_WS_CTRL_BYTES;
+    L.off_stats = o;
+    o += al256s((size_t)BK * L.n_chunks * L.R * 2 * 4);
+    L.off_lse = o;
+    o += al256s((size_t)BK * L.R * 4);
+    L.off_votes = o;
+    o += al256s((size_t)BK * (T - W) * 4);
+    L.off_pooled = o;
+    o += al256s((size_t)BK * (T - W) * 4);
+    L.total = o;
+    return L;
+}
+
+size_t snapkv_ws_bytes(const rs_shape *s, long T, int W) { return (T > W) ? snap_layout(s, T, W).total : RS_WS_CTRL_BYTES; }
+
+int snapkv_dispatch(const rs_shape *s, const void *q_win, const void *k_cache, const void *v_cache, long T, int W,
+                    int K_keep, int pool_kernel, float scale, void *kc_out, void *vc_out, long Tcap_out,
+                    int32_t *idx_out, float *votes_out, char *ws, hipStream_t stream)
+{
+    if (s->dtype != RS_BF16) return RS_UNSUPPORTED;  // the matrix-core path takes bf16 operands
+    const SnapLayout Ly = snap_layout(s, T, W);
+    const long BK = (long)s->B * s->Hkv;
+    const long L = T - W;
+    float *stats = (float *)(ws + Ly.off_stats), *lse = (float *)(ws + Ly.off_lse);
+    float *votes = (float *)(ws + Ly.off_votes);
+    float *pooled = votes_out ? votes_out : (float *)(ws + Ly.off_pooled);
+    const dim3 grid((unsigned)Ly.n_chunks, (unsigned)BK);
+    const bf16 *qw = (const bf16 *)q_win, *kc = (const bf16 *)k_cache;
+    if (s->D == 128)
+        snapkv_sweep_kernel<128, true><<<grid, 256, 0, stream>>>(qw, kc, stats, nullptr, nullptr, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
+    else
+        snapkv_sweep_kernel<64, true><<<grid, 256, 0, stream>>>(qw, kc, stats, nullptr, nullptr, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
+    const long rows_total = BK * Ly.R;
+    snapkv_lse_kernel<<<(unsigned)((rows_total + 255) / 256), 256, 0, stream>>>(stats, lse, Ly.R, Ly.n_chunks, rows_total);
+    // votes exist for prefix keys only: chunks that start past the prefix are not needed
+    const dim3 grid2((unsigned)((L + kSnapKeysPerWg - 1) / kSnapKeysPerWg), (unsigned)BK);
+    if (s->D == 128)
+        snapkv_sweep_kernel<128, false><<<grid2, 256, 0, stream>>>(qw, kc, nullptr, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
+    else
+        snapkv_sweep_kernel<64, false><<<grid2, 256, 0, stream>>>(qw, kc, nullptr, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
+    const long tot = BK * L;
+    snapkv_pool_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, stream>>>(votes, pooled, L, pool_kernel, tot);
+    if (K_keep > 0) snapkv_select_kernel<<<(unsigned)BK, kTokThreads, 0, stream>>>(pooled, idx_out, L, K_keep);
+    const int cpr = s->D * 2 / 16;
+    const long total = BK * (long)(K_keep + W) * cpr;
+    snapkv_gather_kernel<bf16><<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(
+        (const bf16 *)k_cache, (const bf16 *)v_cache, idx_out, (bf16 *)kc_out, (bf16 *)vc_out, T, s->Tcap, Tcap_out, W,
+        K_keep, s->D, total);
+    return hipGetLastError() == hipSuccess ? RS_OK : RS_LAUNCH_FAILED;
+}
+
 }  // namespace rs

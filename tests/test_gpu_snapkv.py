@@ -1,0 +1,86 @@
+"""GPU parity of SnapKV compression (window votes, pooling, top-K positions, gather) and of
+dense decode over the compressed cache, against the float64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import say, to_dev, to_np
+from helpers import attn_close, topk_set_ok
+from paper_2605_28640_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(w, T, Tcap):
+    w = w.scaled(T=T)
+    k, v, g = synth.prefill(w)
+    ko, vo, _, _ = oracle.rat_scan(k, v, g)
+    kc = np.zeros((w.B, w.Hkv, Tcap, w.D), dtype=np.float32)
+    vc = np.zeros_like(kc)
+    kc[:, :, :T], vc[:, :, :T] = oracle.round_to_bf16(ko), oracle.round_to_bf16(vo)
+    return w, synth.window_queries(w), kc, vc
+
+
+CASES = [
+    # workload, T, Tcap, K_keep, pool
+    (synth.C5.scaled(B=1, Hq=8, Hkv=2), 4096, 4096, 512, 7),        # G*W = 128 rows: one row tile
+    (synth.C5.scaled(B=2, Hq=2, Hkv=2, W=20), 3000, 3008, 300, 7),  # ragged rows, ragged key chunks
+    (synth.C5.scaled(B=1, Hq=16, Hkv=2, D=64), 2500, 2560, 100, 1),  # 256 rows: two row tiles; no pooling
+    (synth.C5.scaled(B=1, Hq=4, Hkv=4, W=8), 1200, 1216, 1192, 3),   # keep everything
+]
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_snapkv_compress_then_decode(rs, case):
+    w, T, Tcap, K_keep, pool = CASES[case]
+    say("snapkv case", case, T, Tcap, K_keep, pool, "W", w.W)
+    w, qw, kc, vc = _setup(w, T, Tcap)
+    W, L = w.W, T - w.W
+    scale = 1.0 / np.sqrt(w.D)
+    Tco = ((K_keep + W + 32 + 15) // 16) * 16
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tcap, 16, torch.bfloat16)
+    ws = rs.Workspace(rs.snapkv_compress_workspace_bytes(s, T, W))
+    kco = torch.zeros(w.B, w.Hkv, Tco, w.D, dtype=torch.bfloat16, device="cuda")
+    vco = torch.zeros_like(kco)
+    idx = torch.full((w.B, w.Hkv, K_keep), -5, dtype=torch.int32, device="cuda")
+    votes = torch.zeros(w.B, w.Hkv, L, device="cuda")
+    rs.snapkv_compress(s, to_dev(qw, "bf16"), to_dev(kc, "bf16"), to_dev(vc, "bf16"), T, W, K_keep, pool, scale,
+                       kco, vco, Tco, idx, votes, ws)
+    ovotes = oracle.snapkv_votes(qw, kc, T, scale)
+    opooled = oracle.maxpool1d(ovotes, pool)
+    np.testing.assert_allclose(to_np(votes), opooled, rtol=2e-4, atol=1e-9)
+    gidx = to_np(idx)
+    oidx, okc, ovc = oracle.snapkv_select_gather(opooled, kc, vc, T, W, K_keep)
+    same = 0
+    for b in range(w.B):
+        for h in range(w.Hkv):
+            ok, why = topk_set_ok(opooled[b, h], np.zeros(L, bool), K_keep, gidx[b, h])
+            assert ok, (b, h, why)
+            same += np.array_equal(gidx[b, h], oidx[b, h])
+            rows = np.concatenate([gidx[b, h], np.arange(L, T)])
+            np.testing.assert_array_equal(to_np(kco)[b, h, :K_keep + W], kc[b, h, rows])  # gathered bit for bit
+            np.testing.assert_array_equal(to_np(vco)[b, h, :K_keep + W], vc[b, h, rows])
+    say("  identical kept sets:", same, "of", w.B * w.Hkv)
+    assert torch.all(kco[:, :, K_keep + W:] == 0)
+
+    # a decode step over the compressed cache: append through rat_scan, then dense attention
+    sc = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tco, 16, torch.bfloat16)
+    kd, vd, gd, qd = synth.decode_step(w, 0)
+    sk = torch.zeros(w.B, w.Hkv, w.D, device="cuda")
+    sv = torch.zeros_like(sk)
+    rs.rat_scan(sc, to_dev(kd, "bf16"), to_dev(vd, "bf16"), to_dev(gd), sk, sv, kco, vco, K_keep + W, 1, None)
+    ws2 = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(sc, K_keep + W + 1, 0))
+    out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.bfloat16, device="cuda")
+    rs.sparse_attn_decode(sc, to_dev(qd, "bf16"), kco, vco, K_keep + W + 1, scale, None, 0, None, 0, 0, out, None,
+                          None, ws2)
+    hk, hv = to_np(kco), to_np(vco)
+    want, _ = oracle.sparse_attn_decode(qd, hk, hv, 16, K_keep + W + 1, scale)
+    assert attn_close(to_np(out), want)[0]
+    if K_keep == L:  # nothing dropped: same as dense attention over the full cache
+        full_k = np.concatenate([kc[:, :, :T], hk[:, :, T:T + 1]], axis=2)
+        full_v = np.concatenate([vc[:, :, :T], hv[:, :, T:T + 1]], axis=2)
+        want2, _ = oracle.sparse_attn_decode(qd, full_k, full_v, 16, T + 1, scale)
+        assert attn_close(to_np(out), want2)[0]
+    torch.cuda.synchronize()
+    ws.async_status()
