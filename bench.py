@@ -33,6 +33,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=3)
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain 1 GiB -> 1 GiB device copy (the known-size kernel that scales "
+                         "the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (every box has one; the path shards over batch "
@@ -182,6 +185,14 @@ def main():
             byt = B * Hq * ((Np * 2 * D * 2 + Kx * P * D * 4) if use_meta else Tv * D * 4)
             extra[name] = {"ms": round(ms, 4), "GB/s": round(byt / ms / 1e6, 1),
                            "frac_hbm_peak": round(byt / (ms * 1e-3) / HBM_PEAK, 4), "tok/s": round(B / (ms * 1e-3), 1)}
+
+    if args.calibrate:
+        src = torch.empty(1 << 29, dtype=dt, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- CPU baseline: the test oracle, as it stands, on this machine's host cores ----------
     cpu = None

@@ -330,10 +330,17 @@ int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache
         if (sa > kMaxAttSplits) sa = kMaxAttSplits;
         if (sa > K) sa = K;
         prm.S_score = ss < 1 ? 1 : ss; prm.S_att = sa < 1 ? 1 : sa;
+        int fine = env_int("RATSPARSE_FUSED_FINE", 2) * prm.S_att;
+        if (fine > kMaxAttSplits) fine = kMaxAttSplits;
+        if (fine > K) fine = K;
+        prm.S_att_fine = fine < prm.S_att ? prm.S_att : fine;
+        prm.units_fine = (int)(units * env_int("RATSPARSE_FUSED_FINE_PCT", 6) / 100);
+        prm.S_max = kMaxAttSplits;
         prm.reverse = env_int("RATSPARSE_FUSED_PINGPONG", 1) ? (int)(T_valid & 1) : 0;
+        prm.nt_kv = env_int("RATSPARSE_FUSED_NT", 1);  // bit 0: K/V pages, bit 1: page metadata
         prm.scale = scale; prm.tag = tag; prm.spin_limit = g_spin_limit.load();
         prm.trace = env_int("RATSPARSE_TRACE", 0) ? (uint64_t *)(w + L.off_trace) : nullptr;
-        long items = units * (prm.S_score + prm.S_att);
+        long items = units * (prm.S_score + prm.S_att) + (long)prm.units_fine * (prm.S_att_fine - prm.S_att);
         // two 512-thread workgroups per CU: one streams while the other selects or merges
         const int threads = env_int("RATSPARSE_FUSED_THREADS", 512) == 256 ? 256 : 512;
         long grid = env_int("RATSPARSE_FUSED_GRID", 2 * num_cus());

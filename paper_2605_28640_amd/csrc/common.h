@@ -49,6 +49,15 @@ struct Row8<bf16> {
         w.r = *reinterpret_cast<const uint4 *>(p);
         return w;
     }
+    // streaming load: the line is not meant to stay in the caches
+    __device__ __forceinline__ static raw_t load_raw_nt(const bf16 *p)
+    {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+        raw_t w;
+        w.r = make_uint4(v.x, v.y, v.z, v.w);
+        return w;
+    }
     __device__ __forceinline__ static raw_t zero_raw()
     {
         raw_t w;
@@ -88,6 +97,16 @@ struct Row8<float> {
         raw_t w;
         w.a = *reinterpret_cast<const float4 *>(p);
         w.b = *reinterpret_cast<const float4 *>(p + 4);
+        return w;
+    }
+    __device__ __forceinline__ static raw_t load_raw_nt(const float *p)
+    {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+        const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p + 4));
+        raw_t w;
+        w.a = make_float4(a.x, a.y, a.z, a.w);
+        w.b = make_float4(b.x, b.y, b.z, b.w);
         return w;
     }
     __device__ __forceinline__ static raw_t zero_raw()

@@ -19,7 +19,10 @@ struct FusedParams {
     long Tcap, Np_cap, T_valid;
     int P, Np, K, n_first, n_local;
     int S_score, S_att;
+    int units_fine, S_att_fine;  // the last units_fine units (in ticket order) use S_att_fine slices
+    int S_max;                   // slices the partial buffer holds per unit
     int reverse;            // walk the units from the last to the first
+    int nt_kv;              // stream K/V pages with non-temporal loads
     float scale;
     uint32_t tag;
     int spin_limit;

@@ -42,8 +42,11 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
     const int rg = lane / LPR;
     const int cl = lane % LPR;
     const int c0 = cl * 8;
+    // the units scored last are split finer: their attention is what the launch ends on
     const int n_score = a.units * a.S_score;
-    const int n_total = n_score + a.units * a.S_att;
+    const int u_coarse = a.units - a.units_fine;
+    const int n_att_coarse = u_coarse * a.S_att;
+    const int n_total = n_score + n_att_coarse + a.units_fine * a.S_att_fine;
     const int G = a.Hq / a.Hkv;
 
     int n_ev = 0;
@@ -92,8 +95,13 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                 for (int u = 0; u < UNR; ++u) {
                     const int p = base + u * RPW;
                     if (p < pe) {
-                        mn[u] = R::load_raw(mbase + ((long)p * 2) * D + c0);
-                        mx[u] = R::load_raw(mbase + ((long)p * 2 + 1) * D + c0);
+                        if (a.nt_kv & 2) {
+                            mn[u] = R::load_raw_nt(mbase + ((long)p * 2) * D + c0);
+                            mx[u] = R::load_raw_nt(mbase + ((long)p * 2 + 1) * D + c0);
+                        } else {
+                            mn[u] = R::load_raw(mbase + ((long)p * 2) * D + c0);
+                            mx[u] = R::load_raw(mbase + ((long)p * 2 + 1) * D + c0);
+                        }
                     } else {
                         mn[u] = R::zero_raw();
                         mx[u] = R::zero_raw();
@@ -116,22 +124,33 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
             // the unit's last slice carries the largest ticket: every other slice is already
             // running or done, so it can wait for their scores and run the selection
             if (sel_here) {
+                __builtin_amdgcn_s_setprio(3);  // the unit's attention waits on this: go first on the CU
                 gather_page_keys<kFusedThreads>(srow, a.Np, a.n_first, a.n_local, a.tag, a.spin_limit, a.err, nullptr,
                                                 s_keys);
+                mark(item, 7);
                 uint64_t *dst = a.idx_tagged + (long)unit * a.K;
                 int32_t *plain = a.idx_out ? a.idx_out + (long)unit * a.K : nullptr;
                 const uint32_t tag = a.tag;
                 select_topk_lds<kFusedThreads>(s_keys, a.Np, a.K, sh, [dst, plain, tag](int pos, int p) {
                     store_u64_agent(&dst[pos], ((uint64_t)tag << 32) | (uint32_t)p);
                     if (plain) plain[pos] = p;
-                });
+                }, [&](int ph) { mark(item, ph); });
+                __builtin_amdgcn_s_setprio(0);
                 mark(item, 3);
             }
         } else {
             // ------------------------------ attend item -----------------------------
             const int it = item - n_score;
-            int unit = it / a.S_att;
-            const int slice = it % a.S_att;
+            int unit, slice, S_att;
+            if (it < n_att_coarse) {
+                S_att = a.S_att;
+                unit = it / S_att;
+                slice = it % S_att;
+            } else {
+                S_att = a.S_att_fine;
+                unit = u_coarse + (it - n_att_coarse) / S_att;
+                slice = (it - n_att_coarse) % S_att;
+            }
             if (a.reverse) unit = a.units - 1 - unit;
             const int b = unit / a.Hq, h = unit % a.Hq, kvh = h / G;
             const ST *kb = (const ST *)a.k_cache + (long)(b * a.Hkv + kvh) * a.Tcap * D;
@@ -148,7 +167,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
 
             const int tiles_per_page = a.P / TR;
             const int n_tiles = a.K * tiles_per_page;
-            const int per = (n_tiles + a.S_att - 1) / a.S_att;
+            const int per = (n_tiles + S_att - 1) / S_att;
             const int tb = slice * per;
             const int te = (tb + per < n_tiles) ? tb + per : n_tiles;
 
@@ -157,7 +176,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
 #pragma unroll
             for (int c = 0; c < 8; ++c) o[c] = 0.f;
 
-            const bool finish = (slice == a.S_att - 1);  // largest ticket of the unit: folds the others
+            const bool finish = (slice == S_att - 1);  // largest ticket of the unit: folds the others
             for (int t = tb + wave * TPI; t < te; t += kFusedWaves * TPI) {
                 if (!finish && t + kFusedWaves * TPI >= te) fetch_next();
                 long row0[TPI];
@@ -194,8 +213,13 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                     for (int i = 0; i < RPL; ++i) {
                         const long row = row0[u] + i * RPW + rg;
                         if (row < a.T_valid) {
-                            kr[u][i] = R::load_raw(kb + row * D + c0);
-                            vr[u][i] = R::load_raw(vb + row * D + c0);
+                            if (a.nt_kv & 1) {
+                                kr[u][i] = R::load_raw_nt(kb + row * D + c0);
+                                vr[u][i] = R::load_raw_nt(vb + row * D + c0);
+                            } else {
+                                kr[u][i] = R::load_raw(kb + row * D + c0);
+                                vr[u][i] = R::load_raw(vb + row * D + c0);
+                            }
                         } else {
                             kr[u][i] = R::zero_raw();
                             vr[u][i] = R::zero_raw();
@@ -275,7 +299,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                 }
             }
             if (!finish) {
-                uint64_t *part = a.partial + ((long)unit * a.S_att + slice) * (D + 2);
+                uint64_t *part = a.partial + ((long)unit * a.S_max + slice) * (D + 2);
                 if (tid < D) {
                     publish_f32(&part[2 + tid], O, a.tag);
                     if (tid == 0) {
@@ -283,8 +307,8 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                         publish_f32(&part[1], L, a.tag);
                     }
                 }
-            } else if (a.S_att > 1 && tid < D) {
-                merge_partials(a.partial + (long)unit * a.S_att * (D + 2), a.S_att - 1, D + 2, tid, a.tag, a.spin_limit,
+            } else if (S_att > 1 && tid < D) {
+                merge_partials(a.partial + (long)unit * a.S_max * (D + 2), S_att - 1, D + 2, tid, a.tag, a.spin_limit,
                                a.err, M, L, O);
             }
             mark(item, 6);

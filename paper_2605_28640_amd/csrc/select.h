@@ -42,43 +42,21 @@ __device__ __forceinline__ float acquire_f32(const uint64_t *p, uint32_t tag, in
 // ------------------------------------------------------------------------------------
 template <int NT>
 struct SelectShared {
-    uint32_t hist[256];
-    int wave_tot[2][NT / 64];
-    int ex_gt[NT], ex_eq[NT];  // exclusive counts before (row, wave)
-    uint32_t prefix;
-    int remaining;
+    uint32_t hist[4][256];  // one histogram per radix pass, zeroed once
+    int wave_tot[NT / 64];
+    int ex_cnt[NT];  // (row, wave) table: greater-than count | equal count << 16
 };
 
-// exclusive prefix over the workgroup of (x, y)
-template <int NT>
-__device__ __forceinline__ void block_exclusive_scan2(int x, int y, int &ex, int &ey, SelectShared<NT> &sh)
+// wave64 inclusive prefix sum over ascending lanes, with DPP row shifts and row broadcasts
+__device__ __forceinline__ int wave_incl_scan_dpp(int x)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int ix = x, iy = y;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int px = __shfl_up(ix, d, 64), py = __shfl_up(iy, d, 64);
-        if (lane >= d) {
-            ix += px;
-            iy += py;
-        }
-    }
-    __syncthreads();
-    if (lane == 63) {
-        sh.wave_tot[0][wave] = ix;
-        sh.wave_tot[1][wave] = iy;
-    }
-    __syncthreads();
-    int bx = 0, by = 0;
-#pragma unroll
-    for (int w = 0; w < NT / 64; ++w) {
-        if (w < wave) {
-            bx += sh.wave_tot[0][w];
-            by += sh.wave_tot[1][w];
-        }
-    }
-    ex = bx + ix - x;
-    ey = by + iy - y;
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);  // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);  // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);  // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);  // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
+    return x;
 }
 
 __device__ __forceinline__ int lanes_below(uint64_t ballot)
@@ -86,113 +64,146 @@ __device__ __forceinline__ int lanes_below(uint64_t ballot)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
 }
 
+struct NoMark {
+    __device__ __forceinline__ void operator()(int) const {}
+};
+
 // emit(pos, p): called once per chosen candidate p with its rank pos in ascending order.
 // keys: Np keys in LDS.  Requires Np <= 64 * NT.
-template <int NT, typename Emit>
-__device__ void select_topk_lds(const uint32_t *keys, int Np, int K, SelectShared<NT> &sh, Emit emit)
+template <int NT, typename Emit, typename Mark = NoMark>
+__device__ void select_topk_lds(const uint32_t *keys, int Np, int K, SelectShared<NT> &sh, Emit emit,
+                                Mark mark = Mark())
 {
     constexpr int kSelWaves = NT / 64;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int rows = (Np + NT - 1) / NT;
-    if (tid == 0) {
-        sh.prefix = 0u;
-        sh.remaining = K;
-    }
+    for (int i = tid; i < 4 * 256; i += NT) (&sh.hist[0][0])[i] = 0u;
+    __syncthreads();
+    // every wave tracks the digits found so far and the rank still wanted (same in all waves)
+    uint32_t prefix = 0u;
+    int remaining = K;
 #pragma nounroll
     for (int pass = 3; pass >= 0; --pass) {
-        if (tid < 256) sh.hist[tid] = 0u;
-        __syncthreads();
-        const uint32_t prefix = sh.prefix;
+        uint32_t *hist = sh.hist[pass];
         const int shift = pass * 8;
         const uint32_t himask = (pass == 3) ? 0u : (0xffffffffu << (shift + 8));
-        // run-length combine equal bins of successive keys: the top bytes of scores are
-        // nearly all alike, which would serialise one LDS atomic per key
-        int run_bin = -1, run_cnt = 0;
-#pragma unroll 4
-        for (int p = tid; p < Np; p += NT) {
-            const uint32_t key = keys[p];
-            const int bin = ((key & himask) == prefix) ? (int)((key >> shift) & 255u) : -1;
-            if (bin != run_bin) {
-                if (run_bin >= 0) atomicAdd(&sh.hist[run_bin], (uint32_t)run_cnt);
-                run_bin = bin;
-                run_cnt = 0;
-            }
-            ++run_cnt;
-        }
-        if (run_bin >= 0) atomicAdd(&sh.hist[run_bin], (uint32_t)run_cnt);
-        __syncthreads();
-        if (tid < 64) {
-            // lane l owns bins 4l .. 4l+3; suffix sums from the top bin downwards
-            const uint32_t h0 = sh.hist[tid * 4], h1 = sh.hist[tid * 4 + 1], h2 = sh.hist[tid * 4 + 2],
-                           h3 = sh.hist[tid * 4 + 3];
-            const int own = (int)(h0 + h1 + h2 + h3);
-            int suf = own;  // inclusive suffix over lanes >= tid
+        for (int r0 = 0; r0 < rows; r0 += 4) {
+            // fetch a batch of keys before touching the histogram (LDS atomics in between would
+            // keep each key load waiting for the previous one)
+            uint32_t kq[4];
 #pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int o = __shfl_down(suf, d, 64);
-                if (tid + d < 64) suf += o;
+            for (int j = 0; j < 4; ++j) {
+                const int p = (r0 + j) * NT + tid;
+                kq[j] = (p < Np) ? keys[p] : 0u;
             }
-            const int above = suf - own;  // keys in bins of higher lanes
-            const int rem = sh.remaining;
-            if (above < rem && rem <= suf) {  // the K-th largest falls in this lane's bins
-                int acc = above;
-                int bin = tid * 4;
-                const uint32_t hh[4] = {h0, h1, h2, h3};
-                for (int bb = 3; bb >= 0; --bb) {
-                    if (acc + (int)hh[bb] >= rem) {
-                        bin = tid * 4 + bb;
-                        break;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int p = (r0 + j) * NT + tid;
+                const bool in = p < Np && (kq[j] & himask) == prefix;
+                const uint32_t bin = (kq[j] >> shift) & 255u;
+                if (pass == 3) {
+                    // the top bytes of scores are nearly all alike: one atomic per distinct
+                    // value in the wave instead of one per key on the same address
+                    uint64_t todo = __ballot(in);
+                    while (todo) {
+                        const int leader = (int)__builtin_ctzll(todo);
+                        const uint32_t lb = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+                        const uint64_t same = __ballot(in && bin == lb);
+                        if (lane == leader) atomicAdd(&hist[lb], (uint32_t)__popcll(same));
+                        todo &= ~same;
                     }
-                    acc += (int)hh[bb];
+                } else if (in) {
+                    atomicAdd(&hist[bin], 1u);
                 }
-                sh.prefix = prefix | ((uint32_t)bin << shift);
-                sh.remaining = rem - acc;
             }
         }
         __syncthreads();
+        // lane l owns bins 4(63-l) .. 4(63-l)+3, so a prefix sum over ascending lanes counts
+        // the keys in this lane's bins and every higher bin
+        const int b0 = 4 * (63 - lane);
+        const uint32_t h0 = hist[b0], h1 = hist[b0 + 1], h2 = hist[b0 + 2], h3 = hist[b0 + 3];
+        const int own = (int)(h0 + h1 + h2 + h3);
+        const int incl = wave_incl_scan_dpp(own);
+        const int above = incl - own;
+        int bin = 0, rem_new = 0;
+        const bool found = above < remaining && remaining <= incl;  // the wanted rank falls in this lane's bins
+        if (found) {
+            int acc = above;
+            bin = b0;
+            const uint32_t hh[4] = {h0, h1, h2, h3};
+            for (int bb = 3; bb >= 0; --bb) {
+                if (acc + (int)hh[bb] >= remaining) {
+                    bin = b0 + bb;
+                    break;
+                }
+                acc += (int)hh[bb];
+            }
+            rem_new = remaining - acc;
+        }
+        const uint64_t who = __ballot(found);  // exactly one lane
+        const int src = (int)__builtin_ctzll(who ? who : 1ull);
+        bin = __builtin_amdgcn_readlane(bin, src);
+        remaining = __builtin_amdgcn_readlane(rem_new, src);
+        prefix |= (uint32_t)bin << shift;
+        mark(8 + (3 - pass));
     }
-    const uint32_t kth = sh.prefix;    // the K-th largest key
-    const int take_eq = sh.remaining;  // how many keys equal to it are taken (lowest indices)
+    const uint32_t kth = prefix;   // the K-th largest key
+    const int take_eq = remaining;  // how many keys equal to it are taken (lowest indices)
 
     // Ascending output.  Candidate index = row * NT + wave * 64 + lane, so the order is
     // (row, wave, lane): count per (row, wave) with ballots, scan the table of counts
     // over the workgroup, and rank inside the wave with the ballot bits below the lane.
-    for (int i = 0; i < rows; ++i) {
-        const int p = i * NT + tid;
-        const uint32_t key = (p < Np) ? keys[p] : 0u;
-        const uint64_t bg = __ballot(p < Np && key > kth);
-        const uint64_t be = __ballot(p < Np && key == kth);
-        if (lane == 0) {  // entry (i, w) of the table belongs to thread i * kSelWaves + w
-            sh.ex_gt[i * kSelWaves + wave] = __popcll(bg);
-            sh.ex_eq[i * kSelWaves + wave] = __popcll(be);
+    for (int r0 = 0; r0 < rows; r0 += 4) {
+        uint32_t kq[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int p = (r0 + j) * NT + tid;
+            kq[j] = (p < Np) ? keys[p] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int p = (r0 + j) * NT + tid;
+            const uint64_t bg = __ballot(p < Np && kq[j] > kth);
+            const uint64_t be = __ballot(p < Np && kq[j] == kth);
+            if (lane == 0 && r0 + j < rows) sh.ex_cnt[(r0 + j) * kSelWaves + wave] = __popcll(bg) | (__popcll(be) << 16);
         }
     }
     __syncthreads();
-    int my_gt = 0, my_eq = 0;
-    if (tid < rows * kSelWaves) {
-        my_gt = sh.ex_gt[tid];
-        my_eq = sh.ex_eq[tid];
+    {
+        const int mine = (tid < rows * kSelWaves) ? sh.ex_cnt[tid] : 0;  // entry (i, w) belongs to thread i * waves + w
+        const int incl = wave_incl_scan_dpp(mine);
+        if (lane == 63) sh.wave_tot[wave] = incl;
+        __syncthreads();
+        int before = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w)
+            if (w < wave) before += sh.wave_tot[w];
+        if (tid < rows * kSelWaves) sh.ex_cnt[tid] = before + incl - mine;
+        __syncthreads();
     }
-    int e_gt, e_eq;
-    block_exclusive_scan2<NT>(my_gt, my_eq, e_gt, e_eq, sh);
-    if (tid < rows * kSelWaves) {
-        sh.ex_gt[tid] = e_gt;
-        sh.ex_eq[tid] = e_eq;
-    }
-    __syncthreads();
-    for (int i = 0; i < rows; ++i) {
-        const int p = i * NT + tid;
-        const uint32_t key = (p < Np) ? keys[p] : 0u;
-        const bool is_gt = p < Np && key > kth, is_eq = p < Np && key == kth;
-        const int gt_lane = lanes_below(__ballot(is_gt)), eq_lane = lanes_below(__ballot(is_eq));
-        const int gt_before = sh.ex_gt[i * kSelWaves + wave];
-        const int eq_before = sh.ex_eq[i * kSelWaves + wave];
-        const int quota = take_eq - eq_before;  // equal keys this wave-row may still take
-        if (is_gt || (is_eq && eq_lane < quota)) {
-            const int eq_taken_before = (eq_before < take_eq ? eq_before : take_eq) +
-                                        (quota > 0 ? (eq_lane < quota ? eq_lane : quota) : 0);
-            emit(gt_before + gt_lane + eq_taken_before, p);
+    mark(12);
+    for (int r0 = 0; r0 < rows; r0 += 4) {
+        uint32_t kq[4];
+        int pk[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int p = (r0 + j) * NT + tid;
+            kq[j] = (p < Np) ? keys[p] : 0u;
+            pk[j] = (r0 + j < rows) ? sh.ex_cnt[(r0 + j) * kSelWaves + wave] : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int p = (r0 + j) * NT + tid;
+            const bool is_gt = p < Np && kq[j] > kth, is_eq = p < Np && kq[j] == kth;
+            const int gt_lane = lanes_below(__ballot(is_gt)), eq_lane = lanes_below(__ballot(is_eq));
+            const int gt_before = pk[j] & 0xffff, eq_before = pk[j] >> 16;
+            const int quota = take_eq - eq_before;  // equal keys this wave-row may still take
+            if (is_gt || (is_eq && eq_lane < quota)) {
+                const int eq_taken_before = (eq_before < take_eq ? eq_before : take_eq) +
+                                            (quota > 0 ? (eq_lane < quota ? eq_lane : quota) : 0);
+                emit(gt_before + gt_lane + eq_taken_before, p);
+            }
         }
     }
 }
