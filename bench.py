@@ -31,7 +31,7 @@ def main():
     ap.add_argument("--workload", default="C3", choices=["C3", "C2"])
     ap.add_argument("--budget", type=float, default=1 / 16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=3)
+    ap.add_argument("--cpu-steps", type=int, default=512)
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB device copy (the known-size kernel that scales "

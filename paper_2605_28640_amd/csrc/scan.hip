@@ -16,6 +16,8 @@
 //      stores the rounded states into the cache.
 // Inputs are read once and outputs written once: 12 bytes per channel-token for a
 // bf16 cache.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace rs {
@@ -42,11 +44,16 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
     const int rg = lane / LPR;
     const int c0 = (lane % LPR) * 8;
 
+    // persistent workgroups: each keeps taking the next chunk until none is left
+    const int total = BH * n_chunks;
+    for (;;) {
     int ticket = blockIdx.x;
     if (n_chunks > 1) {
+        __syncthreads();  // the previous chunk's LDS traffic is over
         if (tid == 0) s_ticket = (int)atomicAdd(&ctrl[kCtrlTicket], 1u);
         __syncthreads();
         ticket = s_ticket;
+        if (ticket >= total) break;
     }
     const int j = ticket / BH;   // chunk index along T
     const int bh = ticket % BH;  // consecutive tickets walk the heads first
@@ -211,9 +218,11 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         }
     }
 
+    if (n_chunks == 1) break;
+    }  // chunk loop
+
     if (n_chunks > 1 && tid == 0) {
-        const uint32_t total = (uint32_t)BH * (uint32_t)n_chunks;
-        if (atomicAdd(&ctrl[kCtrlDone], 1u) == total - 1u) {  // last one out resets the counters
+        if (atomicAdd(&ctrl[kCtrlDone], 1u) == gridDim.x - 1u) {  // last workgroup out resets the counters
             atomicExch(&ctrl[kCtrlTicket], 0u);
             atomicExch(&ctrl[kCtrlDone], 0u);
         }
@@ -256,7 +265,21 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
     constexpr int NW = 8;
     constexpr int CHUNK = NW * (64 / (D / 8)) * NT;
     const int n_chunks = (int)((T_new + CHUNK - 1) / CHUNK);
-    rat_scan_chunk_kernel<ST, D, NT, NW><<<dim3((unsigned)(BH * n_chunks)), dim3(NW * 64), 0, stream>>>(
+    long grid = (long)BH * n_chunks;
+    if (n_chunks > 1) {
+        static int per_cu = 0, cus = 0;  // resident workgroups of this kernel
+        if (per_cu == 0) {
+            int dev = 0, n = 0;
+            (void)hipGetDevice(&dev);
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, rat_scan_chunk_kernel<ST, D, NT, NW>, NW * 64, 0) != hipSuccess || n < 1) n = 1;
+            per_cu = n;
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        }
+        const char *e = std::getenv("RATSPARSE_SCAN_GRID");
+        const long want = e ? std::atol(e) : (long)per_cu * cus;
+        if (grid > want) grid = want;
+    }
+    rat_scan_chunk_kernel<ST, D, NT, NW><<<dim3((unsigned)grid), dim3(NW * 64), 0, stream>>>(
         (const ST *)k, (const ST *)v, g, state_k, state_v, (ST *)k_cache, (ST *)v_cache, BH, T_new,
         t0, Tcap, n_chunks, ctrl, rec, tag, spin_limit);
     return 0;
