@@ -152,11 +152,14 @@ def main():
     mean_bytes = sum(bytes_per_step) / len(bytes_per_step)
     mean_fused_ms = sum(fused_ms) / len(fused_ms)
     achieved = mean_bytes / (mean_fused_ms * 1e-3)
+    # HBM bytes per launch from the committed rocprofv3 counter summary of this workload
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "fused_decode_%s_traffic.json" % args.workload)
+    tpath = os.path.join(ROOT, "profiles", "decode_fused_%s_budget_1_16_hbm_traffic.md" % args.workload)
     if os.path.exists(tpath) and abs(args.budget - 1 / 16) < 1e-9:
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_step")
-    roofline = {"bound": "hbm", "kernel": "sparse_attn_decode fused = quest_score_select_kernel + decode_attend_kernel",
+        import re
+        m = re.search(r"^hbm_bytes_per_launch\s*=\s*(\d+)", open(tpath).read(), re.M)
+        traffic = int(m.group(1)) if m else None
+    roofline = {"bound": "hbm", "kernel": "decode_fused_kernel (sparse_attn_decode, fused select+attend, one launch per step)",
                 "achieved": round(achieved / 1e9, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK, 4), "traffic": traffic,
                 "algorithmic_bytes_per_step": int(mean_bytes), "mean_ms": round(mean_fused_ms, 5),

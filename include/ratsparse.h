@@ -109,7 +109,7 @@ int32_t quest_page_meta(const rs_shape *s, const void *k_cache, void *meta, int6
  *   q          [B, Hq, D] dtype
  *   idx_out    [B, Hq, K] int32, ascending
  *   scores_out [B, Hq, Np] float32 or NULL
- * Requires 1 <= K <= Np and K >= number of always-kept pages. */
+ * Requires 1 <= K <= Np <= 15360 and K >= number of always-kept pages. */
 size_t quest_select_decode_workspace_bytes(const rs_shape *s, int64_t T_valid);
 int32_t quest_select_decode(const rs_shape *s, const void *q, const void *meta,
                             int64_t T_valid, int32_t K, int32_t n_first, int32_t n_local,
@@ -142,7 +142,7 @@ int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache
  *   q         [B, Hq, T, D] dtype
  *   means_out [B, Hkv, ceil(T/block), D] float32
  *   idx_out   [B, Hq, T, K] int32, ascending, padded with -1 when fewer than K exist
- * block is a multiple of 16; ceil(T/block) <= 1024; 1 + n_first <= K <= 32. */
+ * block is a multiple of 16; ceil(T/block) <= 256; 1 + n_first <= K <= 32. */
 size_t moba_select_prefill_workspace_bytes(const rs_shape *s, int64_t T, int32_t block);
 int32_t moba_select_prefill(const rs_shape *s, const void *q, const void *k_cache, int64_t T,
                             int32_t block, int32_t K, int32_t n_first, float *means_out,
@@ -153,7 +153,9 @@ int32_t moba_select_prefill(const rs_shape *s, const void *q, const void *k_cach
  * blocks (idx [B, Hq, T, K] as written by moba_select_prefill), or causal dense
  * attention when idx == NULL.
  *   out     [B, Hq, T, D] dtype
- *   lse_out [B, Hq, T] float32 or NULL */
+ *   lse_out [B, Hq, T] float32 or NULL
+ * Runs on the bf16 matrix cores: dtype must be RS_BF16 (RS_UNSUPPORTED otherwise);
+ * ceil(T/block) <= 256 when idx != NULL; T < 2^27. */
 size_t sparse_attn_prefill_workspace_bytes(const rs_shape *s, int64_t T, int32_t block,
                                            int32_t K);
 int32_t sparse_attn_prefill(const rs_shape *s, const void *q, const void *k_cache,
@@ -173,7 +175,7 @@ int32_t sparse_attn_prefill(const rs_shape *s, const void *q, const void *k_cach
  *   idx_out  [B, Hkv, K_keep] int32
  *   votes_out [B, Hkv, T-W] float32 or NULL: the pooled votes
  * Decoding afterwards: rat_scan appends into kc_out / vc_out from row K_keep+W, then
- * dense sparse_attn_decode over them. */
+ * dense sparse_attn_decode over them.  dtype must be RS_BF16; pool_kernel odd, <= 63. */
 size_t snapkv_compress_workspace_bytes(const rs_shape *s, int64_t T, int32_t W);
 int32_t snapkv_compress(const rs_shape *s, const void *q_win, const void *k_cache,
                         const void *v_cache, int64_t T, int32_t W, int32_t K_keep,
