@@ -83,13 +83,17 @@ int32_t ratsparse_async_status(void *ws, void *stream);
  *                                        out: the unrounded state after the last token
  *   k_cache, v_cache [B, Hkv, Tcap, D] dtype   rows t0 .. t0+T_new-1 are written with
  *                                        the states rounded to nearest-even
+ *   meta   [B, Hkv, Tcap/P, 2, D] dtype or NULL: if given, the Quest page metadata (as
+ *                                        written by quest_page_meta) of every page that
+ *                                        holds a new row is brought up to date in the same
+ *                                        call; it must be current for the rows before t0
  * T_new = 1 is the decode-time append.  Requires 0 <= t0, t0 + T_new <= Tcap.
  * Evaluated as a chunked scan; the result equals the sequential recurrence up to
  * float32 rounding order. */
 size_t rat_scan_workspace_bytes(const rs_shape *s, int64_t T_new);
 int32_t rat_scan(const rs_shape *s, const void *k, const void *v, const float *g,
-                 float *state_k, float *state_v, void *k_cache, void *v_cache, int64_t t0,
-                 int64_t T_new, void *ws, size_t ws_bytes, void *stream);
+                 float *state_k, float *state_v, void *k_cache, void *v_cache, void *meta,
+                 int64_t t0, int64_t T_new, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- Quest block representatives: App. A.1, Quest paragraph --------------------------
  * Per page of P tokens and per channel, the minimum and maximum stored key.

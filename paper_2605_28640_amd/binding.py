@@ -37,7 +37,7 @@ SIGNATURES = {
     "ratsparse_workspace_init": (_i32, [_vp, _sz, _vp]),
     "ratsparse_async_status": (_i32, [_vp, _vp]),
     "rat_scan_workspace_bytes": (_sz, [_shp, _i64]),
-    "rat_scan": (_i32, [_shp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _sz, _vp]),
+    "rat_scan": (_i32, [_shp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _sz, _vp]),
     "quest_page_meta": (_i32, [_shp, _vp, _vp, _i64, _i64, _vp]),
     "quest_select_decode_workspace_bytes": (_sz, [_shp, _i64]),
     "quest_select_decode": (_i32, [_shp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
@@ -127,9 +127,9 @@ def rat_scan_workspace_bytes(s, T_new):
     return load().rat_scan_workspace_bytes(ctypes.byref(s), T_new)
 
 
-def rat_scan(s, k, v, g, state_k, state_v, k_cache, v_cache, t0, T_new, ws=None):
+def rat_scan(s, k, v, g, state_k, state_v, k_cache, v_cache, t0, T_new, ws=None, meta=None):
     _check(load().rat_scan(ctypes.byref(s), _ptr(k), _ptr(v), _ptr(g), _ptr(state_k), _ptr(state_v),
-                           _ptr(k_cache), _ptr(v_cache), t0, T_new, ws.ptr if ws else None,
+                           _ptr(k_cache), _ptr(v_cache), _ptr(meta), t0, T_new, ws.ptr if ws else None,
                            ws.nbytes if ws else 0, _stream()))
 
 

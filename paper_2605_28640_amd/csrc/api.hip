@@ -9,9 +9,10 @@
 namespace rs {
 // scan.hip
 int scan_chunk_tokens(int dtype, int D);
+bool scan_uses_step_kernel(long T_new);
 void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
-                   float *state_v, void *k_cache, void *v_cache, int BH, long T_new, long t0, long Tcap,
-                   uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit, hipStream_t stream);
+                   float *state_v, void *k_cache, void *v_cache, void *meta, int P, int BH, long T_new, long t0,
+                   long Tcap, uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit, hipStream_t stream);
 // quest.hip
 void page_meta_dispatch(int dtype, int D, const void *k_cache, void *meta, int BH, long Tcap, int P,
                         int p_begin, int n_pages, long t_end, hipStream_t stream);
@@ -198,11 +199,12 @@ size_t rat_scan_workspace_bytes(const rs_shape *s, int64_t T_new)
 }
 
 int32_t rat_scan(const rs_shape *s, const void *k, const void *v, const float *g, float *state_k,
-                 float *state_v, void *k_cache, void *v_cache, int64_t t0, int64_t T_new, void *ws,
+                 float *state_v, void *k_cache, void *v_cache, void *meta, int64_t t0, int64_t T_new, void *ws,
                  size_t ws_bytes, void *stream)
 {
-    int st = check_shape(s, false);
+    int st = check_shape(s, meta != nullptr);
     if (st != RS_OK) return st;
+    if (meta && !aligned16(meta)) return RS_INVALID_ARG;
     if (!k || !v || !g || !state_k || !state_v || !k_cache || !v_cache) return RS_INVALID_ARG;
     if (!aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(state_k) || !aligned16(state_v) ||
         !aligned16(k_cache) || !aligned16(v_cache))
@@ -214,13 +216,20 @@ int32_t rat_scan(const rs_shape *s, const void *k, const void *v, const float *g
     if (BH * n_chunks > 0x7fffffffL) return RS_UNSUPPORTED;
     uint32_t *ctrl = nullptr;
     uint64_t *rec = nullptr;
-    if (T_new > 8 && n_chunks > 1) {
+    if (!scan_uses_step_kernel(T_new) && n_chunks > 1) {
         if (!ws || !aligned16(ws) || ws_bytes < rat_scan_workspace_bytes(s, T_new)) return RS_WORKSPACE_TOO_SMALL;
         ctrl = (uint32_t *)ws;
         rec = (uint64_t *)((char *)ws + RS_WS_CTRL_BYTES);
     }
-    scan_dispatch(s->dtype, s->D, k, v, g, state_k, state_v, k_cache, v_cache, (int)BH, T_new, t0, s->Tcap, ctrl,
-                  rec, next_tag(), g_spin_limit.load(), (hipStream_t)stream);
+    const bool step = scan_uses_step_kernel(T_new);
+    scan_dispatch(s->dtype, s->D, k, v, g, state_k, state_v, k_cache, v_cache, step ? meta : nullptr, s->P, (int)BH,
+                  T_new, t0, s->Tcap, ctrl, rec, next_tag(), g_spin_limit.load(), (hipStream_t)stream);
+    if (meta && !step) {  // long runs: the pages the new rows touch are recomputed after the scan
+        const int p_begin = (int)(t0 / s->P);
+        const int p_end = (int)((t0 + T_new + s->P - 1) / s->P);
+        page_meta_dispatch(s->dtype, s->D, k_cache, meta, (int)BH, s->Tcap, s->P, p_begin, p_end - p_begin, t0 + T_new,
+                           (hipStream_t)stream);
+    }
     return launch_status();
 }
 

@@ -234,7 +234,7 @@ template <typename ST>
 __global__ __launch_bounds__(256) void rat_step_kernel(
     const ST *__restrict__ k, const ST *__restrict__ v, const float *__restrict__ g,
     float *__restrict__ state_k, float *__restrict__ state_v, ST *__restrict__ k_cache,
-    ST *__restrict__ v_cache, int BH, int D, long T_new, long t0, long Tcap)
+    ST *__restrict__ v_cache, ST *__restrict__ meta, int P, int BH, int D, long T_new, long t0, long Tcap)
 {
     const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (long)BH * D) return;
@@ -250,6 +250,19 @@ __global__ __launch_bounds__(256) void rat_step_kernel(
         const long o = (bh * Tcap + t0 + t) * D + c;
         from_f32(k_cache[o], sk);
         from_f32(v_cache[o], sv);
+        if (meta) {
+            // Quest page min/max of the stored key: a page's first row starts it, later rows fold in
+            const long row = t0 + t;
+            ST *mn = meta + ((bh * (Tcap / P) + row / P) * 2) * D + c;
+            const float x = to_f32(k_cache[o]);
+            float lo = x, hi = x;
+            if (row % P != 0) {
+                lo = fminf(to_f32(mn[0]), x);
+                hi = fmaxf(to_f32(mn[D]), x);
+            }
+            from_f32(mn[0], lo);
+            from_f32(mn[D], hi);
+        }
     }
     state_k[e] = sk;
     state_v[e] = sv;
@@ -292,20 +305,22 @@ int scan_chunk_tokens(int dtype, int D)
 }
 
 // host entry used by the C ABI (arguments already validated)
+bool scan_uses_step_kernel(long T_new) { return T_new <= 8; }
+
 void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
-                   float *state_v, void *k_cache, void *v_cache, int BH, long T_new, long t0,
+                   float *state_v, void *k_cache, void *v_cache, void *meta, int P, int BH, long T_new, long t0,
                    long Tcap, uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit,
                    hipStream_t stream)
 {
-    if (T_new <= 8) {
+    if (scan_uses_step_kernel(T_new)) {
         const long n = (long)BH * D;
         const unsigned blocks = (unsigned)((n + 255) / 256);
         if (dtype == RS_BF16)
             rat_step_kernel<bf16><<<blocks, 256, 0, stream>>>((const bf16 *)k, (const bf16 *)v, g, state_k, state_v,
-                                                             (bf16 *)k_cache, (bf16 *)v_cache, BH, D, T_new, t0, Tcap);
+                                                             (bf16 *)k_cache, (bf16 *)v_cache, (bf16 *)meta, P, BH, D, T_new, t0, Tcap);
         else
             rat_step_kernel<float><<<blocks, 256, 0, stream>>>((const float *)k, (const float *)v, g, state_k, state_v,
-                                                              (float *)k_cache, (float *)v_cache, BH, D, T_new, t0, Tcap);
+                                                              (float *)k_cache, (float *)v_cache, (float *)meta, P, BH, D, T_new, t0, Tcap);
         return;
     }
     if (dtype == RS_BF16) {

@@ -61,8 +61,7 @@ def _decode_run(rs, w, units, check_steps, budget):
     for i in range(w.steps):
         kd, vd, gd, qd = synth.decode_step(w, i)
         t = w.T + i
-        rs.rat_scan(s, to_dev(kd, "bf16"), to_dev(vd, "bf16"), to_dev(gd), sk, sv, kc, vc, t, 1, None)
-        rs.quest_page_meta(s, kc, meta, t, t + 1)
+        rs.rat_scan(s, to_dev(kd, "bf16"), to_dev(vd, "bf16"), to_dev(gd), sk, sv, kc, vc, t, 1, None, meta)
         rs.sparse_attn_decode(s, to_dev(qd, "bf16"), kc, vc, t + 1, scale, None, K, meta, 1, 1, out, None, idx, ws)
         for (b, kvh) in states:  # the oracle follows every append of its units
             osk, osv = states[(b, kvh)]

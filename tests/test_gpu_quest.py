@@ -129,6 +129,38 @@ def test_incremental_meta_equals_bulk(rs):
     np.testing.assert_array_equal(to_np(bulk), oracle.quest_page_meta(kc, 16, 200))
 
 
+def test_scan_with_meta_equals_separate_page_meta(rs):
+    """rat_scan's optional page-metadata update (prefill path and one-token appends across page
+    boundaries) leaves exactly what quest_page_meta computes from the stored cache."""
+    for dtype, D, P in (("bf16", 128, 16), ("f32", 64, 32)):
+        B, H, T0, steps = 1, 2, 300, 70
+        Tcap = 384
+        r = np.random.default_rng(11)
+        mk = lambda n: r.standard_normal((B, H, n, D)).astype(np.float32)
+        k, v = mk(T0 + steps), mk(T0 + steps)
+        if dtype == "bf16":
+            k, v = synth.to_bf16_grid(k), synth.to_bf16_grid(v)
+        g = (1 / (1 + np.exp(-(4.2 + 0.5 * r.standard_normal((B, H, T0 + steps, D)))))).astype(np.float32)
+        dt = tdtype(dtype)
+        s = rs.make_shape(B, H, H, D, Tcap, P, dt)
+        kc = torch.zeros(B, H, Tcap, D, dtype=dt, device="cuda")
+        vc = torch.zeros_like(kc)
+        sk = torch.zeros(B, H, D, device="cuda")
+        sv = torch.zeros_like(sk)
+        meta = torch.zeros(B, H, Tcap // P, 2, D, dtype=dt, device="cuda")
+        ws = rs.Workspace(rs.rat_scan_workspace_bytes(s, T0))
+        rs.rat_scan(s, to_dev(k[:, :, :T0], dtype), to_dev(v[:, :, :T0], dtype), to_dev(g[:, :, :T0]), sk, sv, kc, vc,
+                    0, T0, ws, meta)
+        for t in range(T0, T0 + steps):
+            rs.rat_scan(s, to_dev(k[:, :, t:t + 1], dtype), to_dev(v[:, :, t:t + 1], dtype), to_dev(g[:, :, t:t + 1]),
+                        sk, sv, kc, vc, t, 1, None, meta)
+        want = torch.zeros_like(meta)
+        rs.quest_page_meta(s, kc, want, 0, T0 + steps)
+        assert torch.equal(meta, want)
+        np.testing.assert_array_equal(to_np(meta), oracle.quest_page_meta(to_np(kc), P, T0 + steps))
+        ws.async_status()
+
+
 def test_exact_ties_take_the_lowest_index(rs):
     B, H, D, P, Np = 1, 2, 128, 16, 300
     r = np.random.default_rng(3)
