@@ -80,6 +80,15 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         }
     }
 
+    // first look at the previous chunk's outgoing state, issued behind the data loads so that
+    // its round trip overlaps the fold; the wait below re-polls only if it was not there yet
+    uint64_t early0 = 0, early1 = 0;
+    if (tid < D && j > 0) {
+        const uint64_t *p = rec + (((long)bh * n_chunks + (j - 1)) * 2) * D + tid;
+        early0 = load_u64_agent(p);
+        early1 = load_u64_agent(p + D);
+    }
+
     // fold own tokens: state -> a * state + b
     float a[8], bk[8], bv[8];
 #pragma unroll
@@ -154,15 +163,15 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
             Sv = state_v[bh * D + c];
         } else {
             const uint64_t *p = rec + (((long)bh * n_chunks + (j - 1)) * 2) * D + c;
-            uint64_t w0 = 0, w1 = 0;
+            uint64_t w0 = early0, w1 = early1;
             int spins = 0;
-            bool ok = false;
-            while (true) {
+            bool ok = ((uint32_t)(w0 >> 32) == tag) && ((uint32_t)(w1 >> 32) == tag);
+            while (!ok) {
+                if (++spins > spin_limit) break;
+                __builtin_amdgcn_s_sleep(2);
                 w0 = load_u64_agent(p);
                 w1 = load_u64_agent(p + D);
                 ok = ((uint32_t)(w0 >> 32) == tag) && ((uint32_t)(w1 >> 32) == tag);
-                if (ok || ++spins > spin_limit) break;
-                __builtin_amdgcn_s_sleep(2);
             }
             if (!ok) atomicExch(&ctrl[kCtrlAsyncErr], 1u);  // give up; outputs undefined
             Sk = __uint_as_float((uint32_t)w0);
