@@ -140,22 +140,28 @@ __global__ __launch_bounds__(256) void snapkv_sweep_kernel(const bf16 *__restric
     }
 }
 
-// log-sum-exp of each row over its key chunks
-__global__ void snapkv_lse_kernel(const float *__restrict__ stats, float *__restrict__ lse, int R, int n_chunks,
-                                  long rows_total)
+// log-sum-exp of each row over its key chunks: one wave per row, lanes over chunks
+__global__ __launch_bounds__(256) void snapkv_lse_kernel(const float *__restrict__ stats, float *__restrict__ lse, int R,
+                                                         int n_chunks, long rows_total)
 {
-    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long i = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     if (i >= rows_total) return;
     const long bk = i / R;
     const int r = (int)(i % R);
     float M = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, stats[((bk * n_chunks + c) * R + r) * 2]);
+    for (int c = lane; c < n_chunks; c += 64) M = fmaxf(M, stats[((bk * n_chunks + c) * R + r) * 2]);
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) M = fmaxf(M, shfl_xor_f(M, m));
     float Ls = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
+    for (int c = lane; c < n_chunks; c += 64) {
         const float mc = stats[((bk * n_chunks + c) * R + r) * 2];
         if (mc != -INFINITY) Ls += stats[((bk * n_chunks + c) * R + r) * 2 + 1] * __expf(mc - M);
     }
-    lse[i] = M + __logf(Ls);
+    // fixed butterfly order: the same bits on every run
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) Ls += shfl_xor_f(Ls, m);
+    if (lane == 0) lse[i] = M + __logf(Ls);
 }
 
 __global__ void snapkv_pool_kernel(const float *__restrict__ votes, float *__restrict__ pooled, long L, int kernel,
@@ -202,16 +208,28 @@ __global__ __launch_bounds__(kTokThreads) void snapkv_select_kernel(const float 
         const uint32_t prefix = s_prefix;
         const int shift = pass * 8;
         const uint32_t himask = (pass == 3) ? 0u : (0xffffffffu << (shift + 8));
+        // 32 keys are fetched before the histogram is touched (LDS atomics in between would keep
+        // each load waiting for the previous one); equal bins of successive keys are combined
         int run_bin = -1, run_cnt = 0;
-        for (long p = tid; p < L; p += kTokThreads) {
-            const uint32_t key = float_to_key(src[p]);
-            const int bin = ((key & himask) == prefix) ? (int)((key >> shift) & 255u) : -1;
-            if (bin != run_bin) {
-                if (run_bin >= 0) atomicAdd(&hist[run_bin], (uint32_t)run_cnt);
-                run_bin = bin;
-                run_cnt = 0;
+        for (long p0 = tid; p0 < L; p0 += 32 * kTokThreads) {
+            float x[32];
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                const long p = p0 + (long)j * kTokThreads;
+                x[j] = (p < L) ? src[p] : 0.f;
             }
-            ++run_cnt;
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                const long p = p0 + (long)j * kTokThreads;
+                const uint32_t key = float_to_key(x[j]);
+                const int bin = (p < L && (key & himask) == prefix) ? (int)((key >> shift) & 255u) : -1;
+                if (bin != run_bin) {
+                    if (run_bin >= 0) atomicAdd(&hist[run_bin], (uint32_t)run_cnt);
+                    run_bin = bin;
+                    run_cnt = 0;
+                }
+                ++run_cnt;
+            }
         }
         if (run_bin >= 0) atomicAdd(&hist[run_bin], (uint32_t)run_cnt);
         __syncthreads();
@@ -249,14 +267,23 @@ __global__ __launch_bounds__(kTokThreads) void snapkv_select_kernel(const float 
     const long per = ((L + kTokThreads / 64 - 1) / (kTokThreads / 64) + 63) / 64 * 64;
     const long p0 = wave * per;
     const long p1 = (p0 + per < L) ? p0 + per : L;
-    const long n_it = (p1 > p0) ? (p1 - p0 + 63) / 64 : 0;  // uniform over the wave
+    constexpr int CB = 16;                                               // loads in flight per lane
+    const long n_it = (p1 > p0) ? (p1 - p0 + CB * 64 - 1) / (CB * 64) : 0;  // batches of CB x 64 positions, uniform over the wave
     int n_gt = 0, n_eq = 0;
     for (long it = 0; it < n_it; ++it) {
-        const long p = p0 + it * 64 + lane;
-        const bool in = p < p1;
-        const uint32_t key = in ? float_to_key(src[p]) : 0u;
-        n_gt += __popcll(__ballot(in && key > kth));
-        n_eq += __popcll(__ballot(in && key == kth));
+        float x[CB];
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const long p = p0 + it * (CB * 64) + j * 64 + lane;
+            x[j] = (p < p1) ? src[p] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const long p = p0 + it * (CB * 64) + j * 64 + lane;
+            const uint32_t key = float_to_key(x[j]);
+            n_gt += __popcll(__ballot(p < p1 && key > kth));
+            n_eq += __popcll(__ballot(p < p1 && key == kth));
+        }
     }
     if (lane == 0) {
         s_wgt[wave] = n_gt;
@@ -269,20 +296,28 @@ __global__ __launch_bounds__(kTokThreads) void snapkv_select_kernel(const float 
         eq_before += s_weq[w2];
     }
     for (long it = 0; it < n_it; ++it) {
-        const long p = p0 + it * 64 + lane;
-        const bool in = p < p1;
-        const uint32_t key = in ? float_to_key(src[p]) : 0u;
-        const bool is_gt = in && key > kth, is_eq = in && key == kth;
-        const uint64_t bg = __ballot(is_gt), be = __ballot(is_eq);
-        const int gt_lane = __builtin_amdgcn_mbcnt_hi((uint32_t)(bg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bg, 0u));
-        const int eq_lane = __builtin_amdgcn_mbcnt_hi((uint32_t)(be >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)be, 0u));
-        const int eq_rank = eq_before + eq_lane;  // rank among all positions equal to the K-th vote
-        if (is_gt || (is_eq && eq_rank < take_eq)) {
-            const int eq_taken = (eq_rank < take_eq) ? eq_rank : take_eq;  // equal positions before this one that are kept
-            dst[gt_before + gt_lane + (is_eq ? eq_rank : eq_taken)] = (int32_t)p;
+        float x[CB];
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const long p = p0 + it * (CB * 64) + j * 64 + lane;
+            x[j] = (p < p1) ? src[p] : 0.f;
         }
-        gt_before += __popcll(bg);
-        eq_before += __popcll(be);
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const long p = p0 + it * (CB * 64) + j * 64 + lane;
+            const uint32_t key = float_to_key(x[j]);
+            const bool is_gt = p < p1 && key > kth, is_eq = p < p1 && key == kth;
+            const uint64_t bg = __ballot(is_gt), be = __ballot(is_eq);
+            const int gt_lane = __builtin_amdgcn_mbcnt_hi((uint32_t)(bg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bg, 0u));
+            const int eq_lane = __builtin_amdgcn_mbcnt_hi((uint32_t)(be >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)be, 0u));
+            const int eq_rank = eq_before + eq_lane;  // rank among all positions equal to the K-th vote
+            if (is_gt || (is_eq && eq_rank < take_eq)) {
+                const int eq_taken = (eq_rank < take_eq) ? eq_rank : take_eq;  // equal positions before this one that are kept
+                dst[gt_before + gt_lane + (is_eq ? eq_rank : eq_taken)] = (int32_t)p;
+            }
+            gt_before += __popcll(bg);
+            eq_before += __popcll(be);
+        }
     }
 }
 
@@ -353,7 +388,7 @@ int snapkv_dispatch(const rs_shape *s, const void *q_win, const void *k_cache, c
     else
         snapkv_sweep_kernel<64, true><<<grid, 256, 0, stream>>>(qw, kc, stats, nullptr, nullptr, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
     const long rows_total = BK * Ly.R;
-    snapkv_lse_kernel<<<(unsigned)((rows_total + 255) / 256), 256, 0, stream>>>(stats, lse, Ly.R, Ly.n_chunks, rows_total);
+    snapkv_lse_kernel<<<(unsigned)((rows_total + 3) / 4), 256, 0, stream>>>(stats, lse, Ly.R, Ly.n_chunks, rows_total);
     // votes exist for prefix keys only: chunks that start past the prefix are not needed
     const dim3 grid2((unsigned)((L + kSnapKeysPerWg - 1) / kSnapKeysPerWg), (unsigned)BK);
     if (s->D == 128)
