@@ -34,6 +34,17 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return u >> 16;
 }
 
+// two float32 -> packed bfloat16 pair (a in the low half), round-to-nearest-even through the
+// hardware conversion
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    bf16x2_t v;
+    v[0] = (__bf16)a;
+    v[1] = (__bf16)b;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
 // 8 consecutive channels of one row: raw registers as loaded, and their float32 view
 template <typename ST>
 struct Row8;
@@ -79,10 +90,10 @@ struct Row8<bf16> {
     __device__ __forceinline__ static void store(bf16 *p, const float (&x)[8])
     {
         uint4 r;
-        r.x = f32_to_bf16_bits(x[0]) | (f32_to_bf16_bits(x[1]) << 16);
-        r.y = f32_to_bf16_bits(x[2]) | (f32_to_bf16_bits(x[3]) << 16);
-        r.z = f32_to_bf16_bits(x[4]) | (f32_to_bf16_bits(x[5]) << 16);
-        r.w = f32_to_bf16_bits(x[6]) | (f32_to_bf16_bits(x[7]) << 16);
+        r.x = pack_bf16x2(x[0], x[1]);
+        r.y = pack_bf16x2(x[2], x[3]);
+        r.z = pack_bf16x2(x[4], x[5]);
+        r.w = pack_bf16x2(x[6], x[7]);
         *reinterpret_cast<uint4 *>(p) = r;
     }
 };
@@ -132,7 +143,7 @@ struct Row8<float> {
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16 x) { return bf16_bits_to_f32(x.bits); }
 __device__ __forceinline__ void from_f32(float &d, float x) { d = x; }
-__device__ __forceinline__ void from_f32(bf16 &d, float x) { d.bits = (uint16_t)f32_to_bf16_bits(x); }
+__device__ __forceinline__ void from_f32(bf16 &d, float x) { d.bits = __builtin_bit_cast(uint16_t, (__bf16)x); }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 

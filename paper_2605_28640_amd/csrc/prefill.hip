@@ -19,6 +19,8 @@
 // accumulators only when a row maximum moved, and masks only on steps a boundary crosses.
 #include "common.h"
 
+#include <type_traits>
+
 namespace rs {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -26,8 +28,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kMT = 128;        // query rows per workgroup tile (4 waves x 32)
 constexpr int kKT = 64;         // keys per step (two 32-key MFMA sub-tiles)
-constexpr int kPartStride = 4;  // floats before o in a partial record: [lse, -, -, -, o[D]]
 constexpr uint32_t kSlotShift = 27;
+constexpr float kLazy = 8.f;    // slack (base-2 exponent) before the softmax reference point moves
+constexpr int kMS = 2;          // partial records merged per round of loads
 
 // ------------------------------------------------------------------------------------
 // bucketing of (row, slot) pairs by picked block
@@ -54,8 +57,13 @@ __global__ __launch_bounds__(256) void prefill_count_kernel(const int32_t *__res
 }
 
 // per (batch, head): list offsets and tile offsets by block; resets the fill cursors
+// tile descriptor of the listed-row launch: block, first list entry, rows
+struct TileDesc {
+    uint32_t j, lbase, lcount, pad;
+};
+
 __global__ __launch_bounds__(256) void prefill_scan_kernel(const uint32_t *cnt, uint32_t *off, uint32_t *tile_off,
-                                                           uint32_t *cursor, int Nb)
+                                                           uint32_t *cursor, TileDesc *desc, long desc_stride, int Nb)
 {
     __shared__ uint32_t s_c[256], s_t[256];
     const int tid = threadIdx.x;
@@ -81,6 +89,16 @@ __global__ __launch_bounds__(256) void prefill_scan_kernel(const uint32_t *cnt, 
         off[bh * (Nb + 1) + tid] = s_c[tid];
         tile_off[bh * (Nb + 1) + tid] = s_t[tid];
         cursor[bh * Nb + tid] = 0u;
+        // one descriptor per tile of this block, so a tile workgroup needs a single dependent load
+        const uint32_t nt = (c + kMT - 1) / kMT;
+        for (uint32_t i = 0; i < nt; ++i) {
+            TileDesc d;
+            d.j = (uint32_t)tid;
+            d.lbase = s_c[tid] + i * kMT;
+            d.lcount = (c - i * kMT < (uint32_t)kMT) ? c - i * kMT : (uint32_t)kMT;
+            d.pad = 0u;
+            desc[bh * desc_stride + s_t[tid] + i] = d;
+        }
     }
 }
 
@@ -126,7 +144,10 @@ struct PrefillParams {
     const bf16 *q, *k_cache, *v_cache;
     const int32_t *idx;        // NULL: dense causal
     const uint32_t *off, *tile_off, *cnt, *list;
-    float *partial;            // [units][T][K][kPartStride + D]
+    const TileDesc *desc;
+    long desc_stride;
+    uint16_t *part_o;          // [units][T][K][D] bf16, channels in the accumulator's lane order
+    float *part_lse;           // [units][T][K]
     bf16 *out;
     float *lse_out;
     int Hq, Hkv, Nb, K, block, n_diag;
@@ -147,15 +168,47 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
 }
 
+// One wave-wide direct load moves 64 x 16 bytes from global memory into 1 KB of LDS, lane l
+// landing at byte 16 l of the destination; nothing passes through registers.
+__device__ __forceinline__ void load16_to_lds(const void *g, void *l)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                     (__attribute__((address_space(3))) void *)l, 16, 0, 0);
+}
+
+// K/V tiles sit in LDS unpadded (a wave-wide load fills whole rows back to back), so the bank
+// spread comes from permuting the 16-byte chunks inside each row: chunk c of row r is kept at
+// position c ^ chunk_swizzle(r).  The permutation is chosen so that (a) 16 lanes reading the
+// same chunk of 16 consecutive rows (the K operand) and (b) 32 lanes reading 64 bytes of each
+// of 4 consecutive rows (the transposed V operand) both touch every bank once.
+template <int D>
+__device__ __forceinline__ int chunk_swizzle(int row)
+{
+    if constexpr (D == 128) {
+        const int x = row & 15;
+        return ((x & 3) << 2) | (x >> 2);
+    } else {
+        const int x = (row >> 1) & 7;
+        return ((x & 1) << 2) | (x >> 1);
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_attn_kernel(const PrefillParams a)
 {
-    constexpr int NC = D / 16;   // 16-wide d chunks of the QK^T contraction
-    constexpr int NDT = D / 32;  // 32-wide d tiles of O^T
-    constexpr int LS = D + 16;   // LDS row stride (bf16): rows 8 banks apart, conflict-free transpose reads
-    constexpr int CPT = kKT * D / 8 / 256;  // 16-byte chunks per thread per tile
-    __shared__ __attribute__((aligned(16))) uint16_t sK[2][kKT * LS];
-    __shared__ __attribute__((aligned(16))) uint16_t sV[2][kKT * LS];
+    constexpr int NC = D / 16;     // 16-wide d chunks of the QK^T contraction
+    constexpr int NDT = D / 32;    // 32-wide d tiles of O^T
+    constexpr int CR = D / 8;      // 16-byte chunks per row
+    constexpr int RW = 64 / CR;    // rows one wave-wide load covers
+    constexpr int RPI = 4 * RW;    // rows one pass of the four waves covers
+    constexpr int CPT = kKT / RPI; // passes per tile (loads per thread per tile, for K and for V)
+    // two K and two V buffers as separate objects, addressed with a compile-time buffer index:
+    // the compiler then knows that a step's operand reads and its direct loads into the other
+    // buffer cannot overlap, and puts no wait between them
+    __shared__ __attribute__((aligned(1024))) uint16_t sK0[kKT * D];
+    __shared__ __attribute__((aligned(1024))) uint16_t sK1[kKT * D];
+    __shared__ __attribute__((aligned(1024))) uint16_t sV0[kKT * D];
+    __shared__ __attribute__((aligned(1024))) uint16_t sV1[kKT * D];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lq = lane & 31, h = lane >> 5;
@@ -181,23 +234,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             kv_begin = (r0 / a.block) * a.block;
             kv_end = (r0 + kMT < a.T) ? r0 + kMT : a.T;
         } else {
-            const uint32_t *to = a.tile_off + (long)unit * (a.Nb + 1);
-            if ((uint32_t)x >= to[a.Nb]) return;
-            int lo = 0, hi = a.Nb;  // largest j with to[j] <= x
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (to[mid] <= (uint32_t)x) lo = mid;
-                else hi = mid;
-            }
-            const int j = lo;
+            if ((uint32_t)x >= a.tile_off[(long)unit * (a.Nb + 1) + a.Nb]) return;
+            const uint4 dd = *reinterpret_cast<const uint4 *>(a.desc + (long)unit * a.desc_stride + x);
+            const int j = (int)dd.x;
             gathered = true;
-            const uint32_t first = ((uint32_t)x - to[j]) * kMT;
-            lbase = a.off[(long)unit * (a.Nb + 1) + j] + first;
-            const uint32_t cj = a.cnt[(long)unit * a.Nb + j];
-            lcount = (cj - first < (uint32_t)kMT) ? cj - first : (uint32_t)kMT;
+            lbase = dd.y;
+            lcount = dd.z;
             kv_begin = (long)j * a.block;
             kv_end = (kv_begin + a.block < a.T) ? kv_begin + a.block : a.T;
         }
+    }
+
+    // ---- staging: global -> LDS, 2 CPT wave-wide loads per tile and wave ----
+    // Pass i of a tile: this lane fetches 16 bytes of row RPI i + srow; the wave's four (eight)
+    // rows land contiguously.  Rows past kv_end are replaced by the tile's last valid row
+    // (finite data; their scores are masked).
+    const int srow = wave * RW + lane / CR;
+    const int gchunk = (lane % CR) ^ chunk_swizzle<D>(srow);
+    auto stage = [&](const bf16 *base, uint16_t *tile, int i, long k0) {
+        const int rem = (int)((kv_end - k0 < kKT) ? kv_end - k0 : kKT);  // valid rows, >= 1
+        const int r = (i * RPI + srow < rem) ? i * RPI + srow : rem - 1;
+        load16_to_lds(base + k0 * D + (uint32_t)(r * D + gchunk * 8), tile + (i * RPI + wave * RW) * D);
+    };
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {  // the first tile only needs the block: issue it before the row list is chased
+        stage(kb, sK0, i, kv_begin);
+        stage(vb, sV0, i, kv_begin);
     }
 
     // ---- this lane's query (a column of S^T) ----
@@ -225,6 +287,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int c = 0; c < NC; ++c) qf[c] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * c + 8 * h);
     }
 
+    // ---- operand addresses inside a tile (elements), fixed per lane ----
+    // K operand: row 32 sub + lq, chunk 2 c + h.  V operand through the transpose read: lane =
+    // 32 h + 16 dg + L supplies 8 bytes of row 32 sub + 16 c + 4 h + (L >> 2) (+ 8 for the
+    // second read) at d = 32 dt + 16 dg + 4 (L & 3).  The swizzle only depends on the row
+    // modulo 16, so sub and c enter as plain row offsets.
+    const int L = lane & 15, dg = (lane >> 4) & 1;
+    uint32_t koff[NC], voff[NDT][2];
+    {
+        const int sw = chunk_swizzle<D>(lq);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) koff[c] = (uint32_t)(lq * D + (((2 * c + h) ^ sw) * 8));
+        const int rowa = 4 * h + (L >> 2);
+#pragma unroll
+        for (int ab = 0; ab < 2; ++ab) {
+            const int sv = chunk_swizzle<D>(rowa + 8 * ab);
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt) {
+                const int cg = 4 * dt + 2 * dg + ((L & 3) >> 1);
+                voff[dt][ab] = (uint32_t)((rowa + 8 * ab) * D + ((cg ^ sv) * 8) + 4 * (L & 1));
+            }
+        }
+    }
+
     f32x16 oacc[NDT];
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt)
@@ -234,67 +319,78 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const float cs = a.scale * 1.4426950408889634f;
     float m = -INFINITY, l = 0.f;
 
-    // global -> registers -> LDS staging of one K/V tile (rows past kv_end are zero)
-    uint4 kst[CPT], vst[CPT];
-    auto fetch = [&](long k0) {
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            const int ch = i * 256 + tid;
-            const int key = ch / (D / 8), d0 = (ch % (D / 8)) * 8;
-            kst[i] = make_uint4(0u, 0u, 0u, 0u);
-            vst[i] = kst[i];
-            if (k0 + key < kv_end) {
-                kst[i] = *reinterpret_cast<const uint4 *>(kb + (k0 + key) * D + d0);
-                vst[i] = *reinterpret_cast<const uint4 *>(vb + (k0 + key) * D + d0);
-            }
-        }
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            const int ch = i * 256 + tid;
-            const int key = ch / (D / 8), d0 = (ch % (D / 8)) * 8;
-            *reinterpret_cast<uint4 *>(&sK[buf][key * LS + d0]) = kst[i];
-            *reinterpret_cast<uint4 *>(&sV[buf][key * LS + d0]) = vst[i];
-        }
-    };
-
     const int n_steps = (int)((kv_end - kv_begin + kKT - 1) / kKT);
-    fetch(kv_begin);
-    stash(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's part of tile 0 is in LDS
     __syncthreads();
-    // lane decomposition for the transpose reads: lane = 32 h + 16 dg + L
-    const int L = lane & 15, dg = (lane >> 4) & 1;
 
-    for (int it = 0; it < n_steps; ++it) {
+    // One step: keys k0 .. k0 + 63 from buffer buf; with NEXT, the tile after it is staged
+    // into the other buffer, one load at a time between the matrix instructions (a wave that
+    // issues its loads in one burst stalls until the CU's vector memory path has taken them).
+    auto step = [&](auto next_tag, auto buf_tag, int it) {
+        constexpr bool NEXT = decltype(next_tag)::value;
+        constexpr int BUF = decltype(buf_tag)::value;
         const long k0 = kv_begin + (long)it * kKT;
-        const int buf = it & 1;
-        if (it + 1 < n_steps) fetch(k0 + kKT);  // next tile's loads fly during this tile's math
+        const uint16_t *cK = BUF ? sK1 : sK0, *cV = BUF ? sV1 : sV0;
+        uint16_t *nK = BUF ? sK0 : sK1, *nV = BUF ? sV0 : sV1;
+        const long kn = k0 + kKT;
 
-        if (k0 <= wave_last) {
-            // S^T[key][query] = sum_d K[key][d] Q[query][d], two 32-key sub-tiles
+        if (k0 > wave_last) {
+            if constexpr (NEXT) {
+#pragma unroll
+                for (int i = 0; i < CPT; ++i) {
+                    stage(kb, nK, i, kn);
+                    stage(vb, nV, i, kn);
+                }
+            }
+        } else {
+            // S^T[key][query] = sum_d K[key][d] Q[query][d], two 32-key sub-tiles; consecutive
+            // matrix instructions go to different accumulators (a dependent one issued back to
+            // back waits for the previous result)
             f32x16 sacc[2];
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
+            for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) sacc[sub][v] = 0.f;
 #pragma unroll
-                for (int c = 0; c < NC; ++c) {
-                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&sK[buf][(32 * sub + lq) * LS + 16 * c + 8 * h]);
+            for (int c = 0; c < NC; ++c) {
+                if constexpr (NEXT) {
+                    if (c % (NC / CPT) == 0) stage(kb, nK, c / (NC / CPT), kn);
+                }
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) {
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&cK[32 * sub * D + koff[c]]);
                     sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], sacc[sub], 0, 0, 0);
                 }
             }
+#ifndef RS_NO_SGB
+            // issue order for the block above: operand reads run two matrix-instruction pairs
+            // ahead of their use, the direct loads go out one at a time in between
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+            for (int g = 0; g < NC - 2; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                if (NEXT && g < CPT) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+#endif
             // masks only where a boundary crosses this step (uniform over the wave)
             const bool lane_edge = (k0 + kKT > kv_end) || (causal && (k0 + kKT - 1 > tq || k0 < own_begin));
             if (__any(lane_edge && tq >= 0)) {
+                // keys of this step a lane may see, as offsets from k0 clamped to [-1, 64]
+                long hi_l = kv_end - 1 - k0, lo_l = 0;
+                if (causal) {
+                    hi_l = (tq - k0 < hi_l) ? tq - k0 : hi_l;
+                    lo_l = own_begin - k0;
+                }
+                const int hi = (int)((hi_l > kKT) ? kKT : ((hi_l < -1) ? -1 : hi_l)) - 4 * h;
+                const int lo = (int)((lo_l > kKT) ? kKT : ((lo_l < -1) ? -1 : lo_l)) - 4 * h;
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const long key = k0 + 32 * sub + 8 * (v / 4) + 4 * h + (v % 4);
-                        bool ok = key < kv_end;
-                        if (causal) ok = ok && (key <= tq) && (key >= own_begin);
-                        if (!ok) sacc[sub][v] = -INFINITY;
+                        const int e = 32 * sub + 8 * (v / 4) + (v % 4);  // + 4 h: folded into lo, hi
+                        if (e > hi || e < lo) sacc[sub][v] = -INFINITY;
                     }
             }
             float mx = -INFINITY;
@@ -303,9 +399,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                 for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[sub][v]);
             mx = fmaxf(mx, shfl_xor_f(mx, 32)) * cs;  // cs > 0: scaling commutes with max
-            const float m_new = fmaxf(m, mx);
+            // the reference point of the exponentials follows the running maximum lazily: it moves
+            // only when the maximum has grown by more than kLazy (p then stays below 2^kLazy,
+            // harmless in float32 and bfloat16), so the accumulators are rarely rescaled
+            const float m_cand = fmaxf(m, mx);
+            const float m_new = (m_cand - m > kLazy) ? m_cand : m;  // -inf -> finite counts as a move
             const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            if (__any(m_new != m)) {  // rescale only when some row's maximum moved
+            if (__any(m_new != m)) {
                 const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - m_safe);
                 l *= alpha;
 #pragma unroll
@@ -334,73 +434,142 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                     for (int s8 = 0; s8 < 8; ++s8) pf[c][s8] = (__bf16)sacc[sub][8 * c + s8];
 #pragma unroll
-                for (int dt = 0; dt < NDT; ++dt) {
+                for (int c = 0; c < 2; ++c) {
+                    if constexpr (NEXT) {
+                        if (2 * sub + c < CPT) stage(vb, nV, 2 * sub + c, kn);
+                    }
 #pragma unroll
-                    for (int c = 0; c < 2; ++c) {
-                        const uint16_t *vq = &sV[buf][(32 * sub + 16 * c + 4 * h + (L >> 2)) * LS + 32 * dt + 16 * dg + 4 * (L & 3)];
+                    for (int dt = 0; dt < NDT; ++dt) {
+                        const uint16_t *vq = &cV[(32 * sub + 16 * c) * D];
                         union {
                             s16x4 s[2];
                             bf16x8 f;
                         } vf;
-                        vf.s[0] = lds_read_tr16(vq);
-                        vf.s[1] = lds_read_tr16(vq + 8 * LS);
+                        vf.s[0] = lds_read_tr16(vq + voff[dt][0]);
+                        vf.s[1] = lds_read_tr16(vq + voff[dt][1]);
                         oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.f, pf[c], oacc[dt], 0, 0, 0);
                     }
                 }
             }
+#ifndef RS_NO_SGB
+            // issue order for the P V block: the transposed operand reads (two per matrix
+            // instruction) run ahead of their use, the direct loads go out in between
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+            for (int g = 0; g < 2 * NDT - 2; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                if (NEXT && g < CPT) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+#endif
         }
-        if (it + 1 < n_steps) stash(buf ^ 1);
+        if constexpr (NEXT) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads have landed
         __syncthreads();
+    };
+    {
+        using B0 = std::integral_constant<int, 0>;
+        using B1 = std::integral_constant<int, 1>;
+        int it = 0;
+        for (; it + 2 < n_steps; it += 2) {
+            step(std::true_type{}, B0{}, it);
+            step(std::true_type{}, B1{}, it + 1);
+        }
+        if (it + 2 == n_steps) {
+            step(std::true_type{}, B0{}, it);
+            step(std::false_type{}, B1{}, it + 1);
+        } else {
+            step(std::false_type{}, B0{}, it);
+        }
     }
 
     if (tq < 0) return;
     const float inv = (l > 0.f) ? 1.f / l : 0.f;
     const float lse = (l > 0.f) ? (m + __log2f(l)) * 0.6931471805599453f : -INFINITY;
+    // A partial record keeps a row's normalised output over one listed block as bf16, laid out
+    // so that each lane's 64 (D = 128) channels -- d = 32 dt + 8 g + 4 h + i -- are contiguous:
+    // half h of the record, then (dt, g, i).  The log-sum-exp stays float32 in its own array.
     if (a.idx != nullptr && gathered) {
-        float *rec = a.partial + (((long)unit * a.T + tq) * a.K + slot) * (kPartStride + D);
-        if (h == 0) rec[0] = lse;
+        const long r = ((long)unit * a.T + tq) * a.K + slot;
+        if (h == 0) a.part_lse[r] = lse;
+        uint4 *rec = reinterpret_cast<uint4 *>(a.part_o + r * D + h * (D / 2));
 #pragma unroll
-        for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int d = 32 * dt + 8 * g + 4 * h;
-                *reinterpret_cast<float4 *>(rec + kPartStride + d) =
-                    make_float4(oacc[dt][4 * g] * inv, oacc[dt][4 * g + 1] * inv, oacc[dt][4 * g + 2] * inv,
-                                oacc[dt][4 * g + 3] * inv);
-            }
+        for (int u = 0; u < 2 * NDT; ++u) {
+            const int dt = u >> 1, g0 = 2 * (u & 1);
+            uint4 w;
+            w.x = pack_bf16x2(oacc[dt][4 * g0] * inv, oacc[dt][4 * g0 + 1] * inv);
+            w.y = pack_bf16x2(oacc[dt][4 * g0 + 2] * inv, oacc[dt][4 * g0 + 3] * inv);
+            w.z = pack_bf16x2(oacc[dt][4 * g0 + 4] * inv, oacc[dt][4 * g0 + 5] * inv);
+            w.w = pack_bf16x2(oacc[dt][4 * g0 + 6] * inv, oacc[dt][4 * g0 + 7] * inv);
+            rec[u] = w;
+        }
     } else if (a.idx != nullptr) {
         // own-block tile: fold in the partials the listed-row tiles left for this row's other
-        // blocks (they ran in the previous launch) and write the final output
+        // blocks (they ran in the previous launch) and write the final output.  Slots are taken
+        // kMS at a time so that their loads are all in flight together.
         const int own = (int)(tq / a.block);
-        const int32_t *row = a.idx + ((long)unit * a.T + tq) * a.K;
-        const float *rec0 = a.partial + ((long)unit * a.T + tq) * a.K * (kPartStride + D);
+        const long rbase = ((long)unit * a.T + tq) * a.K;
+        const int32_t *row = a.idx + rbase;
+        int j0[kMS];
+#pragma unroll
+        for (int i = 0; i < kMS; ++i) j0[i] = (i < a.K) ? row[i] : -1;
         bool own_listed = false;
-        for (int k = 0; k < a.K; ++k) own_listed = own_listed || (row[k] == own);
-        const float lse_own = own_listed ? lse : -INFINITY;  // an own block that is not listed does not count
-        float M = lse_own;
-        for (int k = 0; k < a.K; ++k)
-            if (row[k] >= 0 && row[k] != own) M = fmaxf(M, rec0[(long)k * (kPartStride + D)]);
-        float wsum = (lse_own == -INFINITY) ? 0.f : __expf(lse_own - M);
-        const float w_own = wsum * inv;  // o_own = oacc * inv
 #pragma unroll
-        for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) oacc[dt][v] *= w_own;
-        for (int k = 0; k < a.K; ++k) {
-            if (row[k] < 0 || row[k] == own) continue;
-            const float *rk = rec0 + (long)k * (kPartStride + D);
-            const float w = (rk[0] == -INFINITY) ? 0.f : __expf(rk[0] - M);
-            wsum += w;
+        for (int i = 0; i < kMS; ++i) own_listed = own_listed || (j0[i] == own);
+        for (int k = kMS; k < a.K; ++k) own_listed = own_listed || (row[k] == own);
+        float M = own_listed ? lse : -INFINITY;  // an own block that is not listed does not count
+        float wsum = (M == -INFINITY) ? 0.f : 1.f;
+        {
+            const float w_own = wsum * inv;  // o_own = oacc * inv
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 o4 = *reinterpret_cast<const float4 *>(rk + kPartStride + 32 * dt + 8 * g + 4 * h);
-                    oacc[dt][4 * g] = fmaf(w, o4.x, oacc[dt][4 * g]);
-                    oacc[dt][4 * g + 1] = fmaf(w, o4.y, oacc[dt][4 * g + 1]);
-                    oacc[dt][4 * g + 2] = fmaf(w, o4.z, oacc[dt][4 * g + 2]);
-                    oacc[dt][4 * g + 3] = fmaf(w, o4.w, oacc[dt][4 * g + 3]);
+                for (int v = 0; v < 16; ++v) oacc[dt][v] *= w_own;
+        }
+        for (int kc = 0; kc < a.K; kc += kMS) {
+            float ls[kMS];
+            uint4 rc[kMS][2 * NDT];
+#pragma unroll
+            for (int i = 0; i < kMS; ++i) {
+                const int k = kc + i;
+                const int jk = (kc == 0) ? j0[i] : ((k < a.K) ? row[k] : -1);
+                const bool valid = jk >= 0 && jk != own;
+                ls[i] = -INFINITY;
+#pragma unroll
+                for (int u = 0; u < 2 * NDT; ++u) rc[i][u] = make_uint4(0u, 0u, 0u, 0u);
+                if (valid) {
+                    ls[i] = a.part_lse[rbase + k];
+                    const uint4 *rec = reinterpret_cast<const uint4 *>(a.part_o + (rbase + k) * D + h * (D / 2));
+#pragma unroll
+                    for (int u = 0; u < 2 * NDT; ++u) rc[i][u] = rec[u];
                 }
+            }
+            float Mn = M;
+#pragma unroll
+            for (int i = 0; i < kMS; ++i) Mn = fmaxf(Mn, ls[i]);
+            if (Mn == -INFINITY) continue;
+            const float al = (M == -INFINITY) ? 0.f : __expf(M - Mn);
+            M = Mn;
+            wsum *= al;
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) oacc[dt][v] *= al;
+#pragma unroll
+            for (int i = 0; i < kMS; ++i) {
+                const float w = (ls[i] == -INFINITY) ? 0.f : __expf(ls[i] - M);
+                wsum += w;
+#pragma unroll
+                for (int u = 0; u < 2 * NDT; ++u) {
+                    const int dt = u >> 1, v0 = 8 * (u & 1);
+                    const uint32_t ww[4] = {rc[i][u].x, rc[i][u].y, rc[i][u].z, rc[i][u].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        oacc[dt][v0 + 2 * e] = fmaf(w, __uint_as_float(ww[e] << 16), oacc[dt][v0 + 2 * e]);
+                        oacc[dt][v0 + 2 * e + 1] = fmaf(w, __uint_as_float(ww[e] & 0xffff0000u), oacc[dt][v0 + 2 * e + 1]);
+                    }
+                }
+            }
         }
         const float winv = (wsum > 0.f) ? 1.f / wsum : 0.f;
         bf16 *orow = a.out + ((long)unit * a.T + tq) * D;
@@ -411,8 +580,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int g = 0; g < 4; ++g) {
                 const int d = 32 * dt + 8 * g + 4 * h;
                 uint2 w2;
-                w2.x = f32_to_bf16_bits(oacc[dt][4 * g] * winv) | (f32_to_bf16_bits(oacc[dt][4 * g + 1] * winv) << 16);
-                w2.y = f32_to_bf16_bits(oacc[dt][4 * g + 2] * winv) | (f32_to_bf16_bits(oacc[dt][4 * g + 3] * winv) << 16);
+                w2.x = pack_bf16x2(oacc[dt][4 * g] * winv, oacc[dt][4 * g + 1] * winv);
+                w2.y = pack_bf16x2(oacc[dt][4 * g + 2] * winv, oacc[dt][4 * g + 3] * winv);
                 *reinterpret_cast<uint2 *>(orow + d) = w2;
             }
     } else {
@@ -424,8 +593,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int g = 0; g < 4; ++g) {
                 const int d = 32 * dt + 8 * g + 4 * h;
                 uint2 w;
-                w.x = f32_to_bf16_bits(oacc[dt][4 * g] * inv) | (f32_to_bf16_bits(oacc[dt][4 * g + 1] * inv) << 16);
-                w.y = f32_to_bf16_bits(oacc[dt][4 * g + 2] * inv) | (f32_to_bf16_bits(oacc[dt][4 * g + 3] * inv) << 16);
+                w.x = pack_bf16x2(oacc[dt][4 * g] * inv, oacc[dt][4 * g + 1] * inv);
+                w.y = pack_bf16x2(oacc[dt][4 * g + 2] * inv, oacc[dt][4 * g + 3] * inv);
                 *reinterpret_cast<uint2 *>(orow + d) = w;
             }
     }
@@ -440,8 +609,8 @@ __global__ void prefill_zero_kernel(uint32_t *p, long n)
 static size_t al256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct PrefillLayout {
-    size_t off_cnt, off_off, off_tile, off_cursor, off_list, off_partial, total;
-    long list_stride;
+    size_t off_cnt, off_off, off_tile, off_cursor, off_list, off_desc, off_part_lse, off_part_o, total;
+    long list_stride, desc_stride;
 };
 
 static PrefillLayout prefill_layout(const rs_shape *s, long T, int block, int K)
@@ -461,8 +630,13 @@ static PrefillLayout prefill_layout(const rs_shape *s, long T, int block, int K)
     L.list_stride = T * (K > 0 ? K : 0);
     L.off_list = o;
     o += al256((size_t)units * L.list_stride * 4);
-    L.off_partial = o;
-    o += al256((size_t)units * T * (K > 0 ? K : 0) * (kPartStride + s->D) * 4);
+    L.desc_stride = (T * (K > 1 ? K - 1 : 0) + kMT - 1) / kMT + Nb;  // upper bound of listed-row tiles per (batch, head)
+    L.off_desc = o;
+    o += al256((size_t)units * L.desc_stride * sizeof(TileDesc));
+    L.off_part_lse = o;
+    o += al256((size_t)units * T * (K > 0 ? K : 0) * 4);
+    L.off_part_o = o;
+    o += al256((size_t)units * T * (K > 0 ? K : 0) * s->D * 2);
     L.total = o;
     return L;
 }
@@ -493,7 +667,10 @@ int prefill_dispatch(const rs_shape *s, const void *q, const void *k_cache, cons
     p.Tcap = s->Tcap;
     p.scale = scale;
     p.off = p.tile_off = p.cnt = p.list = nullptr;
-    p.partial = nullptr;
+    p.desc = nullptr;
+    p.desc_stride = 0;
+    p.part_o = nullptr;
+    p.part_lse = nullptr;
     p.list_stride = 0;
     p.phase = 2;
     if (idx) {
@@ -506,18 +683,22 @@ int prefill_dispatch(const rs_shape *s, const void *q, const void *k_cache, cons
         prefill_zero_kernel<<<(unsigned)((ncnt + 255) / 256), 256, 0, stream>>>(cnt, ncnt);
         const dim3 gr((unsigned)((T + 255) / 256), (unsigned)units);
         prefill_count_kernel<<<gr, 256, 0, stream>>>(idx, cnt, T, block, Nb, K);
-        prefill_scan_kernel<<<(unsigned)units, 256, 0, stream>>>(cnt, off, tile_off, cursor, Nb);
+        TileDesc *desc = (TileDesc *)(ws + L.off_desc);
+        prefill_scan_kernel<<<(unsigned)units, 256, 0, stream>>>(cnt, off, tile_off, cursor, desc, L.desc_stride, Nb);
         prefill_fill_kernel<<<gr, 256, 0, stream>>>(idx, off, cursor, list, T, block, Nb, K, L.list_stride);
         p.off = off;
         p.tile_off = tile_off;
         p.cnt = cnt;
         p.list = list;
-        p.partial = (float *)(ws + L.off_partial);
+        p.desc = desc;
+        p.desc_stride = L.desc_stride;
+        p.part_o = (uint16_t *)(ws + L.off_part_o);
+        p.part_lse = (float *)(ws + L.off_part_lse);
         p.list_stride = L.list_stride;
     }
     if (idx) {
         // launch 1: tiles of listed rows leave partials; launch 2: own-block tiles fold them in
-        const long gathered_tiles = (T * (K > 1 ? K - 1 : 0) + kMT - 1) / kMT + Nb;  // upper bound per (batch, head)
+        const long gathered_tiles = p.desc_stride;  // upper bound per (batch, head)
         p.phase = 0;
         const dim3 g0((unsigned)gathered_tiles, (unsigned)units);
         if (K > 1) {
