@@ -13,10 +13,14 @@
 // Scores are formed transposed, S^T = K Q^T, so that a lane holds the keys of ONE query and
 // the softmax row reductions are in-lane plus one cross-half shuffle; O^T = V^T P^T then
 // takes P^T straight from the accumulator registers, and V^T through LDS transpose reads of
-// the row-major V tile.  K/V tiles are double-buffered in LDS: the next tile's global loads
-// are issued before the current tile's math and stored after it, one barrier per step.
-// The softmax runs in the base-2 domain (one FMA + one v_exp_f32 per score), rescales the
-// accumulators only when a row maximum moved, and masks only on steps a boundary crosses.
+// the row-major V tile.  K/V tiles are double-buffered in LDS and filled by direct
+// global -> LDS loads (no staging registers): the next tile's loads are issued one at a time
+// between the current tile's matrix instructions, one barrier per step.  Tiles are unpadded;
+// an XOR permutation of the 16-byte chunks of each row keeps both operand reads conflict-free.
+// The softmax runs in the base-2 domain (one FMA + one v_exp_f32 per score), moves its
+// reference point (and rescales the accumulators) only when a row maximum has grown by more
+// than 2^8, and masks only on steps a boundary crosses.  Partials are kept as bfloat16 o
+// (float32 log-sum-exp), in the accumulator's lane order.
 #include "common.h"
 
 #include <type_traits>
@@ -362,7 +366,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], sacc[sub], 0, 0, 0);
                 }
             }
-#ifndef RS_NO_SGB
             // issue order for the block above: operand reads run two matrix-instruction pairs
             // ahead of their use, the direct loads go out one at a time in between
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
@@ -373,7 +376,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 if (NEXT && g < CPT) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-#endif
             // masks only where a boundary crosses this step (uniform over the wave)
             const bool lane_edge = (k0 + kKT > kv_end) || (causal && (k0 + kKT - 1 > tq || k0 < own_begin));
             if (__any(lane_edge && tq >= 0)) {
@@ -451,7 +453,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     }
                 }
             }
-#ifndef RS_NO_SGB
             // issue order for the P V block: the transposed operand reads (two per matrix
             // instruction) run ahead of their use, the direct loads go out in between
             __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
@@ -462,7 +463,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 if (NEXT && g < CPT) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-#endif
         }
         if constexpr (NEXT) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads have landed
         __syncthreads();
