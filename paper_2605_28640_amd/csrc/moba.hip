@@ -117,6 +117,130 @@ __global__ __launch_bounds__(64) void moba_gate_topk_kernel(const ST *__restrict
     }
 }
 
+// ------------------------------------------------------------------------------------
+// bfloat16 queries: the gate scores of 64 query tokens against 32 blocks at a time on the
+// matrix cores, S^T = M Q^T with v_mfma_f32_32x32x16_bf16.  The float32 block means are
+// split into three bfloat16 terms (m = m1 + m2 + m3 up to 2^-24 |m|) and the three products
+// accumulate in float32, so the scores keep float32 accuracy (the top-K needs it: a block
+// mean rounded to bfloat16 would move scores by 2^-9).  A lane of the accumulator holds 16
+// blocks of ONE query; scores go to the same per-thread LDS column as in the scalar kernel
+// and the K picks are taken from there.
+// ------------------------------------------------------------------------------------
+typedef __bf16 gate_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float gate_f32x16 __attribute__((ext_vector_type(16)));
+
+template <int D>
+__global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restrict__ q, const float *__restrict__ means,
+                                                            int32_t *__restrict__ idx_out, int Hq, int Hkv, long T,
+                                                            int block, int Nb, int K, int n_first)
+{
+    constexpr int NC = D / 16;
+    // every wave works alone on 64 query tokens; several waves share a workgroup only to keep
+    // the number of workgroups (and the time to dispatch them) down
+    extern __shared__ float s_score_all[];  // [waves][Nb rounded up to 32][64]
+    const int lane = threadIdx.x & 63, lq = lane & 31, h = lane >> 5;
+    float *s_score = s_score_all + (size_t)(threadIdx.x >> 6) * ((Nb + 31) / 32 * 32) * 64;
+    const int unit = blockIdx.y;  // b * Hq + h
+    const int b = unit / Hq, hq = unit % Hq, kvh = hq / (Hq / Hkv);
+    const long t_tile = ((long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * 64;
+    const long t_last = (t_tile + 63 < T) ? t_tile + 63 : T - 1;
+    const int own_max = (t_tile < T) ? (int)(t_last / block) : -1;  // uniform over the wave; -1: nothing to do
+
+    // B operands: this lane's two query rows (tokens t_tile + lq and t_tile + 32 + lq, clamped)
+    gate_bf16x8 qf[2][NC];
+    int own_q[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const long t = t_tile + 32 * qt + lq;
+        const long tc = (t < T) ? t : T - 1;
+        own_q[qt] = (int)(tc / block);
+        const bf16 *qrow = q + ((long)unit * T + tc) * D + 8 * h;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) qf[qt][c] = *reinterpret_cast<const gate_bf16x8 *>(qrow + 16 * c);
+    }
+    const float *mbase = means + (long)(b * Hkv + kvh) * Nb * D;
+    for (int j0 = 0; j0 <= own_max; j0 += 32) {
+        gate_f32x16 acc[2];
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[qt][v] = 0.f;
+        const int jr = (j0 + lq < Nb) ? j0 + lq : Nb - 1;  // A operand row of this lane (clamped; extra rows are never read back)
+        const float *mrow = mbase + (long)jr * D + 8 * h;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const float4 x0 = *reinterpret_cast<const float4 *>(mrow + 16 * c);
+            const float4 x1 = *reinterpret_cast<const float4 *>(mrow + 16 * c + 4);
+            const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+            gate_bf16x8 m1, m2, m3;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                m1[i] = (__bf16)x[i];
+                const float r1 = x[i] - (float)m1[i];  // exact
+                m2[i] = (__bf16)r1;
+                const float r2 = r1 - (float)m2[i];    // exact
+                m3[i] = (__bf16)r2;
+            }
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+                acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m3, qf[qt][c], acc[qt], 0, 0, 0);
+                acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m2, qf[qt][c], acc[qt], 0, 0, 0);
+                acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m1, qf[qt][c], acc[qt], 0, 0, 0);
+            }
+        }
+        // accumulator value v of lane (lq, h): block j0 + 8 (v / 4) + 4 h + v % 4, query lq
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int j = j0 + 8 * (v / 4) + 4 * h + (v % 4);
+                float sc = acc[qt][v];
+                if (j == own_q[qt] || j < n_first) sc = INFINITY;  // always kept
+                s_score[j * 64 + 32 * qt + lq] = sc;
+            }
+    }
+    __syncthreads();
+    // the picks: thread = query token, candidates 0 .. own.  The sweeps run to the wave-uniform
+    // bound own_max in steps of four (rows up to the next multiple of 32 exist in LDS), so that
+    // four LDS reads are in flight at a time; entries past the thread's own block are skipped.
+    const long t = t_tile + lane;
+    const long tq = (t < T) ? t : T - 1;
+    const int own = (int)(tq / block);
+    const int avail = own + 1;
+    const int take = (K < avail) ? K : avail;
+    for (int r = 0; r < take; ++r) {
+        float best = -INFINITY;
+        int arg = -1;
+        for (int j = 0; j <= own_max; j += 4) {
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = s_score[(j + i) * 64 + lane];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool cand = (j + i <= own) && (__float_as_uint(v[i]) != kPickedBits);
+                if (cand && (arg < 0 || v[i] > best)) {
+                    best = v[i];
+                    arg = j + i;
+                }
+            }
+        }
+        if (arg >= 0) s_score[arg * 64 + lane] = __uint_as_float(kPickedBits);
+    }
+    if (t < T) {
+        int32_t *dst = idx_out + ((long)unit * T + t) * K;
+        int n = 0;
+        for (int j = 0; j <= own_max; j += 4) {
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = s_score[(j + i) * 64 + lane];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (j + i <= own && __float_as_uint(v[i]) == kPickedBits) dst[n++] = j + i;
+        }
+        for (; n < K; ++n) dst[n] = -1;
+    }
+}
+
 size_t moba_select_ws_bytes(const rs_shape *, long, int) { return RS_WS_CTRL_BYTES; }
 
 int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, long T, int block, int K,
@@ -127,6 +251,12 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     const dim3 g1((unsigned)Nb, (unsigned)(s->B * s->Hkv));
     const dim3 g2((unsigned)((T + 63) / 64), (unsigned)(s->B * s->Hq));
     const size_t lds = (size_t)Nb * 64 * 4;
+    const size_t lds_wave = (size_t)((Nb + 31) / 32 * 32) * 64 * 4;
+    // one wave per workgroup measured fastest (the per-wave LDS score table bounds occupancy,
+    // and small workgroups pack the CUs' LDS best)
+    const int wpg = 1;
+    const size_t lds_mfma = lds_wave * wpg;
+    const dim3 g3((unsigned)((T + 64 * wpg - 1) / (64 * wpg)), (unsigned)(s->B * s->Hq));
 #define RS_LAUNCH(ST, DD)                                                                                          \
     do {                                                                                                           \
         moba_block_means_kernel<ST, DD><<<g1, 256, 0, stream>>>((const ST *)k_cache, means_out, s->Tcap, T, block, Nb); \
@@ -134,8 +264,13 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
                                                                 block, Nb, K, n_first);                            \
     } while (0)
     if (s->dtype == RS_BF16) {
-        if (s->D == 128) RS_LAUNCH(bf16, 128);
-        else RS_LAUNCH(bf16, 64);
+        if (s->D == 128) {
+            moba_block_means_kernel<bf16, 128><<<g1, 256, 0, stream>>>((const bf16 *)k_cache, means_out, s->Tcap, T, block, Nb);
+            moba_gate_mfma_kernel<128><<<g3, 64 * wpg, lds_mfma, stream>>>((const bf16 *)q, means_out, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
+        } else {
+            moba_block_means_kernel<bf16, 64><<<g1, 256, 0, stream>>>((const bf16 *)k_cache, means_out, s->Tcap, T, block, Nb);
+            moba_gate_mfma_kernel<64><<<g3, 64 * wpg, lds_mfma, stream>>>((const bf16 *)q, means_out, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
+        }
     } else {
         if (s->D == 128) RS_LAUNCH(float, 128);
         else RS_LAUNCH(float, 64);
