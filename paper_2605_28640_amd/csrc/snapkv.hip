@@ -165,9 +165,10 @@ __global__ __launch_bounds__(256) void snapkv_lse_kernel(const float *__restrict
 }
 
 __global__ void snapkv_pool_kernel(const float *__restrict__ votes, float *__restrict__ pooled, long L, int kernel,
-                                   long total)
+                                   long total, uint32_t *__restrict__ sel_hist, long n_hist)
 {
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    for (long z = i; z < n_hist; z += (long)gridDim.x * blockDim.x) sel_hist[z] = 0u;  // the select's bins start at zero
     if (i >= total) return;
     const long row = i / L, p = i % L;
     const int half = kernel / 2;
@@ -179,145 +180,201 @@ __global__ void snapkv_pool_kernel(const float *__restrict__ votes, float *__res
 }
 
 // ------------------------------------------------------------------------------------
-// top-K_keep of L pooled votes per (batch, KV head), one 1024-thread workgroup each.
-// Radix select over the order-preserving keys in global memory (they stay in L2), then an
-// ordered compaction: each wave owns a contiguous range and ranks with ballots.
+// top-K_keep of L pooled votes per (batch, KV head): radix select over the order-preserving
+// keys, 8 bits per pass, spread over workgroups of 4096 positions each (one workgroup per
+// head would leave most of the chip idle at 128K positions).  Pass p histograms the keys that
+// match the bits fixed so far into 256 global bins; the next launch starts by locating the
+// bin that holds the K-th largest key (every workgroup repeats that small search instead of
+// passing it on).  After four passes the K-th key is known exactly; a count launch leaves,
+// per workgroup, how many keys are above it and equal to it, and the emit launch writes the
+// kept positions in ascending order (equal keys: lowest positions first).
 // ------------------------------------------------------------------------------------
-constexpr int kTokThreads = 1024;
+constexpr int kSelThreads = 256;
+constexpr int kSelPerThread = 16;
+constexpr int kSelSlice = kSelThreads * kSelPerThread;
 
-__global__ __launch_bounds__(kTokThreads) void snapkv_select_kernel(const float *__restrict__ pooled,
-                                                                    int32_t *__restrict__ idx_out, long L, int K_keep)
+// K-th largest key so far: the bits fixed by the first npass passes and the rank still wanted
+// inside that prefix.  Called by the 64 lanes of one wave; every lane returns the result.
+__device__ __forceinline__ void sel_resolve(const uint32_t *__restrict__ hist_bk, int npass, int K_keep,
+                                            uint32_t &prefix, int &remaining)
 {
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t s_prefix;
-    __shared__ int s_remaining;
-    __shared__ int s_wgt[kTokThreads / 64], s_weq[kTokThreads / 64];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long bk = blockIdx.x;
-    const float *src = pooled + bk * L;
-    int32_t *dst = idx_out + bk * K_keep;
-    if (K_keep == 0) return;
-    if (tid == 0) {
-        s_prefix = 0u;
-        s_remaining = K_keep;
-    }
-#pragma nounroll
-    for (int pass = 3; pass >= 0; --pass) {
-        if (tid < 256) hist[tid] = 0u;
-        __syncthreads();
-        const uint32_t prefix = s_prefix;
-        const int shift = pass * 8;
-        const uint32_t himask = (pass == 3) ? 0u : (0xffffffffu << (shift + 8));
-        // 32 keys are fetched before the histogram is touched (LDS atomics in between would keep
-        // each load waiting for the previous one); equal bins of successive keys are combined
-        int run_bin = -1, run_cnt = 0;
-        for (long p0 = tid; p0 < L; p0 += 32 * kTokThreads) {
-            float x[32];
+    const int lane = threadIdx.x & 63;
+    prefix = 0u;
+    remaining = K_keep;
+    for (int pp = 0; pp < npass; ++pp) {
+        const uint32_t *hp = hist_bk + pp * 256;
+        const uint4 hv = *reinterpret_cast<const uint4 *>(hp + lane * 4);
+        const uint32_t hh[4] = {hv.x, hv.y, hv.z, hv.w};
+        const int own = (int)(hh[0] + hh[1] + hh[2] + hh[3]);
+        int suf = own;
 #pragma unroll
-            for (int j = 0; j < 32; ++j) {
-                const long p = p0 + (long)j * kTokThreads;
-                x[j] = (p < L) ? src[p] : 0.f;
-            }
-#pragma unroll
-            for (int j = 0; j < 32; ++j) {
-                const long p = p0 + (long)j * kTokThreads;
-                const uint32_t key = float_to_key(x[j]);
-                const int bin = (p < L && (key & himask) == prefix) ? (int)((key >> shift) & 255u) : -1;
-                if (bin != run_bin) {
-                    if (run_bin >= 0) atomicAdd(&hist[run_bin], (uint32_t)run_cnt);
-                    run_bin = bin;
-                    run_cnt = 0;
-                }
-                ++run_cnt;
-            }
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_down(suf, d, 64);
+            if (lane + d < 64) suf += o;
         }
-        if (run_bin >= 0) atomicAdd(&hist[run_bin], (uint32_t)run_cnt);
-        __syncthreads();
-        if (tid < 64) {
-            const uint32_t h0 = hist[tid * 4], h1 = hist[tid * 4 + 1], h2 = hist[tid * 4 + 2], h3 = hist[tid * 4 + 3];
-            const int own = (int)(h0 + h1 + h2 + h3);
-            int suf = own;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int o = __shfl_down(suf, d, 64);
-                if (tid + d < 64) suf += o;
+        const int above = suf - own;
+        const bool mine = above < remaining && remaining <= suf;
+        int acc = above, bin = lane * 4;
+        for (int bb = 3; bb >= 0; --bb) {
+            if (acc + (int)hh[bb] >= remaining) {
+                bin = lane * 4 + bb;
+                break;
             }
-            const int above = suf - own;
-            const int rem = s_remaining;
-            if (above < rem && rem <= suf) {
-                int acc = above, bin = tid * 4;
-                const uint32_t hh[4] = {h0, h1, h2, h3};
-                for (int bb = 3; bb >= 0; --bb) {
-                    if (acc + (int)hh[bb] >= rem) {
-                        bin = tid * 4 + bb;
-                        break;
-                    }
-                    acc += (int)hh[bb];
-                }
-                s_prefix = prefix | ((uint32_t)bin << shift);
-                s_remaining = rem - acc;
-            }
+            acc += (int)hh[bb];
         }
-        __syncthreads();
+        const uint64_t who = __ballot(mine);  // exactly one lane while remaining <= candidates
+        const int src = who ? (int)__builtin_ctzll(who) : 0;
+        bin = __shfl(bin, src, 64);
+        acc = __shfl(acc, src, 64);
+        prefix |= (uint32_t)bin << (24 - 8 * pp);
+        remaining -= acc;
     }
-    const uint32_t kth = s_prefix;
-    const int take_eq = s_remaining;
+}
 
-    // wave w owns positions [w * per, (w + 1) * per), walked 64 at a time in order
-    const long per = ((L + kTokThreads / 64 - 1) / (kTokThreads / 64) + 63) / 64 * 64;
-    const long p0 = wave * per;
-    const long p1 = (p0 + per < L) ? p0 + per : L;
-    constexpr int CB = 16;                                               // loads in flight per lane
-    const long n_it = (p1 > p0) ? (p1 - p0 + CB * 64 - 1) / (CB * 64) : 0;  // batches of CB x 64 positions, uniform over the wave
-    int n_gt = 0, n_eq = 0;
-    for (long it = 0; it < n_it; ++it) {
-        float x[CB];
+// this thread's 16 keys of the slice: position slice_base + 1024 wave + 64 j + lane (a wave
+// walks its 1024 positions in order); positions past L are flagged invalid
+__device__ __forceinline__ void sel_load_keys(const float *__restrict__ src, long L, long slice_base, uint32_t *key,
+                                              uint32_t &valid)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float x[kSelPerThread];
+    valid = 0u;
 #pragma unroll
-        for (int j = 0; j < CB; ++j) {
-            const long p = p0 + it * (CB * 64) + j * 64 + lane;
-            x[j] = (p < p1) ? src[p] : 0.f;
-        }
-#pragma unroll
-        for (int j = 0; j < CB; ++j) {
-            const long p = p0 + it * (CB * 64) + j * 64 + lane;
-            const uint32_t key = float_to_key(x[j]);
-            n_gt += __popcll(__ballot(p < p1 && key > kth));
-            n_eq += __popcll(__ballot(p < p1 && key == kth));
-        }
+    for (int j = 0; j < kSelPerThread; ++j) {
+        const long p = slice_base + wave * (64 * kSelPerThread) + j * 64 + lane;
+        x[j] = (p < L) ? src[p] : 0.f;
+        if (p < L) valid |= 1u << j;
     }
-    if (lane == 0) {
-        s_wgt[wave] = n_gt;
-        s_weq[wave] = n_eq;
+#pragma unroll
+    for (int j = 0; j < kSelPerThread; ++j) key[j] = float_to_key(x[j]);
+}
+
+__global__ __launch_bounds__(kSelThreads) void snapkv_sel_hist_kernel(const float *__restrict__ pooled,
+                                                                      uint32_t *__restrict__ hist, long L, int K_keep,
+                                                                      int pass)
+{
+    __shared__ uint32_t lh[256];
+    __shared__ uint32_t s_prefix;
+    const int tid = threadIdx.x;
+    const long bk = blockIdx.y;
+    uint32_t key[kSelPerThread], valid;
+    sel_load_keys(pooled + bk * L, L, (long)blockIdx.x * kSelSlice, key, valid);
+    lh[tid] = 0u;
+    if (tid < 64) {
+        uint32_t prefix;
+        int remaining;
+        sel_resolve(hist + bk * 1024, pass, K_keep, prefix, remaining);
+        if (tid == 0) s_prefix = prefix;
     }
     __syncthreads();
-    int gt_before = 0, eq_before = 0;
-    for (int w2 = 0; w2 < wave; ++w2) {
-        gt_before += s_wgt[w2];
-        eq_before += s_weq[w2];
+    const uint32_t prefix = s_prefix;
+    const int shift = 24 - 8 * pass;
+    const uint32_t himask = (pass == 0) ? 0u : (0xffffffffu << (shift + 8));
+#pragma unroll
+    for (int j = 0; j < kSelPerThread; ++j)
+        if (((valid >> j) & 1u) && (key[j] & himask) == prefix) atomicAdd(&lh[(key[j] >> shift) & 255u], 1u);
+    __syncthreads();
+    if (lh[tid]) atomicAdd(&hist[(bk * 4 + pass) * 256 + tid], lh[tid]);
+}
+
+__global__ __launch_bounds__(kSelThreads) void snapkv_sel_count_kernel(const float *__restrict__ pooled,
+                                                                       const uint32_t *__restrict__ hist,
+                                                                       uint32_t *__restrict__ cnt, long L, int K_keep)
+{
+    __shared__ int s_gt[kSelThreads / 64], s_eq[kSelThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long bk = blockIdx.y;
+    uint32_t key[kSelPerThread], valid;
+    sel_load_keys(pooled + bk * L, L, (long)blockIdx.x * kSelSlice, key, valid);
+    uint32_t kth;
+    int take_eq;
+    sel_resolve(hist + bk * 1024, 4, K_keep, kth, take_eq);  // every wave on its own
+    int n_gt = 0, n_eq = 0;
+#pragma unroll
+    for (int j = 0; j < kSelPerThread; ++j) {
+        const bool ok = (valid >> j) & 1u;
+        n_gt += (ok && key[j] > kth) ? 1 : 0;
+        n_eq += (ok && key[j] == kth) ? 1 : 0;
     }
-    for (long it = 0; it < n_it; ++it) {
-        float x[CB];
 #pragma unroll
-        for (int j = 0; j < CB; ++j) {
-            const long p = p0 + it * (CB * 64) + j * 64 + lane;
-            x[j] = (p < p1) ? src[p] : 0.f;
+    for (int d = 32; d >= 1; d >>= 1) {
+        n_gt += __shfl_xor(n_gt, d, 64);
+        n_eq += __shfl_xor(n_eq, d, 64);
+    }
+    if (lane == 0) {
+        s_gt[wave] = n_gt;
+        s_eq[wave] = n_eq;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int g = 0, e = 0;
+        for (int w2 = 0; w2 < kSelThreads / 64; ++w2) {
+            g += s_gt[w2];
+            e += s_eq[w2];
         }
+        cnt[(bk * gridDim.x + blockIdx.x) * 2] = (uint32_t)g;
+        cnt[(bk * gridDim.x + blockIdx.x) * 2 + 1] = (uint32_t)e;
+    }
+}
+
+__global__ __launch_bounds__(kSelThreads) void snapkv_sel_emit_kernel(const float *__restrict__ pooled,
+                                                                      const uint32_t *__restrict__ hist,
+                                                                      const uint32_t *__restrict__ cnt,
+                                                                      int32_t *__restrict__ idx_out, long L, int K_keep)
+{
+    __shared__ int s_gt[kSelThreads / 64], s_eq[kSelThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long bk = blockIdx.y;
+    const long slice_base = (long)blockIdx.x * kSelSlice;
+    int32_t *dst = idx_out + bk * K_keep;
+    uint32_t key[kSelPerThread], valid;
+    sel_load_keys(pooled + bk * L, L, slice_base, key, valid);
+    uint32_t kth;
+    int take_eq;
+    sel_resolve(hist + bk * 1024, 4, K_keep, kth, take_eq);
+    // keys above / equal in the slices before this one
+    int gt_before = 0, eq_before = 0;
+    for (int sl = lane; sl < (int)blockIdx.x; sl += 64) {
+        gt_before += (int)cnt[(bk * gridDim.x + sl) * 2];
+        eq_before += (int)cnt[(bk * gridDim.x + sl) * 2 + 1];
+    }
 #pragma unroll
-        for (int j = 0; j < CB; ++j) {
-            const long p = p0 + it * (CB * 64) + j * 64 + lane;
-            const uint32_t key = float_to_key(x[j]);
-            const bool is_gt = p < p1 && key > kth, is_eq = p < p1 && key == kth;
-            const uint64_t bg = __ballot(is_gt), be = __ballot(is_eq);
-            const int gt_lane = __builtin_amdgcn_mbcnt_hi((uint32_t)(bg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bg, 0u));
-            const int eq_lane = __builtin_amdgcn_mbcnt_hi((uint32_t)(be >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)be, 0u));
-            const int eq_rank = eq_before + eq_lane;  // rank among all positions equal to the K-th vote
-            if (is_gt || (is_eq && eq_rank < take_eq)) {
-                const int eq_taken = (eq_rank < take_eq) ? eq_rank : take_eq;  // equal positions before this one that are kept
-                dst[gt_before + gt_lane + (is_eq ? eq_rank : eq_taken)] = (int32_t)p;
-            }
-            gt_before += __popcll(bg);
-            eq_before += __popcll(be);
+    for (int d = 32; d >= 1; d >>= 1) {
+        gt_before += __shfl_xor(gt_before, d, 64);
+        eq_before += __shfl_xor(eq_before, d, 64);
+    }
+    // and in the waves before this one
+    int n_gt = 0, n_eq = 0;
+#pragma unroll
+    for (int j = 0; j < kSelPerThread; ++j) {
+        const bool ok = (valid >> j) & 1u;
+        n_gt += __popcll(__ballot(ok && key[j] > kth));
+        n_eq += __popcll(__ballot(ok && key[j] == kth));
+    }
+    if (lane == 0) {
+        s_gt[wave] = n_gt;
+        s_eq[wave] = n_eq;
+    }
+    __syncthreads();
+    for (int w2 = 0; w2 < wave; ++w2) {
+        gt_before += s_gt[w2];
+        eq_before += s_eq[w2];
+    }
+#pragma unroll
+    for (int j = 0; j < kSelPerThread; ++j) {
+        const long p = slice_base + wave * (64 * kSelPerThread) + j * 64 + lane;
+        const bool ok = (valid >> j) & 1u;
+        const bool is_gt = ok && key[j] > kth, is_eq = ok && key[j] == kth;
+        const uint64_t bg = __ballot(is_gt), be = __ballot(is_eq);
+        const int gt_lane = __builtin_amdgcn_mbcnt_hi((uint32_t)(bg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bg, 0u));
+        const int eq_lane = __builtin_amdgcn_mbcnt_hi((uint32_t)(be >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)be, 0u));
+        const int eq_rank = eq_before + eq_lane;  // rank among all positions equal to the K-th vote
+        if (is_gt || (is_eq && eq_rank < take_eq)) {
+            const int eq_taken = (eq_rank < take_eq) ? eq_rank : take_eq;  // equal positions before this one that are kept
+            dst[gt_before + gt_lane + (is_eq ? eq_rank : eq_taken)] = (int32_t)p;
         }
+        gt_before += __popcll(bg);
+        eq_before += __popcll(be);
     }
 }
 
@@ -346,7 +403,8 @@ static size_t al256s(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct SnapLayout {
     int n_chunks, R;
-    size_t off_stats, off_lse, off_votes, off_pooled, total;
+    size_t off_stats, off_lse, off_votes, off_pooled, off_hist, off_cnt, total;
+    int n_slices;
 };
 
 static SnapLayout snap_layout(const rs_shape *s, long T, int W)
@@ -364,6 +422,11 @@ static SnapLayout snap_layout(const rs_shape *s, long T, int W)
     o += al256s((size_t)BK * (T - W) * 4);
     L.off_pooled = o;
     o += al256s((size_t)BK * (T - W) * 4);
+    L.n_slices = (int)((T - W + kSelSlice - 1) / kSelSlice);
+    L.off_hist = o;
+    o += al256s((size_t)BK * 4 * 256 * 4);
+    L.off_cnt = o;
+    o += al256s((size_t)BK * L.n_slices * 2 * 4);
     L.total = o;
     return L;
 }
@@ -396,8 +459,15 @@ int snapkv_dispatch(const rs_shape *s, const void *q_win, const void *k_cache, c
     else
         snapkv_sweep_kernel<64, false><<<grid2, 256, 0, stream>>>(qw, kc, nullptr, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
     const long tot = BK * L;
-    snapkv_pool_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, stream>>>(votes, pooled, L, pool_kernel, tot);
-    if (K_keep > 0) snapkv_select_kernel<<<(unsigned)BK, kTokThreads, 0, stream>>>(pooled, idx_out, L, K_keep);
+    uint32_t *sel_hist = (uint32_t *)(ws + Ly.off_hist), *sel_cnt = (uint32_t *)(ws + Ly.off_cnt);
+    snapkv_pool_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, stream>>>(votes, pooled, L, pool_kernel, tot, sel_hist, BK * 1024);
+    if (K_keep > 0) {
+        const dim3 gs((unsigned)Ly.n_slices, (unsigned)BK);
+        for (int pass = 0; pass < 4; ++pass)
+            snapkv_sel_hist_kernel<<<gs, kSelThreads, 0, stream>>>(pooled, sel_hist, L, K_keep, pass);
+        snapkv_sel_count_kernel<<<gs, kSelThreads, 0, stream>>>(pooled, sel_hist, sel_cnt, L, K_keep);
+        snapkv_sel_emit_kernel<<<gs, kSelThreads, 0, stream>>>(pooled, sel_hist, sel_cnt, idx_out, L, K_keep);
+    }
     const int cpr = s->D * 2 / 16;
     const long total = BK * (long)(K_keep + W) * cpr;
     snapkv_gather_kernel<bf16><<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(
