@@ -145,6 +145,31 @@ __device__ __forceinline__ float to_f32(bf16 x) { return bf16_bits_to_f32(x.bits
 __device__ __forceinline__ void from_f32(float &d, float x) { d = x; }
 __device__ __forceinline__ void from_f32(bf16 &d, float x) { d.bits = __builtin_bit_cast(uint16_t, (__bf16)x); }
 
+// One wave-wide direct load moves 64 x 16 bytes from global memory into 1 KB of LDS, lane l
+// landing at byte 16 l of the destination; nothing passes through registers.
+__device__ __forceinline__ void load16_to_lds(const void *g, void *l)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                     (__attribute__((address_space(3))) void *)l, 16, 0, 0);
+}
+
+// Tiles of K/V rows sit in LDS unpadded (a wave-wide load fills whole rows back to back), so the bank
+// spread comes from permuting the 16-byte chunks inside each row: chunk c of row r is kept at
+// position c ^ chunk_swizzle(r).  The permutation is chosen so that (a) 16 lanes reading the
+// same chunk of 16 consecutive rows (the K operand) and (b) 32 lanes reading 64 bytes of each
+// of 4 consecutive rows (the transposed V operand) both touch every bank once.
+template <int D>
+__device__ __forceinline__ int chunk_swizzle(int row)
+{
+    if constexpr (D == 128) {
+        const int x = row & 15;
+        return ((x & 3) << 2) | (x >> 2);
+    } else {
+        const int x = (row >> 1) & 7;
+        return ((x & 1) << 2) | (x >> 1);
+    }
+}
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 __device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, kWave); }

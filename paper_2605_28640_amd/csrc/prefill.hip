@@ -172,31 +172,6 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
 }
 
-// One wave-wide direct load moves 64 x 16 bytes from global memory into 1 KB of LDS, lane l
-// landing at byte 16 l of the destination; nothing passes through registers.
-__device__ __forceinline__ void load16_to_lds(const void *g, void *l)
-{
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                     (__attribute__((address_space(3))) void *)l, 16, 0, 0);
-}
-
-// K/V tiles sit in LDS unpadded (a wave-wide load fills whole rows back to back), so the bank
-// spread comes from permuting the 16-byte chunks inside each row: chunk c of row r is kept at
-// position c ^ chunk_swizzle(r).  The permutation is chosen so that (a) 16 lanes reading the
-// same chunk of 16 consecutive rows (the K operand) and (b) 32 lanes reading 64 bytes of each
-// of 4 consecutive rows (the transposed V operand) both touch every bank once.
-template <int D>
-__device__ __forceinline__ int chunk_swizzle(int row)
-{
-    if constexpr (D == 128) {
-        const int x = row & 15;
-        return ((x & 3) << 2) | (x >> 2);
-    } else {
-        const int x = (row >> 1) & 7;
-        return ((x & 1) << 2) | (x >> 1);
-    }
-}
-
 template <int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_attn_kernel(const PrefillParams a)
 {

@@ -10,27 +10,55 @@
 // so that a lane owns one key column and its vote is an in-lane sum over the query rows.
 #include "common.h"
 
+#include <type_traits>
+
 namespace rs {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kSnapKeysPerWg = 1024;  // keys per workgroup
-constexpr int kSnapKT = 32;           // keys per step
+constexpr int kSnapKeysPerWg = 2048;  // keys per workgroup
+constexpr int kSnapKT = 128;          // keys per step: four 32-key sub-tiles
 
-// sweep 1 (STATS = true): partial (max, sum) per (row, key chunk)
-// sweep 2 (STATS = false): votes per key from the final log-sum-exp of each row
-template <int D, bool STATS>
-__global__ __launch_bounds__(256) void snapkv_sweep_kernel(const bf16 *__restrict__ q_win,
-                                                           const bf16 *__restrict__ k_cache, float *stats,
-                                                           const float *__restrict__ lse, float *votes, int Hq,
-                                                           int Hkv, long T, long Tcap, int W, int n_chunks,
-                                                           float scale)
+// K tiles of 128 keys are double-buffered in LDS and filled by direct global -> LDS loads
+// (unpadded rows, 16-byte chunks permuted by chunk_swizzle); the next tile's loads are issued
+// between the current tile's matrix instructions.  Pass i of a tile: a lane fetches 16 bytes
+// of row RPI i + srow; rows past the end of the keys repeat the last valid row (finite data,
+// masked or never stored).
+template <int D>
+struct SnapStage {
+    static constexpr int CR = D / 8;          // 16-byte chunks per row
+    static constexpr int RW = 64 / CR;        // rows one wave-wide load covers
+    static constexpr int RPI = 4 * RW;        // rows one pass of the four waves covers
+    static constexpr int NP = kSnapKT / RPI;  // passes per tile
+    int srow, gchunk, wave;
+    __device__ __forceinline__ SnapStage()
+    {
+        const int lane = threadIdx.x & 63;
+        wave = threadIdx.x >> 6;
+        srow = wave * RW + lane / CR;
+        gchunk = (lane % CR) ^ chunk_swizzle<D>(srow);
+    }
+    // kt: first row of the tile in global memory; rem: valid rows of the tile (>= 1)
+    __device__ __forceinline__ void pass(const bf16 *kt, uint16_t *tile, int i, int rem) const
+    {
+        const int r = (i * RPI + srow < rem) ? i * RPI + srow : rem - 1;
+        load16_to_lds(kt + (uint32_t)(r * D + gchunk * 8), tile + (i * RPI + wave * RW) * D);
+    }
+};
+
+// sweep 1: partial softmax statistics (max, sum) per (query row, key chunk).  S^T = K Q^T: a
+// lane owns one query row (a column of S^T), so its max and sum are in-lane reductions plus
+// one cross-half shuffle.  Wave w holds rows 32 w .. 32 w + 31 of the 128-row tile.
+template <int D>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void snapkv_stats_kernel(
+    const bf16 *__restrict__ q_win, const bf16 *__restrict__ k_cache, float *__restrict__ stats, int Hq, int Hkv, long T,
+    long Tcap, int W, int n_chunks, float scale)
 {
     constexpr int NC = D / 16;
-    constexpr int KS = D + 8;
-    __shared__ __attribute__((aligned(16))) uint16_t sK[kSnapKT * KS];
-    __shared__ float s_vote[4][kSnapKT];
+    using Stage = SnapStage<D>;
+    __shared__ __attribute__((aligned(1024))) uint16_t sK0[kSnapKT * D];
+    __shared__ __attribute__((aligned(1024))) uint16_t sK1[kSnapKT * D];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lq = lane & 31, h = lane >> 5;
@@ -43,13 +71,26 @@ __global__ __launch_bounds__(256) void snapkv_sweep_kernel(const bf16 *__restric
     const bf16 *kb = k_cache + (long)bk * Tcap * D;
     const long kc0 = (long)chunk * kSnapKeysPerWg;
     const long kc1 = (kc0 + kSnapKeysPerWg < T) ? kc0 + kSnapKeysPerWg : T;
+    const int n_steps = (int)((kc1 - kc0 + kSnapKT - 1) / kSnapKT);
     const int n_row_tiles = (R + 127) / 128;
+    const Stage st;
+    uint32_t koff[NC];  // K operand: row lq of a sub-tile, chunk 2 c + h (elements)
+    {
+        const int sw = chunk_swizzle<D>(lq);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) koff[c] = (uint32_t)(lq * D + (((2 * c + h) ^ sw) * 8));
+    }
+    const float cs = scale * 1.4426950408889634f;  // base-2 domain
 
     for (int rt = 0; rt < n_row_tiles; ++rt) {
-        // this lane's query row (sweep 1: its column of S^T; sweep 2: operand row)
         const int r = rt * 128 + wave * 32 + lq;
         const bool r_ok = r < R;
         const int g = r_ok ? r / W : 0, w = r_ok ? r % W : 0;
+        {
+            const int rem = (int)((kc1 - kc0 < kSnapKT) ? kc1 - kc0 : kSnapKT);
+#pragma unroll
+            for (int i = 0; i < Stage::NP; ++i) st.pass(kb + kc0 * D, sK0, i, rem);
+        }
         bf16x8 qf[NC];
         {
             const bf16 *qrow = q_win + ((long)(b * Hq + kvh * G + g) * W + w) * D;
@@ -58,84 +99,218 @@ __global__ __launch_bounds__(256) void snapkv_sweep_kernel(const bf16 *__restric
         }
         const long pos = L + w;  // absolute position of the query: keys <= pos are visible
         float m = -INFINITY, l = 0.f;
-        // sweep 2: log-sum-exp and position of the 16 query rows this lane sees in S
-        float lse_v[16];
-        int w_v[16];
-        if (!STATS) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = rt * 128 + wave * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-                lse_v[v] = (rr < R) ? lse[(long)bk * R + rr] : INFINITY;  // exp(s - inf) = 0 for padding rows
-                w_v[v] = (rr < R) ? rr % W : 0;
-            }
-        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        __syncthreads();
 
-        for (long k0 = kc0; k0 < kc1; k0 += kSnapKT) {
-            __syncthreads();
-            constexpr int CHUNKS = kSnapKT * D / 8;
+        auto step = [&](auto next_tag, auto buf_tag, int it) {
+            constexpr bool NEXT = decltype(next_tag)::value;
+            constexpr int BUF = decltype(buf_tag)::value;
+            const uint16_t *cK = BUF ? sK1 : sK0;
+            uint16_t *nK = BUF ? sK0 : sK1;
+            const long k0 = kc0 + (long)it * kSnapKT;
+            const long kn = k0 + kSnapKT;
+            const int rem_n = (int)((kc1 - kn < kSnapKT) ? kc1 - kn : kSnapKT);
+            // keys of this tile a lane may see, as offsets from k0: 0 .. hi (all 128 in the bulk)
+            const long hi_l = ((pos < kc1 - 1) ? pos : kc1 - 1) - k0;
+            const bool edge = (k0 + kSnapKT > kc1) || (k0 + kSnapKT - 1 > L);  // uniform
 #pragma unroll
-            for (int i = 0; i < (CHUNKS + 255) / 256; ++i) {
-                const int ch = i * 256 + tid;
-                if (ch < CHUNKS) {
-                    const int key = ch / (D / 8), d0 = (ch % (D / 8)) * 8;
-                    uint4 kk = make_uint4(0u, 0u, 0u, 0u);
-                    if (k0 + key < kc1) kk = *reinterpret_cast<const uint4 *>(kb + (k0 + key) * D + d0);
-                    *reinterpret_cast<uint4 *>(&sK[key * KS + d0]) = kk;
+            for (int sp = 0; sp < 2; ++sp) {  // pairs of 32-key sub-tiles
+                f32x16 sacc[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sacc[u][v] = 0.f;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    if constexpr (NEXT) {
+                        constexpr int every = (2 * NC) / Stage::NP;  // matrix-instruction pairs per load
+                        if ((sp * NC + c) % every == 0) st.pass(kb + kn * D, nK, (sp * NC + c) / every, rem_n);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&cK[32 * (2 * sp + u) * D + koff[c]]);
+                        sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], sacc[u], 0, 0, 0);  // [key][row]
+                    }
                 }
-            }
-            __syncthreads();
-            f32x16 sacc;
+                if (edge) {
+                    const int hi = (int)((hi_l > kSnapKT) ? kSnapKT : ((hi_l < -1) ? -1 : hi_l)) - 4 * h;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+                    for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&sK[lq * KS + 16 * c + 8 * h]);
-                if (STATS) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], sacc, 0, 0, 0);  // [key][row]
-                else sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[c], kf, sacc, 0, 0, 0);        // [row][key]
-            }
-            if (STATS) {
+                        for (int v = 0; v < 16; ++v) {
+                            const int e = 32 * (2 * sp + u) + 8 * (v / 4) + (v % 4);  // + 4 h: folded into hi
+                            if (e > hi) sacc[u][v] = -INFINITY;
+                        }
+                }
                 float mx = -INFINITY;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const long key = k0 + 8 * (v / 4) + 4 * h + (v % 4);
-                    const bool ok = r_ok && key < kc1 && key <= pos;
-                    sacc[v] = ok ? sacc[v] * scale : -INFINITY;
-                    mx = fmaxf(mx, sacc[v]);
-                }
-                mx = fmaxf(mx, shfl_xor_f(mx, 32));
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[u][v]);
+                mx = fmaxf(mx, shfl_xor_f(mx, 32)) * cs;
                 const float m_new = fmaxf(m, mx);
                 const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
                 float psum = 0.f;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) psum += __expf(sacc[v] - m_safe);
-                psum += shfl_xor_f(psum, 32);
-                l = l * ((m == -INFINITY) ? 0.f : __expf(m - m_safe)) + psum;
-                m = m_new;
-            } else {
-                const long key = k0 + lq;  // this lane's key column
-                float vsum = 0.f;
+                for (int u = 0; u < 2; ++u)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const bool ok = key <= L + w_v[v];  // causal inside the window (always true for prefix keys)
-                    vsum += ok ? __expf(sacc[v] * scale - lse_v[v]) : 0.f;
-                }
-                vsum += shfl_xor_f(vsum, 32);
-                if (h == 0) s_vote[wave][lq] = vsum;
-                __syncthreads();
-                if (tid < kSnapKT) {
-                    const long kk = k0 + tid;
-                    if (kk < L && kk < kc1) {
-                        const float tot = (s_vote[0][tid] + s_vote[1][tid]) + (s_vote[2][tid] + s_vote[3][tid]);
-                        float *dst = votes + (long)bk * L + kk;
-                        *dst = (rt == 0) ? tot : *dst + tot;
-                    }
-                }
+                    for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(fmaf(sacc[u][v], cs, -m_safe));
+                psum += shfl_xor_f(psum, 32);
+                l = l * ((m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - m_safe)) + psum;
+                m = m_new;
+            }
+            if constexpr (NEXT) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads have landed
+            __syncthreads();
+        };
+        {
+            using B0 = std::integral_constant<int, 0>;
+            using B1 = std::integral_constant<int, 1>;
+            int it = 0;
+            for (; it + 2 < n_steps; it += 2) {
+                step(std::true_type{}, B0{}, it);
+                step(std::true_type{}, B1{}, it + 1);
+            }
+            if (it + 2 == n_steps) {
+                step(std::true_type{}, B0{}, it);
+                step(std::false_type{}, B1{}, it + 1);
+            } else {
+                step(std::false_type{}, B0{}, it);
             }
         }
-        if (STATS && r_ok && h == 0) {
-            float *st = stats + (((long)bk * n_chunks + chunk) * R + r) * 2;
-            st[0] = m;
-            st[1] = l;
+        if (r_ok && h == 0) {  // (max, sum) back in the natural-log domain
+            float *sp = stats + (((long)bk * n_chunks + chunk) * R + r) * 2;
+            sp[0] = m * 0.6931471805599453f;
+            sp[1] = l;
+        }
+    }
+}
+
+// sweep 2: the votes.  S = Q K^T: a lane owns one key column, and wave w takes the keys of
+// sub-tile w of every 128-key step against all (up to 128) query rows of the row tile, so a
+// key's vote is an in-lane sum plus one cross-half shuffle and is written straight out.  Only
+// prefix keys (< L) are stored, and every window query sees all of them: no mask is needed.
+template <int D>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void snapkv_votes_kernel(
+    const bf16 *__restrict__ q_win, const bf16 *__restrict__ k_cache, const float *__restrict__ lse,
+    float *__restrict__ votes, int Hq, int Hkv, long T, long Tcap, int W, float scale)
+{
+    constexpr int NC = D / 16;
+    using Stage = SnapStage<D>;
+    __shared__ __attribute__((aligned(1024))) uint16_t sK0[kSnapKT * D];
+    __shared__ __attribute__((aligned(1024))) uint16_t sK1[kSnapKT * D];
+
+    __shared__ __attribute__((aligned(16))) float s_lse2[128];  // row log-sum-exp, base-2 domain
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lq = lane & 31, h = lane >> 5;
+    const int chunk = blockIdx.x;
+    const int bk = blockIdx.y;  // b * Hkv + kvh
+    const int b = bk / Hkv, kvh = bk % Hkv;
+    const int G = Hq / Hkv;
+    const int R = G * W;
+    const long L = T - W;
+    const bf16 *kb = k_cache + (long)bk * Tcap * D;
+    const long kc0 = (long)chunk * kSnapKeysPerWg;
+    const long kc1 = (kc0 + kSnapKeysPerWg < L) ? kc0 + kSnapKeysPerWg : L;  // prefix keys only
+    const int n_steps = (int)((kc1 - kc0 + kSnapKT - 1) / kSnapKT);
+    const int n_row_tiles = (R + 127) / 128;
+    const Stage st;
+    uint32_t koff[NC];
+    {
+        const int sw = chunk_swizzle<D>(lq);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) koff[c] = (uint32_t)((32 * wave + lq) * D + (((2 * c + h) ^ sw) * 8));
+    }
+    const float cs = scale * 1.4426950408889634f;
+
+    for (int rt = 0; rt < n_row_tiles; ++rt) {
+        {
+            const int rem = (int)((kc1 - kc0 < kSnapKT) ? kc1 - kc0 : kSnapKT);
+#pragma unroll
+            for (int i = 0; i < Stage::NP; ++i) st.pass(kb + kc0 * D, sK0, i, rem);
+        }
+        // A operands: query rows 32 rg + lq of the row tile, rg = 0..3; and, for the 16 rows of
+        // all rows of the tile, their log-sum-exp in LDS (base-2 domain; +inf for padding rows:
+        // their votes vanish)
+        bf16x8 qf[4][NC];
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const int r = rt * 128 + rg * 32 + lq;
+            const int rc = (r < R) ? r : 0;
+            const bf16 *qrow = q_win + ((long)(b * Hq + kvh * G + rc / W) * W + rc % W) * D;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) qf[rg][c] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * c + 8 * h);
+        }
+        if (rt > 0) __syncthreads();  // the previous row tile's readers are done with s_lse2
+        if (tid < 128) {
+            const int rr = rt * 128 + tid;
+            s_lse2[tid] = (rr < R) ? lse[(long)bk * R + rr] * 1.4426950408889634f : INFINITY;
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        __syncthreads();
+
+        auto step = [&](auto next_tag, auto buf_tag, int it) {
+            constexpr bool NEXT = decltype(next_tag)::value;
+            constexpr int BUF = decltype(buf_tag)::value;
+            const uint16_t *cK = BUF ? sK1 : sK0;
+            uint16_t *nK = BUF ? sK0 : sK1;
+            const long k0 = kc0 + (long)it * kSnapKT;
+            const long kn = k0 + kSnapKT;
+            const int rem_n = (int)((kc1 - kn < kSnapKT) ? kc1 - kn : kSnapKT);
+            float vsum = 0.f;
+#pragma unroll
+            for (int rp = 0; rp < 2; ++rp) {  // pairs of 32-row groups
+                f32x16 sacc[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sacc[u][v] = 0.f;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    if constexpr (NEXT) {
+                        constexpr int every = (2 * NC) / Stage::NP;
+                        if ((rp * NC + c) % every == 0) st.pass(kb + kn * D, nK, (rp * NC + c) / every, rem_n);
+                    }
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&cK[koff[c]]);
+#pragma unroll
+                    for (int u = 0; u < 2; ++u)
+                        sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[2 * rp + u][c], kf, sacc[u], 0, 0, 0);  // [row][key]
+                }
+                // accumulator value v: row 8 (v / 4) + 4 h + v % 4 of the group
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd) {
+                        const float4 ls = *reinterpret_cast<const float4 *>(&s_lse2[(2 * rp + u) * 32 + 8 * qd + 4 * h]);
+                        vsum += __builtin_amdgcn_exp2f(fmaf(sacc[u][4 * qd], cs, -ls.x));
+                        vsum += __builtin_amdgcn_exp2f(fmaf(sacc[u][4 * qd + 1], cs, -ls.y));
+                        vsum += __builtin_amdgcn_exp2f(fmaf(sacc[u][4 * qd + 2], cs, -ls.z));
+                        vsum += __builtin_amdgcn_exp2f(fmaf(sacc[u][4 * qd + 3], cs, -ls.w));
+                    }
+            }
+            vsum += shfl_xor_f(vsum, 32);
+            const long key = k0 + 32 * wave + lq;
+            if (h == 0 && key < kc1) {
+                float *dst = votes + (long)bk * L + key;
+                *dst = (rt == 0) ? vsum : *dst + vsum;
+            }
+            if constexpr (NEXT) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+            __syncthreads();
+        };
+        {
+            using B0 = std::integral_constant<int, 0>;
+            using B1 = std::integral_constant<int, 1>;
+            int it = 0;
+            for (; it + 2 < n_steps; it += 2) {
+                step(std::true_type{}, B0{}, it);
+                step(std::true_type{}, B1{}, it + 1);
+            }
+            if (it + 2 == n_steps) {
+                step(std::true_type{}, B0{}, it);
+                step(std::false_type{}, B1{}, it + 1);
+            } else {
+                step(std::false_type{}, B0{}, it);
+            }
         }
     }
 }
@@ -447,17 +622,17 @@ int snapkv_dispatch(const rs_shape *s, const void *q_win, const void *k_cache, c
     const dim3 grid((unsigned)Ly.n_chunks, (unsigned)BK);
     const bf16 *qw = (const bf16 *)q_win, *kc = (const bf16 *)k_cache;
     if (s->D == 128)
-        snapkv_sweep_kernel<128, true><<<grid, 256, 0, stream>>>(qw, kc, stats, nullptr, nullptr, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
+        snapkv_stats_kernel<128><<<grid, 256, 0, stream>>>(qw, kc, stats, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
     else
-        snapkv_sweep_kernel<64, true><<<grid, 256, 0, stream>>>(qw, kc, stats, nullptr, nullptr, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
+        snapkv_stats_kernel<64><<<grid, 256, 0, stream>>>(qw, kc, stats, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
     const long rows_total = BK * Ly.R;
     snapkv_lse_kernel<<<(unsigned)((rows_total + 3) / 4), 256, 0, stream>>>(stats, lse, Ly.R, Ly.n_chunks, rows_total);
     // votes exist for prefix keys only: chunks that start past the prefix are not needed
     const dim3 grid2((unsigned)((L + kSnapKeysPerWg - 1) / kSnapKeysPerWg), (unsigned)BK);
     if (s->D == 128)
-        snapkv_sweep_kernel<128, false><<<grid2, 256, 0, stream>>>(qw, kc, nullptr, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
+        snapkv_votes_kernel<128><<<grid2, 256, 0, stream>>>(qw, kc, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, scale);
     else
-        snapkv_sweep_kernel<64, false><<<grid2, 256, 0, stream>>>(qw, kc, nullptr, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
+        snapkv_votes_kernel<64><<<grid2, 256, 0, stream>>>(qw, kc, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, scale);
     const long tot = BK * L;
     uint32_t *sel_hist = (uint32_t *)(ws + Ly.off_hist), *sel_cnt = (uint32_t *)(ws + Ly.off_cnt);
     snapkv_pool_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, stream>>>(votes, pooled, L, pool_kernel, tot, sel_hist, BK * 1024);
