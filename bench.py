@@ -54,7 +54,8 @@ def main():
     dev = "cuda:0"
     w = {"C3": synth.C3, "C2": synth.C2}[args.workload]
     B, Hq, Hkv, D, T, P = w.B, w.Hq, w.Hkv, w.D, w.T, w.P
-    n_steps_total = args.warmup + args.steps
+    n_cold = 0 if args.no_extra else 16  # decode steps re-timed with the caches flushed before each
+    n_steps_total = args.warmup + args.steps + n_cold
     Tcap = ((T + max(1024, n_steps_total + args.cpu_steps + 16) + P - 1) // P) * P
     K = int(round(args.budget * (T // P)))
     n_first, n_local = 1, 1
@@ -172,6 +173,45 @@ def main():
                 "min_ms": round(min(fused_ms), 5), "median_ms": round(sorted(fused_ms)[len(fused_ms) // 2], 5)}
     log("decode: %.4f ms/step wall, fused pair %.4f ms mean -> %.0f GB/s (%.1f%% of HBM peak)" %
         (ms_per_step, mean_fused_ms, achieved / 1e9, 100 * achieved / HBM_PEAK))
+
+    # ---- the machine's streaming-read ceiling (plain 16-byte loads over the 2 GiB K cache) ------------
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    probe_bytes = kc.numel() * kc.element_size()
+    for _ in range(2):
+        rs.ratsparse_probe_read(kc, probe_bytes, sink)
+    probe_ms = []
+    for _ in range(5):
+        pa, pb = ev(), ev()
+        pa.record()
+        rs.ratsparse_probe_read(kc, probe_bytes, sink)
+        pb.record()
+        torch.cuda.synchronize()
+        probe_ms.append(pa.elapsed_time(pb))
+    probe_gbs = probe_bytes / (min(probe_ms) * 1e-3) / 1e9  # best of five
+    roofline["measured_read_probe_GB/s"] = round(probe_gbs, 1)
+    roofline["frac_of_measured_read_probe"] = round(achieved / 1e9 / probe_gbs, 4)
+    log("streaming-read probe %.0f GB/s; fused launch at %.1f%% of it" % (probe_gbs, 100 * achieved / 1e9 / probe_gbs))
+
+    # ---- extra: the same step with the caches flushed before it (page metadata ~ Infinity Cache size) --
+    if not args.no_extra:
+        flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+        cold = []
+        base_i = args.warmup + args.steps
+        for j in range(n_cold):
+            flush.fill_(j & 255)
+            pr = (ev(), ev())
+            decode_step(base_i + j, pr)
+            cold.append(pr)
+        torch.cuda.synchronize()
+        if cold:
+            cms = sorted(a.elapsed_time(b) for a, b in cold)
+            cb = fused_bytes(T + base_i + n_cold // 2 + 1)
+            extra["fused_cold_cache"] = {"ms_median": round(cms[len(cms) // 2], 5), "ms_min": round(cms[0], 5),
+                                         "GB/s": round(cb / cms[len(cms) // 2] / 1e6, 1),
+                                         "frac_hbm_peak": round(cb / (cms[len(cms) // 2] * 1e-3) / HBM_PEAK, 4),
+                                         "note": "a 512 MiB fill runs before each step"}
+        del flush
+        torch.cuda.empty_cache()
 
     # ---- extra: other budgets and the dense path on the same cache (not the headline) --
     if not args.no_extra:
@@ -347,7 +387,27 @@ def main():
             want = oout if same else oracle.sparse_attn_decode(qd, hk, hv, P, t + 1, scale, gidx)[0]
             ref = np.maximum(np.abs(want).max(-1), np.sqrt((want ** 2).mean(-1)))
             worst = max(worst, float((np.abs(got - want).max(-1) / ref).max()))
+        # the same oracle step on one thread (a few steps, on a copy of the state: nothing is kept)
+        nthr = oracle.num_threads()
+        oracle.set_num_threads(1)
+        t_one, n_one = 0.0, 2
+        osk1, osv1 = osk.copy(), osv.copy()
+        for c in range(n_one):
+            i = n_steps_total + args.cpu_steps - 1 - c  # inputs of the last steps, reused
+            t = T + n_steps_total + args.cpu_steps - 1
+            kd, vd, gd, qd = steps_in[i]
+            t1 = time.perf_counter()
+            ko, vo, osk1, osv1 = oracle.rat_scan(kd, vd, gd, osk1, osv1)
+            p = t // P
+            oracle.quest_page_meta(hk[:, :, p * P:(p + 1) * P], P, t - p * P + 1)
+            Np = (t + 1 + P - 1) // P
+            sc = oracle.quest_scores(qd, hmeta, Np)
+            oidx = oracle.quest_select(sc, K, n_first, n_local)
+            oracle.sparse_attn_decode(qd, hk, hv, P, t + 1, scale, oidx)
+            t_one += time.perf_counter() - t1
+        oracle.set_num_threads(nthr)
         cpu = {"value": round(B * args.cpu_steps / t_cpu, 2), "unit": "tok/s", "cores": oracle.num_threads(),
+               "value_1_thread": round(B * n_one / t_one, 2),
                "kind": "oracle",
                "sample": "%d full decode steps of the same workload (all %d (batch, head) units: scan append, page "
                          "meta update, page scores, top-K, attention over %d pages), continuing the timed run's cache"

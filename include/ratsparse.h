@@ -74,6 +74,11 @@ int32_t ratsparse_workspace_init(void *ws, size_t ws_bytes, void *stream);
  * `ws` gave up a bounded wait (its outputs are then undefined); clears the record. */
 int32_t ratsparse_async_status(void *ws, void *stream);
 
+/* Measurement aid (no part of the method): enqueue a plain streaming read of `bytes` bytes at
+ * src (16-byte aligned device memory); sink is 4 bytes of device memory that is practically
+ * never written.  The achieved rate is the read ceiling to hold a read-bound kernel against. */
+int32_t ratsparse_probe_read(const void *src, size_t bytes, void *sink, void *stream);
+
 /* ---- Exponentially decaying memory: Sec. 2.1, Eq. 1 --------------------------------
  * For every (batch, KV head, channel):  s_t = g_t * s_{t-1} + (1 - g_t) * x_t  for the
  * T_new tokens given, for x = k and x = v with the same gate, starting from the carry.

@@ -36,6 +36,11 @@ def num_threads() -> int:
     return int(lib().ref_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """OpenMP threads used by the following calls (timing aid)."""
+    lib().ref_set_num_threads(ctypes.c_int(int(n)))
+
+
 def _f32(a):
     a = np.ascontiguousarray(a, dtype=np.float32)
     return a

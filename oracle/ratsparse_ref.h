@@ -32,6 +32,7 @@ extern "C" {
 
 /* number of threads the parallel-over-(batch,head) loops will use */
 int ref_num_threads(void);
+void ref_set_num_threads(int n);
 
 /* Round-to-nearest-even of a double straight to bfloat16 (8 significant bits,
  * float32 exponent range), returned as the float holding that value. */

@@ -18,6 +18,12 @@ int ref_num_threads(void)
 #endif
 }
 
+/* number of OpenMP threads the following calls use (timing aid; no effect on results) */
+void ref_set_num_threads(int n)
+{
+    if (n > 0) omp_set_num_threads(n);
+}
+
 /* bfloat16: 1 sign, 8 exponent, 7 stored mantissa bits => 8 significant bits, the
  * exponent range of float32.  A value x = m * 2^e with 0.5 <= |m| < 1 is rounded on
  * the grid 2^(e-8); below the smallest normal 2^-126 the grid is fixed at 2^-133.

@@ -36,6 +36,7 @@ SIGNATURES = {
     "ratsparse_version": (ctypes.c_char_p, []),
     "ratsparse_workspace_init": (_i32, [_vp, _sz, _vp]),
     "ratsparse_async_status": (_i32, [_vp, _vp]),
+    "ratsparse_probe_read": (_i32, [_vp, _sz, _vp, _vp]),
     "rat_scan_workspace_bytes": (_sz, [_shp, _i64]),
     "rat_scan": (_i32, [_shp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _sz, _vp]),
     "quest_page_meta": (_i32, [_shp, _vp, _vp, _i64, _i64, _vp]),
@@ -121,6 +122,10 @@ class Workspace:
 
     def async_status(self):
         _check(load().ratsparse_async_status(self.ptr, _stream()))
+
+
+def ratsparse_probe_read(src, nbytes, sink):
+    _check(load().ratsparse_probe_read(_ptr(src), nbytes, _ptr(sink), _stream()))
 
 
 def rat_scan_workspace_bytes(s, T_new):
