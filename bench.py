@@ -356,6 +356,11 @@ def main():
         worst = 0.0
         sel_equal = 0
         t_cpu = 0.0
+        # strict head-level hit rate (Sec. 3, H1): a head scores 1 only if its selection holds the golden position
+        # at every step; here step c's golden position is planted needle (c mod n) of the sequence
+        gold = [synth.needle_positions(w, b, 0) for b in range(B)]
+        hit_gpu = np.ones((B, Hq), dtype=bool)
+        hit_ref = np.ones((B, Hq), dtype=bool)
         idx_gpu = torch.zeros(B, Hq, K, dtype=torch.int32, device=dev)
         for c in range(args.cpu_steps):
             i = n_steps_total + c
@@ -382,6 +387,11 @@ def main():
             gidx = idx_gpu.cpu().numpy()
             same = np.array_equal(gidx, oidx)
             sel_equal += int(same)
+            for b in range(B):
+                if len(gold[b]):
+                    gp = int(gold[b][c % len(gold[b])]) // P
+                    hit_gpu[b] &= (gidx[b] == gp).any(axis=-1)
+                    hit_ref[b] &= (oidx[b] == gp).any(axis=-1)
             # (untimed) parity on identical selections: the oracle's cache rows can differ from the GPU's by
             # one bf16 ulp where the fp32 and fp64 states straddle a rounding boundary, which may flip a near-tie
             want = oout if same else oracle.sparse_attn_decode(qd, hk, hv, P, t + 1, scale, gidx)[0]
@@ -413,7 +423,9 @@ def main():
                          "meta update, page scores, top-K, attention over %d pages), continuing the timed run's cache"
                          % (args.cpu_steps, B * Hq, K),
                "seconds": round(t_cpu, 2), "gpu_vs_oracle_max_rel_err_same_selection": round(worst, 5),
-               "gpu_selection_identical_steps": "%d/%d" % (sel_equal, args.cpu_steps)}
+               "gpu_selection_identical_steps": "%d/%d" % (sel_equal, args.cpu_steps),
+               "strict_head_hit_rate": {"gpu": round(float(hit_gpu.mean()), 4), "oracle": round(float(hit_ref.mean()), 4),
+                                        "steps": args.cpu_steps, "random_selector_per_step": round(K / (T // P), 4)}}
 
     line = {
         "metric": "sparse decode tok/s + % HBM peak, OLMo2-7B-shaped layer @64K ctx, 1/16 budget",

@@ -43,6 +43,12 @@ CASES = [
     (synth.C2.scaled(Hq=8, Hkv=2), 4096 + 5, 4096 + 64, 16, 32, 1, 1),  # GQA, bf16, D=128
     (synth.C3.scaled(B=2, Hq=2, Hkv=2), 8192, 8192, 64, 8, 1, 2),     # 64-token pages
     (synth.C1.scaled(dtype="bf16"), 1000, 1024, 32, 5, 0, 0),          # D=64 bf16, nothing forced
+    # the paper's own Quest settings (App. A.1; Tables 3-4): T = 4096, 64-token pages with
+    # top-16 / 8 / 4, 16-token pages with top-4
+    (synth.C3.scaled(B=1, Hq=4, Hkv=4), 4096, 4096 + 64, 64, 16, 1, 1),
+    (synth.C3.scaled(B=1, Hq=4, Hkv=4), 4096, 4096 + 64, 64, 8, 1, 1),
+    (synth.C3.scaled(B=1, Hq=4, Hkv=4), 4096, 4096 + 64, 64, 4, 1, 1),
+    (synth.C3.scaled(B=1, Hq=4, Hkv=4), 4096, 4096 + 64, 16, 4, 1, 1),
 ]
 
 
@@ -207,3 +213,30 @@ def test_argument_errors_are_reported(rs):
     big = rs.make_shape(4, 32, 32, 128, 65536, 16, torch.bfloat16)
     with pytest.raises(rs.RatsparseError, match="workspace too small"):
         rs.sparse_attn_decode(big, t, t, t, 65536, 1.0, None, 0, None, 0, 0, t, None, None, small)
+
+
+def test_random_selector_five_seeds(rs):
+    """The random selector of the paper's H2 analysis (Sec. 3): uniform K-subsets of the pages
+    drawn on the host, five seeds, evaluated through the listed-pages mode (Eq. 4 unchanged).
+    Unsorted lists and a list that misses the newest page are legal inputs."""
+    w, kc, vc = _cache_from_oracle(synth.C2.scaled(Hq=8, Hkv=2), 4096 + 5, 4096 + 64)
+    T, Tcap, P, K = 4096 + 5, 4096 + 64, 16, 32
+    Np = -(-T // P)
+    _, _, _, q = synth.decode_step(w, 0)
+    scale = 1.0 / np.sqrt(w.D)
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tcap, P, torch.bfloat16)
+    tkc, tvc, tq = to_dev(kc, "bf16"), to_dev(vc, "bf16"), to_dev(q, "bf16")
+    ws = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, T, K))
+    for seed in range(5):
+        r = np.random.default_rng(1000 + seed)
+        ridx = np.stack([np.stack([r.choice(Np, size=K, replace=False) for _ in range(w.Hq)]) for _ in range(w.B)])
+        ridx = ridx.astype(np.int32)
+        out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.bfloat16, device="cuda")
+        lse = torch.zeros(w.B, w.Hq, device="cuda")
+        rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, to_dev(ridx), K, None, 0, 0, out, lse, None, ws)
+        want, wlse = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, ridx)
+        ok, worst = attn_close(to_np(out), want)
+        assert ok, (seed, worst)
+        np.testing.assert_allclose(to_np(lse), wlse, rtol=1e-4, atol=1e-4)
+    torch.cuda.synchronize()
+    ws.async_status()

@@ -28,6 +28,11 @@ CASES = [
     (synth.C5.scaled(B=2, Hq=2, Hkv=2, W=20), 3000, 3008, 300, 7),  # ragged rows, ragged key chunks
     (synth.C5.scaled(B=1, Hq=16, Hkv=2, D=64), 2500, 2560, 100, 1),  # 256 rows: two row tiles; no pooling
     (synth.C5.scaled(B=1, Hq=4, Hkv=4, W=8), 1200, 1216, 1192, 3),   # keep everything
+    # the paper's own SnapKV settings (App. A.1; Tables 3-4): T = 4096, a 64-token observation
+    # window, 1024 / 512 / 256 positions kept
+    (synth.C5.scaled(B=1, Hq=4, Hkv=4, W=64), 4096, 4096, 1024, 7),
+    (synth.C5.scaled(B=1, Hq=4, Hkv=4, W=64), 4096, 4096, 512, 7),
+    (synth.C5.scaled(B=1, Hq=4, Hkv=2, W=64), 4096, 4096, 256, 7),    # two heads per KV head: 128 window rows
 ]
 
 
