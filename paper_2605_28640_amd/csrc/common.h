@@ -170,6 +170,22 @@ __device__ __forceinline__ int chunk_swizzle(int row)
     }
 }
 
+// max / sum of a value with the one 32 lanes away, the same in both lanes, through
+// v_permlane32_swap (no LDS round trip): swap(x, x) leaves [low half | low half] and
+// [high half | high half]
+__device__ __forceinline__ float half_pair_max(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_pair_sum(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 __device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, kWave); }

@@ -259,6 +259,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // last key any lane of this wave may see (contiguous tiles): later steps are skipped by the wave
     const long wave_last = causal ? ((r0 + wave * 32 + 31 < a.T) ? r0 + wave * 32 + 31 : a.T - 1) : kv_end - 1;
 
+    // keys visible to this lane's query, as 32-bit offsets from kv_begin (everything for a padding
+    // lane: it never triggers the masking path, its results are dropped)
+    int vis_lo = 0, vis_hi = (int)(kv_end - kv_begin) - 1;
+    if (causal) {
+        vis_lo = (int)(own_begin - kv_begin);
+        vis_hi = (tq - kv_begin < vis_hi) ? (int)(tq - kv_begin) : vis_hi;
+    }
+    if (tq < 0) {
+        vis_lo = INT32_MIN / 2;
+        vis_hi = INT32_MAX / 2;
+    }
     bf16x8 qf[NC];
     {
         const bf16 *qrow = a.q + ((long)unit * a.T + (tq >= 0 ? tq : 0)) * D;
@@ -352,16 +363,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
             // masks only where a boundary crosses this step (uniform over the wave)
-            const bool lane_edge = (k0 + kKT > kv_end) || (causal && (k0 + kKT - 1 > tq || k0 < own_begin));
-            if (__any(lane_edge && tq >= 0)) {
-                // keys of this step a lane may see, as offsets from k0 clamped to [-1, 64]
-                long hi_l = kv_end - 1 - k0, lo_l = 0;
-                if (causal) {
-                    hi_l = (tq - k0 < hi_l) ? tq - k0 : hi_l;
-                    lo_l = own_begin - k0;
-                }
-                const int hi = (int)((hi_l > kKT) ? kKT : ((hi_l < -1) ? -1 : hi_l)) - 4 * h;
-                const int lo = (int)((lo_l > kKT) ? kKT : ((lo_l < -1) ? -1 : lo_l)) - 4 * h;
+            // (all in 32-bit offsets from kv_begin: the lane sees keys vis_lo .. vis_hi)
+            const int kr = it * kKT;
+            if (__any(kr < vis_lo || kr + kKT - 1 > vis_hi)) {
+                const int hi = ((vis_hi - kr > kKT) ? kKT : ((vis_hi - kr < -1) ? -1 : vis_hi - kr)) - 4 * h;
+                const int lo = ((vis_lo - kr > kKT) ? kKT : ((vis_lo - kr < -1) ? -1 : vis_lo - kr)) - 4 * h;
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -375,7 +381,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[sub][v]);
-            mx = fmaxf(mx, shfl_xor_f(mx, 32)) * cs;  // cs > 0: scaling commutes with max
+            mx = half_pair_max(mx) * cs;  // cs > 0: scaling commutes with max
             // the reference point of the exponentials follows the running maximum lazily: it moves
             // only when the maximum has grown by more than kLazy (p then stays below 2^kLazy,
             // harmless in float32 and bfloat16), so the accumulators are rarely rescaled
@@ -399,8 +405,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     sacc[sub][v] = __builtin_amdgcn_exp2f(fmaf(sacc[sub][v], cs, -m_safe));
                     psum += sacc[sub][v];
                 }
-            psum += shfl_xor_f(psum, 32);
-            l += psum;
+            l += half_pair_sum(psum);
             // P^T as the B operand: accumulator values 8c .. 8c+7 are this lane's keys
             // 16c + 4h + {0..3} and 16c + 8 + 4h + {0..3}; V^T is read in the same key order
 #pragma unroll

@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[u][v]);
-                mx = fmaxf(mx, shfl_xor_f(mx, 32)) * cs;
+                mx = half_pair_max(mx) * cs;
                 const float m_new = fmaxf(m, mx);
                 const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
                 float psum = 0.f;
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(fmaf(sacc[u][v], cs, -m_safe));
-                psum += shfl_xor_f(psum, 32);
+                psum = half_pair_sum(psum);
                 l = l * ((m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - m_safe)) + psum;
                 m = m_new;
             }
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                         vsum += __builtin_amdgcn_exp2f(fmaf(sacc[u][4 * qd + 3], cs, -ls.w));
                     }
             }
-            vsum += shfl_xor_f(vsum, 32);
+            vsum = half_pair_sum(vsum);
             const long key = k0 + 32 * wave + lq;
             if (h == 0 && key < kc1) {
                 float *dst = votes + (long)bk * L + key;
