@@ -16,27 +16,33 @@
 //      stores the rounded states into the cache.
 // Inputs are read once and outputs written once: 12 bytes per channel-token for a
 // bf16 cache.
+//
+// The chunks of one unit form a serial chain (one hop is about 0.7 us), which bounds the
+// time when there are few (batch, head) pairs.  The channels of Eq. 1 are independent, so
+// the kernel can also take a unit to be a slab of DS < D channels of a (batch, head): more,
+// shorter chains (a chunk then spans D / DS times as many tokens for the same bytes).
 #include <cstdlib>
 
 #include "common.h"
 
 namespace rs {
 
-template <typename ST, int D, int NT, int NW>
+template <typename ST, int D, int DS, int NT, int NW>
 __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
     const ST *__restrict__ k, const ST *__restrict__ v, const float *__restrict__ g,
     float *__restrict__ state_k, float *__restrict__ state_v, ST *__restrict__ k_cache,
     ST *__restrict__ v_cache, int BH, long T_new, long t0, long Tcap, int n_chunks,
     uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit)
 {
-    constexpr int LPR = D / 8;       // lanes per row
+    constexpr int LPR = DS / 8;      // lanes per row (of the slab)
     constexpr int RPW = 64 / LPR;    // row groups per wave
     constexpr int CHUNK = NW * RPW * NT;
+    constexpr int NS = D / DS;       // slabs per (batch, head)
     using R = Row8<ST>;
 
     __shared__ int s_ticket;
-    __shared__ float s_agg[NW][3][D];
-    __shared__ float s_carry[NW][2][D];
+    __shared__ float s_agg[NW][3][DS];
+    __shared__ float s_carry[NW][2][DS];
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -45,7 +51,8 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
     const int c0 = (lane % LPR) * 8;
 
     // persistent workgroups: each keeps taking the next chunk until none is left
-    const int total = BH * n_chunks;
+    const int units = BH * NS;
+    const int total = units * n_chunks;
     for (;;) {
     int ticket = blockIdx.x;
     if (n_chunks > 1) {
@@ -55,8 +62,10 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         ticket = s_ticket;
         if (ticket >= total) break;
     }
-    const int j = ticket / BH;   // chunk index along T
-    const int bh = ticket % BH;  // consecutive tickets walk the heads first
+    const int j = ticket / units;   // chunk index along T
+    const int unit = ticket % units;  // consecutive tickets walk the units first
+    const int bh = unit / NS;
+    const int ch0 = (unit % NS) * DS;  // first channel of the slab
 
     const long tbase = (long)j * CHUNK + (long)(wave * RPW + rg) * NT;
     const long in_row0 = (long)bh * T_new;
@@ -67,7 +76,7 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
     for (int i = 0; i < NT; ++i) {
         const long t = tbase + i;
         if (t < T_new) {
-            const long off = (in_row0 + t) * D + c0;
+            const long off = (in_row0 + t) * D + ch0 + c0;
             kr[i] = R::load_raw(k + off);
             vr[i] = R::load_raw(v + off);
             g0[i] = *reinterpret_cast<const float4 *>(g + off);
@@ -83,10 +92,10 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
     // first look at the previous chunk's outgoing state, issued behind the data loads so that
     // its round trip overlaps the fold; the wait below re-polls only if it was not there yet
     uint64_t early0 = 0, early1 = 0;
-    if (tid < D && j > 0) {
-        const uint64_t *p = rec + (((long)bh * n_chunks + (j - 1)) * 2) * D + tid;
+    if (tid < DS && j > 0) {
+        const uint64_t *p = rec + (((long)unit * n_chunks + (j - 1)) * 2) * DS + tid;
         early0 = load_u64_agent(p);
-        early1 = load_u64_agent(p + D);
+        early1 = load_u64_agent(p + DS);
     }
 
     // fold own tokens: state -> a * state + b
@@ -147,7 +156,7 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
     }
     __syncthreads();
 
-    if (tid < D) {
+    if (tid < DS) {
         const int c = tid;
         float A = 1.f, Bk = 0.f, Bv = 0.f;
 #pragma unroll
@@ -159,10 +168,10 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         }
         float Sk, Sv;
         if (j == 0) {
-            Sk = state_k[bh * D + c];
-            Sv = state_v[bh * D + c];
+            Sk = state_k[bh * D + ch0 + c];
+            Sv = state_v[bh * D + ch0 + c];
         } else {
-            const uint64_t *p = rec + (((long)bh * n_chunks + (j - 1)) * 2) * D + c;
+            const uint64_t *p = rec + (((long)unit * n_chunks + (j - 1)) * 2) * DS + c;
             uint64_t w0 = early0, w1 = early1;
             int spins = 0;
             bool ok = ((uint32_t)(w0 >> 32) == tag) && ((uint32_t)(w1 >> 32) == tag);
@@ -170,7 +179,7 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
                 if (++spins > spin_limit) break;
                 __builtin_amdgcn_s_sleep(2);
                 w0 = load_u64_agent(p);
-                w1 = load_u64_agent(p + D);
+                w1 = load_u64_agent(p + DS);
                 ok = ((uint32_t)(w0 >> 32) == tag) && ((uint32_t)(w1 >> 32) == tag);
             }
             if (!ok) atomicExch(&ctrl[kCtrlAsyncErr], 1u);  // give up; outputs undefined
@@ -180,12 +189,12 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         const float Ok = fmaf(A, Sk, Bk);
         const float Ov = fmaf(A, Sv, Bv);
         if (j == n_chunks - 1) {
-            state_k[bh * D + c] = Ok;
-            state_v[bh * D + c] = Ov;
+            state_k[bh * D + ch0 + c] = Ok;
+            state_v[bh * D + ch0 + c] = Ov;
         } else {
-            uint64_t *p = rec + (((long)bh * n_chunks + j) * 2) * D + c;
+            uint64_t *p = rec + (((long)unit * n_chunks + j) * 2) * DS + c;
             store_u64_agent(p, ((uint64_t)tag << 32) | __float_as_uint(Ok));
-            store_u64_agent(p + D, ((uint64_t)tag << 32) | __float_as_uint(Ov));
+            store_u64_agent(p + DS, ((uint64_t)tag << 32) | __float_as_uint(Ov));
         }
         float ck = Sk, cv = Sv;
 #pragma unroll
@@ -221,7 +230,7 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
                 sk[c] = fmaf(gg[c], sk[c], om * kx[c]);
                 sv[c] = fmaf(gg[c], sv[c], om * vx[c]);
             }
-            const long off = (out_row0 + t) * D + c0;
+            const long off = (out_row0 + t) * D + ch0 + c0;
             R::store(k_cache + off, sk);
             R::store(v_cache + off, sv);
         }
@@ -277,7 +286,7 @@ __global__ __launch_bounds__(256) void rat_step_kernel(
     state_v[e] = sv;
 }
 
-template <typename ST, int D>
+template <typename ST, int D, int DS>
 static int launch_scan(const void *k, const void *v, const float *g, float *state_k,
                        float *state_v, void *k_cache, void *v_cache, int BH, long T_new, long t0,
                        long Tcap, uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit,
@@ -285,15 +294,15 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
 {
     constexpr int NT = sizeof(ST) == 2 ? 4 : 2;
     constexpr int NW = 8;
-    constexpr int CHUNK = NW * (64 / (D / 8)) * NT;
+    constexpr int CHUNK = NW * (64 / (DS / 8)) * NT;
     const int n_chunks = (int)((T_new + CHUNK - 1) / CHUNK);
-    long grid = (long)BH * n_chunks;
+    long grid = (long)BH * (D / DS) * n_chunks;
     if (n_chunks > 1) {
         static int per_cu = 0, cus = 0;  // resident workgroups of this kernel
         if (per_cu == 0) {
             int dev = 0, n = 0;
             (void)hipGetDevice(&dev);
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, rat_scan_chunk_kernel<ST, D, NT, NW>, NW * 64, 0) != hipSuccess || n < 1) n = 1;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, rat_scan_chunk_kernel<ST, D, DS, NT, NW>, NW * 64, 0) != hipSuccess || n < 1) n = 1;
             per_cu = n;
             if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         }
@@ -301,7 +310,7 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
         const long want = e ? std::atol(e) : (long)per_cu * cus;
         if (grid > want) grid = want;
     }
-    rat_scan_chunk_kernel<ST, D, NT, NW><<<dim3((unsigned)grid), dim3(NW * 64), 0, stream>>>(
+    rat_scan_chunk_kernel<ST, D, DS, NT, NW><<<dim3((unsigned)grid), dim3(NW * 64), 0, stream>>>(
         (const ST *)k, (const ST *)v, g, state_k, state_v, (ST *)k_cache, (ST *)v_cache, BH, T_new,
         t0, Tcap, n_chunks, ctrl, rec, tag, spin_limit);
     return 0;
@@ -332,13 +341,19 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
                                                               (float *)k_cache, (float *)v_cache, (float *)meta, P, BH, D, T_new, t0, Tcap);
         return;
     }
+    // few (batch, head) pairs and a long run: 32-channel slabs, so that the chunk chains are
+    // shorter and there are more of them
+    const char *es = std::getenv("RATSPARSE_SCAN_SLAB");
+    const bool slab = es ? std::atoi(es) != 0 : (BH <= 16 && T_new >= 16384);
+#define RS_SCAN(ST, DD, DSS) launch_scan<ST, DD, DSS>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream)
     if (dtype == RS_BF16) {
-        if (D == 128) launch_scan<bf16, 128>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream);
-        else launch_scan<bf16, 64>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream);
+        if (D == 128) slab ? RS_SCAN(bf16, 128, 32) : RS_SCAN(bf16, 128, 128);
+        else slab ? RS_SCAN(bf16, 64, 32) : RS_SCAN(bf16, 64, 64);
     } else {
-        if (D == 128) launch_scan<float, 128>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream);
-        else launch_scan<float, 64>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream);
+        if (D == 128) slab ? RS_SCAN(float, 128, 32) : RS_SCAN(float, 128, 128);
+        else slab ? RS_SCAN(float, 64, 32) : RS_SCAN(float, 64, 64);
     }
+#undef RS_SCAN
 }
 
 }  // namespace rs

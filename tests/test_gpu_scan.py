@@ -70,6 +70,33 @@ def test_ragged_lengths_carry_in_and_offset(rs, dtype, D, T, B, H):
     assert np.all(kc[:, :, :t0] == 0) and np.all(kc[:, :, t0 + T:] == 0)
 
 
+@pytest.mark.parametrize("dtype,D,T,B,H", [("bf16", 128, 3 * 512 + 37, 1, 2), ("f32", 64, 1300, 2, 1),
+                                           ("bf16", 64, 2048, 1, 3), ("bf16", 128, 20000, 1, 2)])
+def test_channel_slab_mode(rs, monkeypatch, dtype, D, T, B, H):
+    """The few-heads form of the scan (a unit is a 32-channel slab of a (batch, head), chunks span
+    more tokens) gives the same states; the last case also takes it by the library's own choice."""
+    say("scan slab", dtype, D, T, B, H)
+    if T < 16384:
+        monkeypatch.setenv("RATSPARSE_SCAN_SLAB", "1")
+    r = np.random.default_rng(T + 1)
+    k = r.standard_normal((B, H, T, D)).astype(np.float32)
+    v = r.standard_normal((B, H, T, D)).astype(np.float32)
+    if dtype == "bf16":
+        k, v = synth.to_bf16_grid(k), synth.to_bf16_grid(v)
+    g = _gate(r, (B, H, T, D))
+    sk0 = r.standard_normal((B, H, D)).astype(np.float32)
+    sv0 = r.standard_normal((B, H, D)).astype(np.float32)
+    t0, Tcap = 16, T + 32
+    kc, vc, sk, sv = _run_scan(rs, k, v, g, dtype, Tcap, t0=t0, sk0=sk0, sv0=sv0)
+    ko, vo, osk, osv = oracle.rat_scan(k, v, g, sk0, sv0)
+    assert scan_close(sk, osk)[0] and scan_close(sv, osv)[0]
+    if dtype == "f32":
+        assert scan_close(kc[:, :, t0:t0 + T], ko)[0] and scan_close(vc[:, :, t0:t0 + T], vo)[0]
+    else:
+        assert bf16_store_ok(kc[:, :, t0:t0 + T], ko) and bf16_store_ok(vc[:, :, t0:t0 + T], vo)
+    assert np.all(kc[:, :, :t0] == 0) and np.all(kc[:, :, t0 + T:] == 0)
+
+
 def test_decode_appends_and_split_invariance(rs):
     B, H, T, D = 1, 2, 600, 128
     r = np.random.default_rng(5)
