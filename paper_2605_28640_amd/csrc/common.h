@@ -146,11 +146,20 @@ __device__ __forceinline__ void from_f32(float &d, float x) { d = x; }
 __device__ __forceinline__ void from_f32(bf16 &d, float x) { d.bits = __builtin_bit_cast(uint16_t, (__bf16)x); }
 
 // One wave-wide direct load moves 64 x 16 bytes from global memory into 1 KB of LDS, lane l
-// landing at byte 16 l of the destination; nothing passes through registers.
-__device__ __forceinline__ void load16_to_lds(const void *g, void *l)
+// landing at byte 16 l of the destination; nothing passes through registers.  The source is
+// named by a buffer descriptor (a wave-uniform base) plus a per-lane byte offset: the buffer
+// form of the instruction only counts as a vector memory operation, so the compiler keeps
+// exact counts for the LDS reads issued around it (with the global-address form it treats the
+// LDS counter as out of order and turns every wait for an operand read into a wait for all of
+// them, the ones issued just before included).
+typedef __amdgpu_buffer_rsrc_t LdsSource;
+__device__ __forceinline__ LdsSource lds_source(const void *base)
 {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                     (__attribute__((address_space(3))) void *)l, 16, 0, 0);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7fffffff, 0x00020000);
+}
+__device__ __forceinline__ void load16_to_lds(LdsSource src, uint32_t byte_offset, void *l)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (__attribute__((address_space(3))) void *)l, 16, (int)byte_offset, 0, 0, 0);
 }
 
 // Tiles of K/V rows sit in LDS unpadded (a wave-wide load fills whole rows back to back), so the bank

@@ -191,7 +191,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lq = lane & 31, h = lane >> 5;
-    const int unit = blockIdx.y;
+    // Workgroups are handed to the eight XCDs round-robin in launch order, and each XCD has an L2
+    // of its own.  Launch slot L therefore runs on XCD L % 8; give that XCD whole (batch, head)
+    // units (unit % 8 == XCD) and consecutive tiles of one unit, so that the workgroups resident
+    // on an XCD stream the same K and V rows at about the same time and share them in its L2.
+    int unit = blockIdx.y, xtile = blockIdx.x;
+    {
+        const unsigned nu = gridDim.y, nt = gridDim.x;
+        if (nu % 8 == 0) {
+            const unsigned L = blockIdx.y * nt + blockIdx.x;
+            const unsigned xcd = L & 7, s = L >> 3;
+            unit = (int)(xcd + 8 * (s / nt));
+            xtile = (int)(s % nt);
+        }
+    }
     const int b = unit / a.Hq, hq = unit % a.Hq, kvh = hq / (a.Hq / a.Hkv);
     const bf16 *kb = a.k_cache + (long)(b * a.Hkv + kvh) * a.Tcap * D;
     const bf16 *vb = a.v_cache + (long)(b * a.Hkv + kvh) * a.Tcap * D;
@@ -202,7 +215,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     long kv_begin, kv_end;  // keys visited
     uint32_t lbase = 0, lcount = 0;
     {
-        int x = blockIdx.x;
+        const int x = xtile;
         if (a.idx == nullptr) {  // dense causal: heavy tiles first
             const int tile = a.n_diag - 1 - x;
             r0 = (long)tile * kMT;
@@ -233,7 +246,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     auto stage = [&](const bf16 *base, uint16_t *tile, int i, long k0) {
         const int rem = (int)((kv_end - k0 < kKT) ? kv_end - k0 : kKT);  // valid rows, >= 1
         const int r = (i * RPI + srow < rem) ? i * RPI + srow : rem - 1;
-        load16_to_lds(base + k0 * D + (uint32_t)(r * D + gchunk * 8), tile + (i * RPI + wave * RW) * D);
+        load16_to_lds(lds_source(base + k0 * D), (uint32_t)(r * D + gchunk * 8) * 2u, tile + (i * RPI + wave * RW) * D);
     };
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {  // the first tile only needs the block: issue it before the row list is chased
@@ -336,6 +349,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             // S^T[key][query] = sum_d K[key][d] Q[query][d], two 32-key sub-tiles; consecutive
             // matrix instructions go to different accumulators (a dependent one issued back to
             // back waits for the previous result)
+            // matrix phases run at raised priority: of the two waves that share a SIMD, the one
+            // feeding the matrix pipe is issued first and the other's softmax fills the gaps
+            __builtin_amdgcn_s_setprio(1);
             f32x16 sacc[2];
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
@@ -364,6 +380,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
             // masks only where a boundary crosses this step (uniform over the wave)
             // (all in 32-bit offsets from kv_begin: the lane sees keys vis_lo .. vis_hi)
+            __builtin_amdgcn_s_setprio(0);
             const int kr = it * kKT;
             if (__any(kr < vis_lo || kr + kKT - 1 > vis_hi)) {
                 const int hi = ((vis_hi - kr > kKT) ? kKT : ((vis_hi - kr < -1) ? -1 : vis_hi - kr)) - 4 * h;
@@ -406,6 +423,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     psum += sacc[sub][v];
                 }
             l += half_pair_sum(psum);
+            __builtin_amdgcn_s_setprio(1);
             // P^T as the B operand: accumulator values 8c .. 8c+7 are this lane's keys
             // 16c + 4h + {0..3} and 16c + 8 + 4h + {0..3}; V^T is read in the same key order
 #pragma unroll
@@ -443,6 +461,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 if (NEXT && g < CPT) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+            __builtin_amdgcn_s_setprio(0);
         }
         if constexpr (NEXT) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads have landed
         __syncthreads();

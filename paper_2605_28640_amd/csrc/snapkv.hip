@@ -43,7 +43,7 @@ struct SnapStage {
     __device__ __forceinline__ void pass(const bf16 *kt, uint16_t *tile, int i, int rem) const
     {
         const int r = (i * RPI + srow < rem) ? i * RPI + srow : rem - 1;
-        load16_to_lds(kt + (uint32_t)(r * D + gchunk * 8), tile + (i * RPI + wave * RW) * D);
+        load16_to_lds(lds_source(kt), (uint32_t)(r * D + gchunk * 8) * 2u, tile + (i * RPI + wave * RW) * D);
     }
 };
 
