@@ -37,3 +37,70 @@ def test_status_strings_and_host_side_validation():
     assert lib.quest_page_meta(ctypes.byref(s), None, None, 0, 16, None) == 1  # null pointers
     assert lib.quest_page_meta(ctypes.byref(s), 16, 16, 0, 65, None) == 1  # past the capacity
     assert lib.rat_scan_workspace_bytes(ctypes.byref(s), 4096) > binding.RS_WS_CTRL_BYTES
+
+
+def test_every_entry_point_rejects_bad_arguments_before_touching_the_gpu():
+    """Argument validation is synchronous and comes before any launch: with made-up (non-null,
+    16-byte aligned, never dereferenced) addresses each entry point must answer with
+    1 = invalid argument, 2 = unsupported or 3 = workspace too small."""
+    from paper_2605_28640_amd import binding
+    lib = binding.load()
+    A = 1 << 20  # an aligned made-up address
+    s = binding.make_shape(1, 4, 2, 128, 256, 16, binding.RS_BF16)
+    sp = ctypes.byref(s)
+    big = 1 << 30
+
+    # rat_scan(s, k, v, g, state_k, state_v, k_cache, v_cache, meta, t0, T_new, ws, ws_bytes, stream)
+    assert lib.rat_scan(sp, None, A, A, A, A, A, A, None, 0, 16, A, big, None) == 1
+    assert lib.rat_scan(sp, A, A, A, A, A, A, A, None, 250, 16, A, big, None) == 1      # runs past Tcap
+    assert lib.rat_scan(sp, A, A, A, A, A, A, A, None, 0, 0, A, big, None) == 1         # no tokens
+    assert lib.rat_scan(sp, A, A, A, A, A, A, A, A + 4, 0, 16, A, big, None) == 1       # misaligned meta
+    assert lib.rat_scan(sp, A, A, A, A, A, A, A, None, 0, 256, A, 16, None) == 3        # workspace too small
+
+    # quest_select_decode(s, q, meta, T_valid, K, n_first, n_local, idx_out, scores_out, ws, ws_bytes, stream)
+    assert lib.quest_select_decode(sp, A, A, 256, 17, 1, 1, A, None, A, big, None) == 1  # K > pages
+    assert lib.quest_select_decode(sp, A, A, 256, 2, 2, 2, A, None, A, big, None) == 1   # forced pages > K
+    assert lib.quest_select_decode(sp, A, A, 257, 4, 1, 1, A, None, A, big, None) == 1   # T_valid > Tcap
+    assert lib.quest_select_decode(sp, A, None, 256, 4, 1, 1, A, None, A, big, None) == 1
+    assert lib.quest_select_decode(sp, A, A, 256, 4, 1, 1, A, None, A, 16, None) == 3
+    assert lib.quest_select_decode(sp, A, A, 256, 4, 1, 1, A, None, None, big, None) == 3
+
+    # sparse_attn_decode(s, q, k_cache, v_cache, T_valid, scale, idx, K, meta, n_first, n_local, out,
+    #                    lse_out, idx_out, ws, ws_bytes, stream)
+    assert lib.sparse_attn_decode(sp, A, A, A, 0, 0.1, None, 0, None, 0, 0, A, None, None, A, big, None) == 1
+    assert lib.sparse_attn_decode(sp, A, A, A, 256, 0.1, A, 17, None, 0, 0, A, None, None, A, big, None) == 1
+    assert lib.sparse_attn_decode(sp, A, A, A, 256, 0.1, None, 4, A + 8, 1, 1, A, None, None, A, big, None) == 1
+    assert lib.sparse_attn_decode(sp, A, A, A, 256, 0.1, None, 4, A, 1, 1, None, None, None, A, big, None) == 1
+    assert lib.sparse_attn_decode(sp, A, A, A, 256, 0.1, None, 4, A, 1, 1, A, None, None, A, 16, None) == 3
+
+    # moba_select_prefill(s, q, k_cache, T, block, K, n_first, means_out, idx_out, ws, ws_bytes, stream)
+    assert lib.moba_select_prefill(sp, A, A, 256, 24, 3, 0, A, A, A, big, None) == 1     # block not a multiple of 16
+    assert lib.moba_select_prefill(sp, A, A, 256, 64, 33, 0, A, A, A, big, None) == 1    # K > 32
+    assert lib.moba_select_prefill(sp, A, A, 256, 64, 1, 1, A, A, A, big, None) == 1     # no room for own block
+    assert lib.moba_select_prefill(sp, A, A, 512, 64, 3, 0, A, A, A, big, None) == 1     # T > Tcap
+    assert lib.moba_select_prefill(sp, A, A, 256, 64, 3, 0, A, A, A, 16, None) == 3
+
+    # sparse_attn_prefill(s, q, k_cache, v_cache, T, block, scale, idx, K, out, lse_out, ws, ws_bytes, stream)
+    assert lib.sparse_attn_prefill(sp, A, A, A, 256, 64, 0.1, A, 0, A, None, A, big, None) == 1
+    assert lib.sparse_attn_prefill(sp, A, A, A, 256, 64, 0.1, A + 4, 3, A, None, A, big, None) == 1
+    assert lib.sparse_attn_prefill(sp, A, A, None, 256, 64, 0.1, None, 0, A, None, A, big, None) == 1
+    assert lib.sparse_attn_prefill(sp, A, A, A, 256, 64, 0.1, A, 3, A, None, A, 16, None) == 3
+    f32 = binding.make_shape(1, 4, 2, 128, 256, 16, binding.RS_F32)  # the matrix-core paths store bf16
+    assert lib.sparse_attn_prefill(ctypes.byref(f32), A, A, A, 256, 64, 0.1, None, 0, A, None, A, big, None) == 2
+
+    # snapkv_compress(s, q_win, k_cache, v_cache, T, W, K_keep, pool_kernel, scale, kc_out, vc_out,
+    #                 Tcap_out, idx_out, votes_out, ws, ws_bytes, stream)
+    assert lib.snapkv_compress(sp, A, A, A, 256, 32, 64, 4, 0.1, A, A, 128, A, None, A, big, None) == 1   # even pool
+    assert lib.snapkv_compress(sp, A, A, A, 256, 256, 0, 7, 0.1, A, A, 512, A, None, A, big, None) == 1   # W >= T
+    assert lib.snapkv_compress(sp, A, A, A, 256, 32, 225, 7, 0.1, A, A, 512, A, None, A, big, None) == 1  # keep > T - W
+    assert lib.snapkv_compress(sp, A, A, A, 256, 32, 64, 7, 0.1, A, A, 64, A, None, A, big, None) == 1    # output too short
+    assert lib.snapkv_compress(sp, A, A, A, 256, 32, 64, 7, 0.1, A, A, 128, A, None, A, 16, None) == 3
+
+    # shapes
+    for bad in (binding.make_shape(0, 4, 2, 128, 256, 16, binding.RS_BF16),
+                binding.make_shape(1, 4, 2, 128, 250, 16, binding.RS_BF16)):  # Tcap not a multiple of P
+        assert lib.quest_page_meta(ctypes.byref(bad), A, A, 0, 16, None) == 1
+    odd_page = binding.make_shape(1, 4, 2, 128, 240, 48, binding.RS_BF16)
+    assert lib.quest_page_meta(ctypes.byref(odd_page), A, A, 0, 16, None) == 2
+    for code in (1, 2, 3, 4, 5):
+        assert len(lib.ratsparse_status_string(code)) > 0
