@@ -10,8 +10,8 @@ namespace rs {
 // ------------------------------------------------------------------------------------
 template <typename ST, int D>
 __global__ __launch_bounds__(256) void moba_block_means_kernel(const ST *__restrict__ k_cache,
-                                                               float *__restrict__ means, long Tcap, long T,
-                                                               int block, int Nb)
+                                                               float *__restrict__ means, uint16_t *__restrict__ split,
+                                                               long Tcap, long T, int block, int Nb)
 {
     constexpr int LPR = D / 8;
     constexpr int RPW = 64 / LPR;
@@ -45,7 +45,21 @@ __global__ __launch_bounds__(256) void moba_block_means_kernel(const ST *__restr
     __syncthreads();
     if (tid < D) {
         const float s = (s_acc[0][tid] + s_acc[1][tid]) + (s_acc[2][tid] + s_acc[3][tid]);
-        means[(bh * Nb + j) * D + tid] = s / (float)(t1 - t0);
+        const float m = s / (float)(t1 - t0);
+        means[(bh * Nb + j) * D + tid] = m;
+        if (split) {
+            // the mean as three bfloat16 terms, m = m1 + m2 + m3 up to 2^-24 |m| (both remainders
+            // are exact in float32): the operands of the matrix-core gate, rows [m1 | m2 | m3]
+            const __bf16 m1 = (__bf16)m;
+            const float r1 = m - (float)m1;
+            const __bf16 m2 = (__bf16)r1;
+            const float r2 = r1 - (float)m2;
+            const __bf16 m3 = (__bf16)r2;
+            uint16_t *row = split + (bh * Nb + j) * 3 * D + tid;
+            row[0] = __builtin_bit_cast(uint16_t, m1);
+            row[D] = __builtin_bit_cast(uint16_t, m2);
+            row[2 * D] = __builtin_bit_cast(uint16_t, m3);
+        }
     }
 }
 
@@ -119,18 +133,23 @@ __global__ __launch_bounds__(64) void moba_gate_topk_kernel(const ST *__restrict
 
 // ------------------------------------------------------------------------------------
 // bfloat16 queries: the gate scores of 64 query tokens against 32 blocks at a time on the
-// matrix cores, S^T = M Q^T with v_mfma_f32_32x32x16_bf16.  The float32 block means are
-// split into three bfloat16 terms (m = m1 + m2 + m3 up to 2^-24 |m|) and the three products
-// accumulate in float32, so the scores keep float32 accuracy (the top-K needs it: a block
-// mean rounded to bfloat16 would move scores by 2^-9).  A lane of the accumulator holds 16
-// blocks of ONE query; scores go to the same per-thread LDS column as in the scalar kernel
-// and the K picks are taken from there.
+// matrix cores, S^T = M Q^T with v_mfma_f32_32x32x16_bf16.  The float32 block means come
+// split into three bfloat16 terms (m = m1 + m2 + m3 up to 2^-24 |m|, written by the means
+// kernel) and the three products accumulate in float32, so the scores keep float32 accuracy
+// (the top-K needs it: a block mean rounded to bfloat16 would move scores by 2^-9).  A lane
+// of the accumulator holds 16 blocks of ONE query.
+// Picks, K <= 4 and at most 64 candidate blocks: the scores stay in registers.  Each half-lane
+// keeps the four largest of its values (three v_med3 and a v_max per value), the two halves
+// of a query merge their lists, the take-th largest is the threshold, and the picked set is
+// the bit mask of scores >= threshold.  If that mask does not hold exactly `take` blocks (an
+// exact tie at the threshold), or for larger K / more blocks, the scores go to a per-thread LDS
+// column as in the scalar kernel and the K picks are K sweeps over it.
 // ------------------------------------------------------------------------------------
 typedef __bf16 gate_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float gate_f32x16 __attribute__((ext_vector_type(16)));
 
 template <int D>
-__global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restrict__ q, const float *__restrict__ means,
+__global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restrict__ q, const uint16_t *__restrict__ split,
                                                             int32_t *__restrict__ idx_out, int Hq, int Hkv, long T,
                                                             int block, int Nb, int K, int n_first)
 {
@@ -158,29 +177,20 @@ __global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restr
 #pragma unroll
         for (int c = 0; c < NC; ++c) qf[qt][c] = *reinterpret_cast<const gate_bf16x8 *>(qrow + 16 * c);
     }
-    const float *mbase = means + (long)(b * Hkv + kvh) * Nb * D;
-    for (int j0 = 0; j0 <= own_max; j0 += 32) {
-        gate_f32x16 acc[2];
+    const uint16_t *sbase = split + (long)(b * Hkv + kvh) * Nb * 3 * D;
+    // scores of blocks j0 .. j0 + 31 against this wave's 64 queries
+    auto scores = [&](int j0, gate_f32x16 (&acc)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[qt][v] = 0.f;
         const int jr = (j0 + lq < Nb) ? j0 + lq : Nb - 1;  // A operand row of this lane (clamped; extra rows are never read back)
-        const float *mrow = mbase + (long)jr * D + 8 * h;
+        const uint16_t *mrow = sbase + (long)jr * 3 * D + 8 * h;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            const float4 x0 = *reinterpret_cast<const float4 *>(mrow + 16 * c);
-            const float4 x1 = *reinterpret_cast<const float4 *>(mrow + 16 * c + 4);
-            const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-            gate_bf16x8 m1, m2, m3;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                m1[i] = (__bf16)x[i];
-                const float r1 = x[i] - (float)m1[i];  // exact
-                m2[i] = (__bf16)r1;
-                const float r2 = r1 - (float)m2[i];    // exact
-                m3[i] = (__bf16)r2;
-            }
+            const gate_bf16x8 m1 = *reinterpret_cast<const gate_bf16x8 *>(mrow + 16 * c);
+            const gate_bf16x8 m2 = *reinterpret_cast<const gate_bf16x8 *>(mrow + D + 16 * c);
+            const gate_bf16x8 m3 = *reinterpret_cast<const gate_bf16x8 *>(mrow + 2 * D + 16 * c);
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt) {
                 acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m3, qf[qt][c], acc[qt], 0, 0, 0);
@@ -188,16 +198,102 @@ __global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restr
                 acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m1, qf[qt][c], acc[qt], 0, 0, 0);
             }
         }
-        // accumulator value v of lane (lq, h): block j0 + 8 (v / 4) + 4 h + v % 4, query lq
+    };
+    // accumulator value v of lane (lq, h): block j0 + 8 (v / 4) + 4 h + v % 4, query lq
+    if (K <= 4 && own_max < 64 && own_max >= 0) {
+        float sc[2][2][16];  // [block group][query tile][value]; -inf: not a candidate
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
+        for (int g = 0; g < 2; ++g) {
+            if (32 * g <= own_max) {
+                gate_f32x16 acc[2];
+                scores(32 * g, acc);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int j = j0 + 8 * (v / 4) + 4 * h + (v % 4);
-                float sc = acc[qt][v];
-                if (j == own_q[qt] || j < n_first) sc = INFINITY;  // always kept
-                s_score[j * 64 + 32 * qt + lq] = sc;
+                for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int j = 32 * g + 8 * (v / 4) + 4 * h + (v % 4);
+                        float x = acc[qt][v];
+                        if (j == own_q[qt] || j < n_first) x = INFINITY;  // always kept
+                        sc[g][qt][v] = (j <= own_q[qt]) ? x : -INFINITY;
+                    }
+            } else {
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sc[g][qt][v] = -INFINITY;
             }
+        }
+        uint32_t mask[2][2];  // [query tile][block group]: picked blocks, complete after the exchange
+        bool exact = true;
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            // the four largest of this half-lane's values, then of both halves
+            float a4 = -INFINITY, b4 = -INFINITY, c4 = -INFINITY, d4 = -INFINITY;
+            auto put = [&](float x) __attribute__((always_inline)) {
+                const float na = fmaxf(a4, x), nb = __builtin_amdgcn_fmed3f(a4, b4, x);
+                const float nc = __builtin_amdgcn_fmed3f(b4, c4, x), nd = __builtin_amdgcn_fmed3f(c4, d4, x);
+                a4 = na, b4 = nb, c4 = nc, d4 = nd;
+            };
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) put(sc[g][qt][v]);
+            const float pa = shfl_xor_f(a4, 32), pb = shfl_xor_f(b4, 32), pc = shfl_xor_f(c4, 32), pd = shfl_xor_f(d4, 32);
+            put(pa), put(pb), put(pc), put(pd);
+            const int avail = own_q[qt] + 1;
+            const int take = (K < avail) ? K : avail;
+            const float thr = (take == 1) ? a4 : (take == 2) ? b4 : (take == 3) ? c4 : d4;
+            int cnt = 0;
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                uint32_t m = 0u;
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (sc[g][qt][v] >= thr) m |= 1u << (8 * (v / 4) + (v % 4));
+                m <<= 4 * h;
+                m |= (uint32_t)__shfl_xor((int)m, 32, 64);
+                mask[qt][g] = m;
+                cnt += __popc(m);
+            }
+            exact = exact && (cnt == take);
+        }
+        if (!__any(!exact)) {
+            // half h writes the picks of query tile h: token t_tile + 32 h + lq, ascending blocks
+            const long t = t_tile + 32 * h + lq;
+            if (t < T) {
+                uint64_t m = h ? (((uint64_t)mask[1][1] << 32) | mask[1][0]) : (((uint64_t)mask[0][1] << 32) | mask[0][0]);
+                int32_t *dst = idx_out + ((long)unit * T + t) * K;
+                for (int n = 0; n < K; ++n) {
+                    dst[n] = m ? (int32_t)__builtin_ctzll(m) : -1;
+                    m &= m - 1;
+                }
+            }
+            return;
+        }
+        // an exact tie at some threshold: through LDS, where the sweeps settle it by block order
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int j = 32 * g + 8 * (v / 4) + 4 * h + (v % 4);
+                    if (32 * g <= own_max) s_score[j * 64 + 32 * qt + lq] = sc[g][qt][v];
+                }
+    } else {
+        for (int j0 = 0; j0 <= own_max; j0 += 32) {
+            gate_f32x16 acc[2];
+            scores(j0, acc);
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int j = j0 + 8 * (v / 4) + 4 * h + (v % 4);
+                    float x = acc[qt][v];
+                    if (j == own_q[qt] || j < n_first) x = INFINITY;  // always kept
+                    s_score[j * 64 + 32 * qt + lq] = x;
+                }
+        }
     }
     __syncthreads();
     // the picks: thread = query token, candidates 0 .. own.  The sweeps run to the wave-uniform
@@ -241,11 +337,17 @@ __global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restr
     }
 }
 
-size_t moba_select_ws_bytes(const rs_shape *, long, int) { return RS_WS_CTRL_BYTES; }
+// workspace: the block means as three bfloat16 terms, [batch * KV heads][blocks][3][D]
+size_t moba_select_ws_bytes(const rs_shape *s, long T, int block)
+{
+    const size_t Nb = (size_t)((T + block - 1) / block);
+    return RS_WS_CTRL_BYTES + (((size_t)s->B * s->Hkv * Nb * 3 * s->D * 2 + 255) & ~(size_t)255);
+}
 
 int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, long T, int block, int K,
-                         int n_first, float *means_out, int32_t *idx_out, char *, hipStream_t stream)
+                         int n_first, float *means_out, int32_t *idx_out, char *ws, hipStream_t stream)
 {
+    uint16_t *split = (uint16_t *)(ws + RS_WS_CTRL_BYTES);
     const int Nb = (int)((T + block - 1) / block);
     if (Nb > 256) return RS_UNSUPPORTED;  // one LDS score column per thread: Nb * 256 bytes
     const dim3 g1((unsigned)Nb, (unsigned)(s->B * s->Hkv));
@@ -259,17 +361,17 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     const dim3 g3((unsigned)((T + 64 * wpg - 1) / (64 * wpg)), (unsigned)(s->B * s->Hq));
 #define RS_LAUNCH(ST, DD)                                                                                          \
     do {                                                                                                           \
-        moba_block_means_kernel<ST, DD><<<g1, 256, 0, stream>>>((const ST *)k_cache, means_out, s->Tcap, T, block, Nb); \
+        moba_block_means_kernel<ST, DD><<<g1, 256, 0, stream>>>((const ST *)k_cache, means_out, nullptr, s->Tcap, T, block, Nb); \
         moba_gate_topk_kernel<ST, DD><<<g2, 64, lds, stream>>>((const ST *)q, means_out, idx_out, s->Hq, s->Hkv, T,  \
                                                                 block, Nb, K, n_first);                            \
     } while (0)
     if (s->dtype == RS_BF16) {
         if (s->D == 128) {
-            moba_block_means_kernel<bf16, 128><<<g1, 256, 0, stream>>>((const bf16 *)k_cache, means_out, s->Tcap, T, block, Nb);
-            moba_gate_mfma_kernel<128><<<g3, 64 * wpg, lds_mfma, stream>>>((const bf16 *)q, means_out, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
+            moba_block_means_kernel<bf16, 128><<<g1, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
+            moba_gate_mfma_kernel<128><<<g3, 64 * wpg, lds_mfma, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
         } else {
-            moba_block_means_kernel<bf16, 64><<<g1, 256, 0, stream>>>((const bf16 *)k_cache, means_out, s->Tcap, T, block, Nb);
-            moba_gate_mfma_kernel<64><<<g3, 64 * wpg, lds_mfma, stream>>>((const bf16 *)q, means_out, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
+            moba_block_means_kernel<bf16, 64><<<g1, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
+            moba_gate_mfma_kernel<64><<<g3, 64 * wpg, lds_mfma, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
         }
     } else {
         if (s->D == 128) RS_LAUNCH(float, 128);

@@ -99,3 +99,33 @@ def test_moba_select_and_sparse_prefill(rs, case):
         assert attn_close(to_np(outf), od)[0]
     torch.cuda.synchronize()
     ws.async_status()
+
+
+@pytest.mark.parametrize("K,n_first", [(3, 0), (4, 1), (8, 0)])
+def test_moba_exact_ties_pick_lowest_blocks(rs, K, n_first):
+    """A cache that repeats with the block length has identical block means, so every gate
+    score of a query ties exactly: the routing must keep the query's own block, the first
+    n_first blocks, and fill up with the lowest block indices (the oracle's tie rule)."""
+    say("moba ties", K, n_first)
+    w = synth.C4.scaled(B=1, Hq=2, Hkv=2, T=1024)
+    T, block = 1024, 64
+    Nb = T // block
+    rng = np.random.default_rng(7)
+    one = oracle.round_to_bf16(rng.standard_normal((w.B, w.Hkv, block, w.D)).astype(np.float32))
+    kc = np.tile(one, (1, 1, Nb, 1))
+    q = oracle.round_to_bf16(rng.standard_normal((w.B, w.Hq, T, w.D)).astype(np.float32))
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, T, 16, torch.bfloat16)
+    means = torch.zeros(w.B, w.Hkv, Nb, w.D, device="cuda")
+    idx = torch.full((w.B, w.Hq, T, K), -9, dtype=torch.int32, device="cuda")
+    ws = rs.Workspace(rs.moba_select_prefill_workspace_bytes(s, T, block))
+    rs.moba_select_prefill(s, to_dev(q, "bf16"), to_dev(kc, "bf16"), T, block, K, n_first, means, idx, ws)
+    omeans = oracle.moba_block_means(kc, T, block)
+    oidx = oracle.moba_select(q, omeans, T, block, K, n_first)
+    gidx = to_np(idx)
+    for t in (0, 63, 64, 200, 511, 1023):
+        own = t // block
+        want = sorted(set(list(range(min(K - 1, own))) + [own]))  # lowest blocks, then own
+        want = want + [-1] * (K - len(want))
+        assert list(oidx[0, 0, t]) == want, (t, oidx[0, 0, t], want)  # the oracle follows the stated rule
+    np.testing.assert_array_equal(gidx, oidx)
+    ws.async_status()
