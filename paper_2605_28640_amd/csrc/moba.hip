@@ -21,6 +21,17 @@ __global__ __launch_bounds__(256) void moba_block_means_kernel(const ST *__restr
     const int rg = lane / LPR, c0 = (lane % LPR) * 8;
     const int j = blockIdx.x;
     const long bh = blockIdx.y;
+    // The split terms are laid out as the gate's matrix operands: for block group g = j / 32,
+    // term and 16-channel chunk c, the 64 lanes' 16-byte fragments follow each other (lane =
+    // 32 * (channel half) + j % 32), so that a wave loads an operand as 1 KB of contiguous memory.
+    const long Ng = (Nb + 31) / 32;
+    auto split_at = [&](int term, int d) {
+        return split + ((((bh * Ng + j / 32) * 3 + term) * (D / 16) + d / 16) * 64 + 32 * ((d % 16) / 8) + j % 32) * 8 + d % 8;
+    };
+    if (j >= Nb) {  // padding rows of the last group: zeros
+        if (split && tid < D) *split_at(0, tid) = *split_at(1, tid) = *split_at(2, tid) = 0;
+        return;
+    }
     const long t0 = (long)j * block;
     const long t1 = (t0 + block < T) ? t0 + block : T;
 
@@ -49,16 +60,15 @@ __global__ __launch_bounds__(256) void moba_block_means_kernel(const ST *__restr
         means[(bh * Nb + j) * D + tid] = m;
         if (split) {
             // the mean as three bfloat16 terms, m = m1 + m2 + m3 up to 2^-24 |m| (both remainders
-            // are exact in float32): the operands of the matrix-core gate, rows [m1 | m2 | m3]
+            // are exact in float32): the operands of the matrix-core gate
             const __bf16 m1 = (__bf16)m;
             const float r1 = m - (float)m1;
             const __bf16 m2 = (__bf16)r1;
             const float r2 = r1 - (float)m2;
             const __bf16 m3 = (__bf16)r2;
-            uint16_t *row = split + (bh * Nb + j) * 3 * D + tid;
-            row[0] = __builtin_bit_cast(uint16_t, m1);
-            row[D] = __builtin_bit_cast(uint16_t, m2);
-            row[2 * D] = __builtin_bit_cast(uint16_t, m3);
+            *split_at(0, tid) = __builtin_bit_cast(uint16_t, m1);
+            *split_at(1, tid) = __builtin_bit_cast(uint16_t, m2);
+            *split_at(2, tid) = __builtin_bit_cast(uint16_t, m3);
         }
     }
 }
@@ -141,72 +151,107 @@ __global__ __launch_bounds__(64) void moba_gate_topk_kernel(const ST *__restrict
 // Picks, K <= 4 and at most 64 candidate blocks: the scores stay in registers.  Each half-lane
 // keeps the four largest of its values (three v_med3 and a v_max per value), the two halves
 // of a query merge their lists, the take-th largest is the threshold, and the picked set is
-// the bit mask of scores >= threshold.  If that mask does not hold exactly `take` blocks (an
-// exact tie at the threshold), or for larger K / more blocks, the scores go to a per-thread LDS
-// column as in the scalar kernel and the K picks are K sweeps over it.
+// the bit mask of scores >= threshold; if that mask does not hold exactly `take` blocks (an
+// exact tie at the threshold) the blocks above the threshold are taken and the tied ones fill
+// up in index order.  This path uses no LDS.  For larger K / more blocks the scores go to a
+// per-thread LDS column as in the scalar kernel and the K picks are K sweeps over it.
 // ------------------------------------------------------------------------------------
 typedef __bf16 gate_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float gate_f32x16 __attribute__((ext_vector_type(16)));
 
-template <int D>
-__global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restrict__ q, const uint16_t *__restrict__ split,
-                                                            int32_t *__restrict__ idx_out, int Hq, int Hkv, long T,
-                                                            int block, int Nb, int K, int n_first)
+template <int D, bool REG>  // REG: picks in registers (K <= 4, at most 64 blocks)
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void moba_gate_mfma_kernel(const bf16 *__restrict__ q, const uint16_t *__restrict__ split,
+                                                           int32_t *__restrict__ idx_out, int Hq, int Hkv, long T,
+                                                           int block, int Nb, int K, int n_first)
 {
     constexpr int NC = D / 16;
-    // every wave works alone on 64 query tokens; several waves share a workgroup only to keep
-    // the number of workgroups (and the time to dispatch them) down
-    extern __shared__ float s_score_all[];  // [waves][Nb rounded up to 32][64]
+    constexpr int CR = D / 8;    // 16-byte chunks per query row
+    constexpr int RW = 64 / CR;  // rows one wave-wide direct load covers
+    constexpr int NP = 64 / RW;  // direct loads per 64-row tile
+    // A workgroup is one wave; it walks over tiles of 64 query tokens of one (batch, head).  The
+    // tile's query rows come through LDS: row-contiguous direct loads (a lane fetching its own
+    // row in 16-byte pieces would touch 64 cache lines per instruction), issued one tile ahead --
+    // once the current tile's operands sit in registers and its matrix work is done -- so that
+    // they land under the picks of the current tile.
+    __shared__ __attribute__((aligned(1024))) uint16_t sQ[64 * D];
+    extern __shared__ float s_score[];  // [Nb rounded up to 32][64], only for the LDS picks
     const int lane = threadIdx.x & 63, lq = lane & 31, h = lane >> 5;
-    float *s_score = s_score_all + (size_t)(threadIdx.x >> 6) * ((Nb + 31) / 32 * 32) * 64;
     const int unit = blockIdx.y;  // b * Hq + h
     const int b = unit / Hq, hq = unit % Hq, kvh = hq / (Hq / Hkv);
-    const long t_tile = ((long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * 64;
-    const long t_last = (t_tile + 63 < T) ? t_tile + 63 : T - 1;
-    const int own_max = (t_tile < T) ? (int)(t_last / block) : -1;  // uniform over the wave; -1: nothing to do
+    const long n_tiles = (T + 63) / 64;
+    if ((long)blockIdx.x >= n_tiles) return;
 
+    const int srow = lane / CR;
+    auto stage_q = [&](long t_tile) __attribute__((always_inline)) {
+        const LdsSource src = lds_source(q + ((long)unit * T + t_tile) * D);
+        const int last = (int)((T - 1 - t_tile < 63) ? T - 1 - t_tile : 63);  // rows past the end repeat the last one
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int row = i * RW + srow;
+            const int r = (row < last) ? row : last;
+            load16_to_lds(src, (uint32_t)(r * D + (((lane % CR) ^ chunk_swizzle<D>(row)) * 8)) * 2u, sQ + i * RW * D);
+        }
+    };
+    stage_q((long)blockIdx.x * 64);
+
+    const uint16_t *sbase = split + (long)(b * Hkv + kvh) * ((Nb + 31) / 32) * 3 * 32 * D;  // wave-uniform
+    const LdsSource means_src = lds_source(sbase);  // operand loads: descriptor + scalar offset + 16 bytes per lane
+    // scores of blocks j0 .. j0 + 31 against this wave's 64 queries
+    auto scores = [&](int j0, const gate_bf16x8 (&qf)[2][NC], gate_f32x16 (&acc)[2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[qt][v] = 0.f;
+        const int frag = (j0 / 32) * 3 * 32 * D * 2;  // byte offset of the group's [term][chunk][lane][8]: 1 KB per operand
+        // operands are fetched two chunks ahead of the matrix instructions that use them
+        gate_bf16x8 m[3][3];
+        auto fetch = [&](int c) __attribute__((always_inline)) {
+#pragma unroll
+            for (int term = 0; term < 3; ++term)
+                m[c % 3][term] = __builtin_bit_cast(gate_bf16x8, __builtin_amdgcn_raw_buffer_load_b128(means_src, lane * 16, frag + (term * NC + c) * 1024, 0));
+        };
+        fetch(0);
+        fetch(1);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if (c + 2 < NC) fetch(c + 2);
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+                acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m[c % 3][2], qf[qt][c], acc[qt], 0, 0, 0);
+                acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m[c % 3][1], qf[qt][c], acc[qt], 0, 0, 0);
+                acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m[c % 3][0], qf[qt][c], acc[qt], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the fetch distance: no sinking of the loads to their uses
+        }
+    };
+    for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const long t_tile = tile * 64;
+    const long t_last = (t_tile + 63 < T) ? t_tile + 63 : T - 1;
+    const int own_max = (int)(t_last / block);  // uniform over the wave
+    const bool more = tile + gridDim.x < n_tiles;
     // B operands: this lane's two query rows (tokens t_tile + lq and t_tile + 32 + lq, clamped)
     gate_bf16x8 qf[2][NC];
     int own_q[2];
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the tile's rows are in LDS
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         const long t = t_tile + 32 * qt + lq;
         const long tc = (t < T) ? t : T - 1;
         own_q[qt] = (int)(tc / block);
-        const bf16 *qrow = q + ((long)unit * T + tc) * D + 8 * h;
+        const int row = 32 * qt + lq;
+        const int sw = chunk_swizzle<D>(row);
 #pragma unroll
-        for (int c = 0; c < NC; ++c) qf[qt][c] = *reinterpret_cast<const gate_bf16x8 *>(qrow + 16 * c);
+        for (int c = 0; c < NC; ++c) qf[qt][c] = *reinterpret_cast<const gate_bf16x8 *>(&sQ[row * D + (((2 * c + h) ^ sw) * 8)]);
     }
-    const uint16_t *sbase = split + (long)(b * Hkv + kvh) * Nb * 3 * D;
-    // scores of blocks j0 .. j0 + 31 against this wave's 64 queries
-    auto scores = [&](int j0, gate_f32x16 (&acc)[2]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[qt][v] = 0.f;
-        const int jr = (j0 + lq < Nb) ? j0 + lq : Nb - 1;  // A operand row of this lane (clamped; extra rows are never read back)
-        const uint16_t *mrow = sbase + (long)jr * 3 * D + 8 * h;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const gate_bf16x8 m1 = *reinterpret_cast<const gate_bf16x8 *>(mrow + 16 * c);
-            const gate_bf16x8 m2 = *reinterpret_cast<const gate_bf16x8 *>(mrow + D + 16 * c);
-            const gate_bf16x8 m3 = *reinterpret_cast<const gate_bf16x8 *>(mrow + 2 * D + 16 * c);
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt) {
-                acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m3, qf[qt][c], acc[qt], 0, 0, 0);
-                acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m2, qf[qt][c], acc[qt], 0, 0, 0);
-                acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m1, qf[qt][c], acc[qt], 0, 0, 0);
-            }
-        }
-    };
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the operands are in registers, the LDS tile is free again
     // accumulator value v of lane (lq, h): block j0 + 8 (v / 4) + 4 h + v % 4, query lq
-    if (K <= 4 && own_max < 64 && own_max >= 0) {
+    if constexpr (REG) {
         float sc[2][2][16];  // [block group][query tile][value]; -inf: not a candidate
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
             if (32 * g <= own_max) {
                 gate_f32x16 acc[2];
-                scores(32 * g, acc);
+                scores(32 * g, qf, acc);
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
@@ -223,8 +268,9 @@ __global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restr
                     for (int v = 0; v < 16; ++v) sc[g][qt][v] = -INFINITY;
             }
         }
-        uint32_t mask[2][2];  // [query tile][block group]: picked blocks, complete after the exchange
-        bool exact = true;
+        if (more) stage_q((tile + gridDim.x) * 64);  // lands under the picks
+        // half h writes the picks of query tile h (token t_tile + 32 h + lq) as a 64-bit mask of blocks
+        uint64_t picks = 0;
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
             // the four largest of this half-lane's values, then of both halves
@@ -243,47 +289,46 @@ __global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restr
             const int avail = own_q[qt] + 1;
             const int take = (K < avail) ? K : avail;
             const float thr = (take == 1) ? a4 : (take == 2) ? b4 : (take == 3) ? c4 : d4;
-            int cnt = 0;
+            // blocks of this query (both halves) whose score passes `test` against the threshold
+            auto blocks_where = [&](auto test) __attribute__((always_inline)) {
+                uint32_t w[2];
 #pragma unroll
-            for (int g = 0; g < 2; ++g) {
-                uint32_t m = 0u;
+                for (int g = 0; g < 2; ++g) {
+                    uint32_t m = 0u;
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    if (sc[g][qt][v] >= thr) m |= 1u << (8 * (v / 4) + (v % 4));
-                m <<= 4 * h;
-                m |= (uint32_t)__shfl_xor((int)m, 32, 64);
-                mask[qt][g] = m;
-                cnt += __popc(m);
-            }
-            exact = exact && (cnt == take);
-        }
-        if (!__any(!exact)) {
-            // half h writes the picks of query tile h: token t_tile + 32 h + lq, ascending blocks
-            const long t = t_tile + 32 * h + lq;
-            if (t < T) {
-                uint64_t m = h ? (((uint64_t)mask[1][1] << 32) | mask[1][0]) : (((uint64_t)mask[0][1] << 32) | mask[0][0]);
-                int32_t *dst = idx_out + ((long)unit * T + t) * K;
-                for (int n = 0; n < K; ++n) {
-                    dst[n] = m ? (int32_t)__builtin_ctzll(m) : -1;
-                    m &= m - 1;
+                    for (int v = 0; v < 16; ++v)
+                        if (test(sc[g][qt][v], thr)) m |= 1u << (8 * (v / 4) + (v % 4));
+                    m <<= 4 * h;
+                    w[g] = m | (uint32_t)__shfl_xor((int)m, 32, 64);
+                }
+                return ((uint64_t)w[1] << 32) | w[0];
+            };
+            uint64_t sel = blocks_where([](float x, float t) { return x >= t; });
+            if (__any(__popcll(sel) != take)) {
+                // an exact tie at the threshold: everything above it, then the tied blocks in index order
+                const uint64_t above = blocks_where([](float x, float t) { return x > t; });
+                uint64_t tied = sel & ~above;
+                sel = above;
+                for (int r = take - __popcll(above); r > 0; --r) {
+                    sel |= tied & (0 - tied);
+                    tied &= tied - 1;
                 }
             }
-            return;
+            if (qt == h) picks = sel;
         }
-        // an exact tie at some threshold: through LDS, where the sweeps settle it by block order
-#pragma unroll
-        for (int g = 0; g < 2; ++g)
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int j = 32 * g + 8 * (v / 4) + 4 * h + (v % 4);
-                    if (32 * g <= own_max) s_score[j * 64 + 32 * qt + lq] = sc[g][qt][v];
-                }
+        const long t = t_tile + 32 * h + lq;
+        if (t < T) {
+            int32_t *dst = idx_out + ((long)unit * T + t) * K;
+            for (int n = 0; n < K; ++n) {
+                dst[n] = picks ? (int32_t)__builtin_ctzll(picks) : -1;
+                picks &= picks - 1;
+            }
+        }
+        continue;
     } else {
         for (int j0 = 0; j0 <= own_max; j0 += 32) {
             gate_f32x16 acc[2];
-            scores(j0, acc);
+            scores(j0, qf, acc);
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
@@ -295,6 +340,7 @@ __global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restr
                 }
         }
     }
+    if (more) stage_q((tile + gridDim.x) * 64);  // lands under the picks
     __syncthreads();
     // the picks: thread = query token, candidates 0 .. own.  The sweeps run to the wave-uniform
     // bound own_max in steps of four (rows up to the next multiple of 32 exist in LDS), so that
@@ -335,13 +381,16 @@ __global__ __launch_bounds__(256) void moba_gate_mfma_kernel(const bf16 *__restr
         }
         for (; n < K; ++n) dst[n] = -1;
     }
+    __syncthreads();  // the score columns are rewritten by the next tile
+    }  // tiles
 }
 
-// workspace: the block means as three bfloat16 terms, [batch * KV heads][blocks][3][D]
+// workspace: the block means as three bfloat16 terms in matrix-operand order,
+// [batch * KV heads][groups of 32 blocks][3][D / 16][64 lanes][8]
 size_t moba_select_ws_bytes(const rs_shape *s, long T, int block)
 {
-    const size_t Nb = (size_t)((T + block - 1) / block);
-    return RS_WS_CTRL_BYTES + (((size_t)s->B * s->Hkv * Nb * 3 * s->D * 2 + 255) & ~(size_t)255);
+    const size_t Ng = (size_t)(((T + block - 1) / block + 31) / 32);
+    return RS_WS_CTRL_BYTES + (((size_t)s->B * s->Hkv * Ng * 32 * 3 * s->D * 2 + 255) & ~(size_t)255);
 }
 
 int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, long T, int block, int K,
@@ -351,14 +400,19 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     const int Nb = (int)((T + block - 1) / block);
     if (Nb > 256) return RS_UNSUPPORTED;  // one LDS score column per thread: Nb * 256 bytes
     const dim3 g1((unsigned)Nb, (unsigned)(s->B * s->Hkv));
+    const dim3 g1p((unsigned)((Nb + 31) / 32 * 32), (unsigned)(s->B * s->Hkv));  // with the split's padding rows
     const dim3 g2((unsigned)((T + 63) / 64), (unsigned)(s->B * s->Hq));
     const size_t lds = (size_t)Nb * 64 * 4;
     const size_t lds_wave = (size_t)((Nb + 31) / 32 * 32) * 64 * 4;
-    // one wave per workgroup measured fastest (the per-wave LDS score table bounds occupancy,
-    // and small workgroups pack the CUs' LDS best)
-    const int wpg = 1;
-    const size_t lds_mfma = lds_wave * wpg;
-    const dim3 g3((unsigned)((T + 64 * wpg - 1) / (64 * wpg)), (unsigned)(s->B * s->Hq));
+    // the gate kernel: one-wave workgroups, about eight per CU, each walking over the 64-token
+    // tiles of one (batch, head)
+    const bool in_registers = K <= 4 && Nb <= 64;  // its register picks need no score columns
+    const size_t lds_mfma = in_registers ? 0 : lds_wave;
+    const long n_tiles = (T + 63) / 64, units = (long)s->B * s->Hq;
+    long per_unit = (2048 + units - 1) / units;
+    if (const char *e = getenv("RATSPARSE_GATE_WAVES")) per_unit = (atol(e) + units - 1) / units;
+    if (per_unit < 1) per_unit = 1;
+    const dim3 g3((unsigned)(n_tiles < per_unit ? n_tiles : per_unit), (unsigned)units);
 #define RS_LAUNCH(ST, DD)                                                                                          \
     do {                                                                                                           \
         moba_block_means_kernel<ST, DD><<<g1, 256, 0, stream>>>((const ST *)k_cache, means_out, nullptr, s->Tcap, T, block, Nb); \
@@ -367,11 +421,13 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     } while (0)
     if (s->dtype == RS_BF16) {
         if (s->D == 128) {
-            moba_block_means_kernel<bf16, 128><<<g1, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
-            moba_gate_mfma_kernel<128><<<g3, 64 * wpg, lds_mfma, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
+            moba_block_means_kernel<bf16, 128><<<g1p, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
+            if (in_registers) moba_gate_mfma_kernel<128, true><<<g3, 64, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
+            else moba_gate_mfma_kernel<128, false><<<g3, 64, lds_mfma, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
         } else {
-            moba_block_means_kernel<bf16, 64><<<g1, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
-            moba_gate_mfma_kernel<64><<<g3, 64 * wpg, lds_mfma, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
+            moba_block_means_kernel<bf16, 64><<<g1p, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
+            if (in_registers) moba_gate_mfma_kernel<64, true><<<g3, 64, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
+            else moba_gate_mfma_kernel<64, false><<<g3, 64, lds_mfma, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
         }
     } else {
         if (s->D == 128) RS_LAUNCH(float, 128);
