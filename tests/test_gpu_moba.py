@@ -29,6 +29,7 @@ CASES = [
     (synth.C4.scaled(B=1, Hq=4, Hkv=2), 1000, 1024, 64, 4, 1),      # GQA, ragged tail block, first block kept
     (synth.C4.scaled(B=2, Hq=2, Hkv=2, D=64), 777, 800, 128, 2, 0),  # D=64, T not a multiple of anything
     (synth.C4.scaled(B=1, Hq=2, Hkv=1), 512, 512, 16, 8, 0),         # small blocks inside one row tile
+    (synth.C4.scaled(B=2, Hq=4, Hkv=2), 1024, 1024, 128, 3, 0),      # 8 (batch, head) units: the XCD-aware tile order
     # the paper's own MoBA settings (App. A.1; Tables 3-4): T = 4096, 64-token blocks with
     # top-16 / 8 / 4, 128-token blocks with top-8 / 4
     (synth.C4.scaled(B=1, Hq=2, Hkv=2), 4096, 4096, 64, 16, 0),
