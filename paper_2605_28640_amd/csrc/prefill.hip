@@ -20,7 +20,8 @@
 // The softmax runs in the base-2 domain (one FMA + one v_exp_f32 per score), moves its
 // reference point (and rescales the accumulators) only when a row maximum has grown by more
 // than 2^8, and masks only on steps a boundary crosses.  Partials are kept as bfloat16 o
-// (float32 log-sum-exp), in the accumulator's lane order.
+// (float32 log-sum-exp).  Output rows and partial records pass through LDS on their way out
+// and in, so that global memory sees whole 2 D-byte rows.
 #include "common.h"
 
 #include <type_traits>
@@ -34,7 +35,6 @@ constexpr int kMT = 128;        // query rows per workgroup tile (4 waves x 32)
 constexpr int kKT = 64;         // keys per step (two 32-key MFMA sub-tiles)
 constexpr uint32_t kSlotShift = 27;
 constexpr float kLazy = 8.f;    // slack (base-2 exponent) before the softmax reference point moves
-constexpr int kMS = 2;          // partial records merged per round of loads
 
 // ------------------------------------------------------------------------------------
 // bucketing of (row, slot) pairs by picked block
@@ -150,7 +150,7 @@ struct PrefillParams {
     const uint32_t *off, *tile_off, *cnt, *list;
     const TileDesc *desc;
     long desc_stride;
-    uint16_t *part_o;          // [units][T][K][D] bf16, channels in the accumulator's lane order
+    uint16_t *part_o;          // [units][T][K][D] bf16
     float *part_lse;           // [units][T][K]
     bf16 *out;
     float *lse_out;
@@ -482,40 +482,72 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
     }
 
-    if (tq < 0) return;
+    // ---- epilogue ----
+    // Rows leave (and partial records enter) through LDS, so that global memory sees whole rows:
+    // a lane that wrote its own row's channels straight from the accumulator layout would touch
+    // 64 cache lines per store instruction.  After the last step's barrier the four tile buffers
+    // are free; wave w takes buffer w as 64 private rows of D bf16 (two slots of 32 rows), chunks
+    // permuted as in the K/V tiles.  Rows are in channel order: the lane of query row lq, half h
+    // holds channels 32 dt + 8 g + 4 h + {0..3} in oacc[dt][4 g ..].
+    const bool wave_live = gathered ? ((uint32_t)(wave * 32) < lcount) : (r0 + wave * 32 < a.T);
+    if (!wave_live) return;  // no barrier below
+    uint16_t *stg = (wave == 0) ? sK0 : (wave == 1) ? sK1 : (wave == 2) ? sV0 : sV1;
+    const int sw_lq = chunk_swizzle<D>(lq);
+    const int frow = lane / CR, fchunk = lane % CR;  // flush: RW rows of CR chunks per instruction
+    auto put_rows = [&](float sc) __attribute__((always_inline)) {
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                uint2 w2;
+                w2.x = pack_bf16x2(oacc[dt][4 * g] * sc, oacc[dt][4 * g + 1] * sc);
+                w2.y = pack_bf16x2(oacc[dt][4 * g + 2] * sc, oacc[dt][4 * g + 3] * sc);
+                *reinterpret_cast<uint2 *>(stg + lq * D + (((4 * dt + g) ^ sw_lq) * 8) + 4 * h) = w2;
+            }
+    };
+    auto flush_rows = [&](auto dest_of_row) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 32 / RW; ++i) {
+            const int row = i * RW + frow;
+            bf16 *dst = dest_of_row(i, row);
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * D + ((fchunk ^ chunk_swizzle<D>(row)) * 8));
+            if (dst) *reinterpret_cast<uint4 *>(dst + fchunk * 8) = v;
+        }
+    };
     const float inv = (l > 0.f) ? 1.f / l : 0.f;
     const float lse = (l > 0.f) ? (m + __log2f(l)) * 0.6931471805599453f : -INFINITY;
-    // A partial record keeps a row's normalised output over one listed block as bf16, laid out
-    // so that each lane's 64 (D = 128) channels -- d = 32 dt + 8 g + 4 h + i -- are contiguous:
-    // half h of the record, then (dt, g, i).  The log-sum-exp stays float32 in its own array.
     if (a.idx != nullptr && gathered) {
-        const long r = ((long)unit * a.T + tq) * a.K + slot;
-        if (h == 0) a.part_lse[r] = lse;
-        uint4 *rec = reinterpret_cast<uint4 *>(a.part_o + r * D + h * (D / 2));
+        // a partial record: the row's normalised output over one listed block as bf16 (channel
+        // order), its log-sum-exp as float32 in an array of its own
+        uint32_t ent[32 / RW];  // list entries of the rows this lane helps to flush
 #pragma unroll
-        for (int u = 0; u < 2 * NDT; ++u) {
-            const int dt = u >> 1, g0 = 2 * (u & 1);
-            uint4 w;
-            w.x = pack_bf16x2(oacc[dt][4 * g0] * inv, oacc[dt][4 * g0 + 1] * inv);
-            w.y = pack_bf16x2(oacc[dt][4 * g0 + 2] * inv, oacc[dt][4 * g0 + 3] * inv);
-            w.z = pack_bf16x2(oacc[dt][4 * g0 + 4] * inv, oacc[dt][4 * g0 + 5] * inv);
-            w.w = pack_bf16x2(oacc[dt][4 * g0 + 6] * inv, oacc[dt][4 * g0 + 7] * inv);
-            rec[u] = w;
+        for (int i = 0; i < 32 / RW; ++i) {
+            const uint32_t rr = (uint32_t)(wave * 32 + i * RW + frow);
+            ent[i] = (rr < lcount) ? a.list[(long)unit * a.list_stride + lbase + rr] : 0xffffffffu;
         }
-    } else if (a.idx != nullptr) {
+        if (tq >= 0 && h == 0) a.part_lse[((long)unit * a.T + tq) * a.K + slot] = lse;
+        put_rows(inv);
+        flush_rows([&](int i, int) -> bf16 * {
+            if (ent[i] == 0xffffffffu) return nullptr;
+            const long t_r = (long)(ent[i] & ((1u << kSlotShift) - 1u));
+            const int slot_r = (int)(ent[i] >> kSlotShift);
+            return reinterpret_cast<bf16 *>(a.part_o) + (((long)unit * a.T + t_r) * a.K + slot_r) * D;
+        });
+        return;
+    }
+    const long wrow0 = r0 + wave * 32;  // contiguous tiles: the wave's first row
+    float out_scale = inv;
+    float out_lse = lse;
+    if (a.idx != nullptr) {
         // own-block tile: fold in the partials the listed-row tiles left for this row's other
-        // blocks (they ran in the previous launch) and write the final output.  Slots are taken
-        // kMS at a time so that their loads are all in flight together.
-        const int own = (int)(tq / a.block);
-        const long rbase = ((long)unit * a.T + tq) * a.K;
+        // blocks (they ran in the previous launch).  Two slots at a time: their records of the
+        // wave's 32 rows come in by row-contiguous direct loads, the lanes then pick their channels.
+        const long tqc = (tq >= 0) ? tq : wrow0;  // padding lanes read a valid row and drop the result
+        const int own = (int)(tqc / a.block);
+        const long rbase = ((long)unit * a.T + tqc) * a.K;
         const int32_t *row = a.idx + rbase;
-        int j0[kMS];
-#pragma unroll
-        for (int i = 0; i < kMS; ++i) j0[i] = (i < a.K) ? row[i] : -1;
         bool own_listed = false;
-#pragma unroll
-        for (int i = 0; i < kMS; ++i) own_listed = own_listed || (j0[i] == own);
-        for (int k = kMS; k < a.K; ++k) own_listed = own_listed || (row[k] == own);
+        for (int k = 0; k < a.K; ++k) own_listed = own_listed || (row[k] == own);
         float M = own_listed ? lse : -INFINITY;  // an own block that is not listed does not count
         float wsum = (M == -INFINITY) ? 0.f : 1.f;
         {
@@ -525,78 +557,74 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                 for (int v = 0; v < 16; ++v) oacc[dt][v] *= w_own;
         }
-        for (int kc = 0; kc < a.K; kc += kMS) {
-            float ls[kMS];
-            uint4 rc[kMS][2 * NDT];
+        const int rows_here = (int)((a.T - wrow0 < 32) ? a.T - wrow0 : 32);  // >= 1
+        for (int kc = 0; kc < a.K; kc += 2) {
+            float ls[2];
+            bool any_valid = false;
 #pragma unroll
-            for (int i = 0; i < kMS; ++i) {
+            for (int i = 0; i < 2; ++i) {
                 const int k = kc + i;
-                const int jk = (kc == 0) ? j0[i] : ((k < a.K) ? row[k] : -1);
-                const bool valid = jk >= 0 && jk != own;
-                ls[i] = -INFINITY;
+                const int jk = (k < a.K) ? row[k] : -1;
+                const bool valid = jk >= 0 && jk != own && tq >= 0;
+                ls[i] = valid ? a.part_lse[rbase + k] : -INFINITY;
+                any_valid = any_valid || valid;
+            }
+            if (!__any(any_valid)) continue;  // wave-uniform
 #pragma unroll
-                for (int u = 0; u < 2 * NDT; ++u) rc[i][u] = make_uint4(0u, 0u, 0u, 0u);
-                if (valid) {
-                    ls[i] = a.part_lse[rbase + k];
-                    const uint4 *rec = reinterpret_cast<const uint4 *>(a.part_o + (rbase + k) * D + h * (D / 2));
+            for (int i = 0; i < 2; ++i) {
+                const int k = (kc + i < a.K) ? kc + i : a.K - 1;
+                const LdsSource src = lds_source(reinterpret_cast<const bf16 *>(a.part_o) + (((long)unit * a.T + wrow0) * a.K + k) * D);
 #pragma unroll
-                    for (int u = 0; u < 2 * NDT; ++u) rc[i][u] = rec[u];
+                for (int j = 0; j < 32 / RW; ++j) {
+                    const int rr = j * RW + frow;
+                    const int rc = (rr < rows_here) ? rr : rows_here - 1;
+                    load16_to_lds(src, (uint32_t)(rc * a.K * D + ((fchunk ^ chunk_swizzle<D>(rr)) * 8)) * 2u,
+                                  stg + (i * 32 + j * RW) * D);
                 }
             }
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the records are in LDS
+            uint2 rc2[2][4 * NDT];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int u = 0; u < 4 * NDT; ++u)
+                    rc2[i][u] = *reinterpret_cast<const uint2 *>(stg + (i * 32 + lq) * D + ((u ^ sw_lq) * 8) + 4 * h);
             float Mn = M;
 #pragma unroll
-            for (int i = 0; i < kMS; ++i) Mn = fmaxf(Mn, ls[i]);
-            if (Mn == -INFINITY) continue;
-            const float al = (M == -INFINITY) ? 0.f : __expf(M - Mn);
-            M = Mn;
-            wsum *= al;
+            for (int i = 0; i < 2; ++i) Mn = fmaxf(Mn, ls[i]);
+            if (Mn != -INFINITY) {
+                const float al = (M == -INFINITY) ? 0.f : __expf(M - Mn);
+                M = Mn;
+                wsum *= al;
 #pragma unroll
-            for (int dt = 0; dt < NDT; ++dt)
+                for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) oacc[dt][v] *= al;
+                    for (int v = 0; v < 16; ++v) oacc[dt][v] *= al;
 #pragma unroll
-            for (int i = 0; i < kMS; ++i) {
-                const float w = (ls[i] == -INFINITY) ? 0.f : __expf(ls[i] - M);
-                wsum += w;
+                for (int i = 0; i < 2; ++i) {
+                    const float w = (ls[i] == -INFINITY) ? 0.f : __expf(ls[i] - M);
+                    wsum += w;
+                    if (ls[i] != -INFINITY) {  // a record that was never written may hold anything
 #pragma unroll
-                for (int u = 0; u < 2 * NDT; ++u) {
-                    const int dt = u >> 1, v0 = 8 * (u & 1);
-                    const uint32_t ww[4] = {rc[i][u].x, rc[i][u].y, rc[i][u].z, rc[i][u].w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        oacc[dt][v0 + 2 * e] = fmaf(w, __uint_as_float(ww[e] << 16), oacc[dt][v0 + 2 * e]);
-                        oacc[dt][v0 + 2 * e + 1] = fmaf(w, __uint_as_float(ww[e] & 0xffff0000u), oacc[dt][v0 + 2 * e + 1]);
+                        for (int u = 0; u < 4 * NDT; ++u) {
+                            const int dt = u >> 2, g = u & 3;
+                            oacc[dt][4 * g] = fmaf(w, __uint_as_float(rc2[i][u].x << 16), oacc[dt][4 * g]);
+                            oacc[dt][4 * g + 1] = fmaf(w, __uint_as_float(rc2[i][u].x & 0xffff0000u), oacc[dt][4 * g + 1]);
+                            oacc[dt][4 * g + 2] = fmaf(w, __uint_as_float(rc2[i][u].y << 16), oacc[dt][4 * g + 2]);
+                            oacc[dt][4 * g + 3] = fmaf(w, __uint_as_float(rc2[i][u].y & 0xffff0000u), oacc[dt][4 * g + 3]);
+                        }
                     }
                 }
             }
         }
-        const float winv = (wsum > 0.f) ? 1.f / wsum : 0.f;
-        bf16 *orow = a.out + ((long)unit * a.T + tq) * D;
-        if (h == 0 && a.lse_out) a.lse_out[(long)unit * a.T + tq] = (wsum > 0.f) ? M + __logf(wsum) : -INFINITY;
-#pragma unroll
-        for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int d = 32 * dt + 8 * g + 4 * h;
-                uint2 w2;
-                w2.x = pack_bf16x2(oacc[dt][4 * g] * winv, oacc[dt][4 * g + 1] * winv);
-                w2.y = pack_bf16x2(oacc[dt][4 * g + 2] * winv, oacc[dt][4 * g + 3] * winv);
-                *reinterpret_cast<uint2 *>(orow + d) = w2;
-            }
-    } else {
-        bf16 *orow = a.out + ((long)unit * a.T + tq) * D;
-        if (h == 0 && a.lse_out) a.lse_out[(long)unit * a.T + tq] = lse;
-#pragma unroll
-        for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int d = 32 * dt + 8 * g + 4 * h;
-                uint2 w;
-                w.x = pack_bf16x2(oacc[dt][4 * g] * inv, oacc[dt][4 * g + 1] * inv);
-                w.y = pack_bf16x2(oacc[dt][4 * g + 2] * inv, oacc[dt][4 * g + 3] * inv);
-                *reinterpret_cast<uint2 *>(orow + d) = w;
-            }
+        out_scale = (wsum > 0.f) ? 1.f / wsum : 0.f;
+        out_lse = (wsum > 0.f) ? M + __logf(wsum) : -INFINITY;
     }
+    if (tq >= 0 && h == 0 && a.lse_out) a.lse_out[(long)unit * a.T + tq] = out_lse;
+    put_rows(out_scale);
+    flush_rows([&](int, int row) -> bf16 * {
+        return (wrow0 + row < a.T) ? a.out + ((long)unit * a.T + wrow0 + row) * D : nullptr;
+    });
 }
 
 __global__ void prefill_zero_kernel(uint32_t *p, long n)
