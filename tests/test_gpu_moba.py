@@ -40,6 +40,28 @@ CASES = [
 ]
 
 
+def _random_cases(seed, n):
+    """Seeded random small shapes: head counts and grouping, both head dims, block sizes from 16
+    to 256, ragged lengths, 1-8 picked blocks, 0-1 always-kept leading blocks."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        Hkv = int(rng.integers(1, 3))
+        G = int(rng.choice([1, 2]))
+        D = int(rng.choice([64, 128]))
+        block = int(rng.choice([16, 32, 64, 128, 256]))
+        T = int(rng.integers(block + 1, 1400))
+        Tcap = -(-T // 16) * 16 + 16 * int(rng.integers(0, 3))
+        n_first = int(rng.integers(0, 2))
+        K = int(rng.integers(1 + n_first, 9))
+        w = synth.C4.scaled(B=int(rng.integers(1, 3)), Hq=Hkv * G, Hkv=Hkv, D=D)
+        out.append((w, T, Tcap, block, K, n_first))
+    return out
+
+
+CASES += _random_cases(20260528, 8)
+
+
 @pytest.mark.parametrize("case", range(len(CASES)))
 def test_moba_select_and_sparse_prefill(rs, case):
     w, T, Tcap, block, K, n_first = CASES[case]

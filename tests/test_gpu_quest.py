@@ -52,6 +52,32 @@ CASES = [
 ]
 
 
+def _random_cases(seed, n):
+    """Seeded random small shapes: head counts and grouping, both head dims and dtypes, every
+    page size, ragged lengths, budgets from one page to all of them, 0-2 forced pages per end."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        Hkv = int(rng.integers(1, 4))
+        G = int(rng.choice([1, 2, 4]))
+        D = int(rng.choice([64, 128]))
+        dtype = str(rng.choice(["bf16", "f32"]))
+        P = int(rng.choice([16, 32, 64, 128]))
+        T = int(rng.integers(P + 1, 2500))
+        Np = -(-T // P)
+        Tcap = Np * P + P * int(rng.integers(0, 3))
+        n_first, n_local = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+        forced = min(n_first + n_local, Np)
+        K = int(rng.integers(max(1, forced), Np + 1))
+        w = synth.C1.scaled(B=int(rng.integers(1, 4)), Hq=Hkv * G, Hkv=Hkv, D=D, dtype=dtype,
+                            n_needles=0 if T < 64 else 4)
+        out.append((w, T, Tcap, P, K, n_first, n_local))
+    return out
+
+
+CASES += _random_cases(20260528, 12)
+
+
 @pytest.mark.parametrize("case", range(len(CASES)))
 def test_meta_select_attend(rs, case):
     w, T, Tcap, P, K, n_first, n_local = CASES[case]

@@ -44,9 +44,15 @@ def test_c1_tiny_fp32(rs):
     assert np.all(kc[:, :, w.T:] == 0) and np.all(vc[:, :, w.T:] == 0)  # nothing written past T
 
 
+def _random_scan_cases(seed, n):
+    rng = np.random.default_rng(seed)
+    return [(str(rng.choice(["bf16", "f32"])), int(rng.choice([64, 128])), int(rng.integers(1, 6000)),
+             int(rng.integers(1, 3)), int(rng.integers(1, 4))) for _ in range(n)]
+
+
 @pytest.mark.parametrize("dtype,D,T,B,H", [("bf16", 128, 3 * 128 + 37, 2, 3), ("bf16", 64, 700, 1, 2),
                                            ("f32", 128, 333, 1, 2), ("bf16", 128, 9, 1, 1),
-                                           ("bf16", 128, 128, 1, 2)])
+                                           ("bf16", 128, 128, 1, 2)] + _random_scan_cases(20260528, 8))
 def test_ragged_lengths_carry_in_and_offset(rs, dtype, D, T, B, H):
     say("scan ragged", dtype, D, T, B, H)
     r = np.random.default_rng(T)

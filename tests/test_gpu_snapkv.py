@@ -36,6 +36,28 @@ CASES = [
 ]
 
 
+def _random_cases(seed, n):
+    """Seeded random small shapes: grouping 1-4, both head dims, windows of 4-64 rows, ragged
+    lengths, kept counts from a handful to everything, odd pooling kernels 1-9."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        Hkv = int(rng.integers(1, 3))
+        G = int(rng.choice([1, 2, 4]))
+        D = int(rng.choice([64, 128]))
+        W = int(rng.integers(4, 65))
+        T = int(rng.integers(W + 40, 2200))
+        Tcap = -(-T // 16) * 16 + 16 * int(rng.integers(0, 3))
+        K_keep = int(rng.integers(1, T - W + 1)) if rng.random() < 0.8 else T - W
+        pool = int(rng.choice([1, 3, 5, 7, 9]))
+        w = synth.C5.scaled(B=int(rng.integers(1, 3)), Hq=Hkv * G, Hkv=Hkv, D=D, W=W)
+        out.append((w, T, Tcap, K_keep, pool))
+    return out
+
+
+CASES += _random_cases(20260528, 8)
+
+
 @pytest.mark.parametrize("case", range(len(CASES)))
 def test_snapkv_compress_then_decode(rs, case):
     w, T, Tcap, K_keep, pool = CASES[case]
