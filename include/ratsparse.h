@@ -29,6 +29,11 @@
  *     A kernel-side failure of a bounded wait is recorded in the workspace and
  *     reported by ratsparse_async_status().
  *   - Outputs must not alias inputs.
+ *   - Stream capture: quest_page_meta, moba_select_prefill, sparse_attn_prefill and
+ *     snapkv_compress keep no per-call state on the host and may be captured into a
+ *     HIP graph and replayed.  rat_scan, quest_select_decode and sparse_attn_decode
+ *     hand a fresh call tag to their kernels on every call (it tells this call's
+ *     words in the workspace from stale ones) and must be called, not replayed.
  */
 #ifndef RATSPARSE_H
 #define RATSPARSE_H
