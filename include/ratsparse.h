@@ -65,7 +65,7 @@ typedef struct rs_shape {
     int32_t Hkv;   /* KV heads, divides Hq */
     int32_t D;     /* head dimension: 64 or 128 */
     int32_t Tcap;  /* rows per (batch, KV head) of the caches (row stride); multiple of P */
-    int32_t P;     /* Quest page size in tokens: 16, 32, 64 or 128 (used by the page entry points) */
+    int32_t P;     /* Quest page size in tokens: 16, 32, 64, 128, 256 or 512 (used by the page entry points) */
     int32_t dtype; /* RS_F32 or RS_BF16 */
 } rs_shape;
 

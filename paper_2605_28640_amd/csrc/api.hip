@@ -72,7 +72,7 @@ static int check_shape(const rs_shape *s, bool need_page)
     if (s->dtype != RS_F32 && s->dtype != RS_BF16) return RS_UNSUPPORTED;
     if (s->D != 64 && s->D != 128) return RS_UNSUPPORTED;
     if (need_page) {
-        if (s->P != 16 && s->P != 32 && s->P != 64 && s->P != 128) return RS_UNSUPPORTED;
+        if (s->P != 16 && s->P != 32 && s->P != 64 && s->P != 128 && s->P != 256 && s->P != 512) return RS_UNSUPPORTED;
         if (s->Tcap % s->P != 0) return RS_INVALID_ARG;
     }
     if ((long)s->B * s->Hq > kMaxUnits) return RS_UNSUPPORTED;

@@ -49,6 +49,9 @@ CASES = [
     (synth.C3.scaled(B=1, Hq=4, Hkv=4), 4096, 4096 + 64, 64, 8, 1, 1),
     (synth.C3.scaled(B=1, Hq=4, Hkv=4), 4096, 4096 + 64, 64, 4, 1, 1),
     (synth.C3.scaled(B=1, Hq=4, Hkv=4), 4096, 4096 + 64, 16, 4, 1, 1),
+    # large pages
+    (synth.C3.scaled(B=1, Hq=4, Hkv=2), 8192 + 77, 8192 + 512, 512, 5, 1, 1),
+    (synth.C3.scaled(B=2, Hq=2, Hkv=2), 6000, 6144, 256, 6, 0, 1),
 ]
 
 
@@ -62,7 +65,7 @@ def _random_cases(seed, n):
         G = int(rng.choice([1, 2, 4]))
         D = int(rng.choice([64, 128]))
         dtype = str(rng.choice(["bf16", "f32"]))
-        P = int(rng.choice([16, 32, 64, 128]))
+        P = int(rng.choice([16, 32, 64, 128, 256]))
         T = int(rng.integers(P + 1, 2500))
         Np = -(-T // P)
         Tcap = Np * P + P * int(rng.integers(0, 3))
