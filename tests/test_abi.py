@@ -96,6 +96,13 @@ def test_every_entry_point_rejects_bad_arguments_before_touching_the_gpu():
     assert lib.snapkv_compress(sp, A, A, A, 256, 32, 64, 7, 0.1, A, A, 64, A, None, A, big, None) == 1    # output too short
     assert lib.snapkv_compress(sp, A, A, A, 256, 32, 64, 7, 0.1, A, A, 128, A, None, A, 16, None) == 3
 
+    # more pages than the selection's LDS keys hold
+    huge = binding.make_shape(1, 1, 1, 64, 15361 * 16, 16, binding.RS_BF16)
+    hp = ctypes.byref(huge)
+    n = lib.sparse_attn_decode_workspace_bytes(hp, 15361 * 16, 4)
+    assert lib.quest_select_decode(hp, A, A, 15361 * 16, 4, 1, 1, A, None, A, n, None) == 2
+    assert lib.sparse_attn_decode(hp, A, A, A, 15361 * 16, 0.1, None, 4, A, 1, 1, A, None, None, A, n, None) == 2
+
     # shapes
     for bad in (binding.make_shape(0, 4, 2, 128, 256, 16, binding.RS_BF16),
                 binding.make_shape(1, 4, 2, 128, 250, 16, binding.RS_BF16)):  # Tcap not a multiple of P

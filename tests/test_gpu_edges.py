@@ -33,6 +33,8 @@ DECODE = [
     (synth.C2.scaled(Hq=4, Hkv=2), 1024, 1024, 16, 7, 1, 1),          # cache filled to its capacity
     (synth.C2.scaled(Hq=4, Hkv=4), 1000, 1024, 128, 3, 1, 1),         # 128-token pages, ragged last page
     (synth.C1, 300, 320, 32, 10, 3, 4),                               # several first / local pages, K = all 10 pages
+    # the largest page count the selection takes (15360 keys in LDS), ragged last page
+    (synth.C1.scaled(Hq=1, Hkv=1, dtype="bf16"), 15360 * 16 - 3, 15360 * 16, 16, 64, 1, 1),
 ]
 
 
@@ -81,6 +83,7 @@ PREFILL = [
     (synth.C4.scaled(B=1, Hq=2, Hkv=1), 64, 64, 64, 2),     # one block: nothing to route
     (synth.C4.scaled(B=1, Hq=2, Hkv=2), 300, 304, 32, 1),   # top-1: every token attends its own block only
     (synth.C4.scaled(B=1, Hq=2, Hkv=2, D=64), 129, 144, 128, 2),  # a second block of one token
+    (synth.C4.scaled(B=1, Hq=2, Hkv=1, D=64), 4096, 4096, 16, 32),  # the most blocks (256) and the largest K (32)
 ]
 
 
