@@ -270,7 +270,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const bool causal = !gathered;
     const long own_begin = (a.idx != nullptr && !gathered && tq >= 0) ? (tq / a.block) * a.block : 0;
     // last key any lane of this wave may see (contiguous tiles): later steps are skipped by the wave
-    const long wave_last = causal ? ((r0 + wave * 32 + 31 < a.T) ? r0 + wave * 32 + 31 : a.T - 1) : kv_end - 1;
+    // (a wave none of whose 32 rows exists skips every step; it still stages its share of the tiles)
+    const bool wave_live = gathered ? ((uint32_t)(wave * 32) < lcount) : (r0 + wave * 32 < a.T);
+    const long wave_last = !wave_live ? -1 : causal ? ((r0 + wave * 32 + 31 < a.T) ? r0 + wave * 32 + 31 : a.T - 1) : kv_end - 1;
 
     // keys visible to this lane's query, as 32-bit offsets from kv_begin (everything for a padding
     // lane: it never triggers the masking path, its results are dropped)
@@ -489,7 +491,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // are free; wave w takes buffer w as 64 private rows of D bf16 (two slots of 32 rows), chunks
     // permuted as in the K/V tiles.  Rows are in channel order: the lane of query row lq, half h
     // holds channels 32 dt + 8 g + 4 h + {0..3} in oacc[dt][4 g ..].
-    const bool wave_live = gathered ? ((uint32_t)(wave * 32) < lcount) : (r0 + wave * 32 < a.T);
     if (!wave_live) return;  // no barrier below
     uint16_t *stg = (wave == 0) ? sK0 : (wave == 1) ? sK1 : (wave == 2) ? sV0 : sV1;
     const int sw_lq = chunk_swizzle<D>(lq);
