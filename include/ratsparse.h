@@ -31,8 +31,8 @@
  *   - Outputs must not alias inputs.
  *   - Stream capture: quest_page_meta, moba_select_prefill, sparse_attn_prefill and
  *     snapkv_compress keep no per-call state on the host and may be captured into a
- *     HIP graph and replayed.  rat_scan, quest_select_decode and sparse_attn_decode
- *     hand a fresh call tag to their kernels on every call (it tells this call's
+ *     HIP graph and replayed.  rat_scan, quest_select_decode and sparse_attn_decode (and
+ *     their _group forms) hand a fresh call tag to their kernels on every call (it tells this call's
  *     words in the workspace from stale ones) and must be called, not replayed.
  */
 #ifndef RATSPARSE_H
@@ -147,6 +147,29 @@ int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache
                            const int32_t *idx, int32_t K, const void *meta, int32_t n_first,
                            int32_t n_local, void *out, float *lse_out, int32_t *idx_out,
                            void *ws, size_t ws_bytes, void *stream);
+
+/* ---- Group-shared Quest selection (an option for grouped-query attention) --------------
+ * Not in the paper, which selects per query head (Sec. 3 defines the selected set per head);
+ * offered for Hq / Hkv in {2, 4, 8} so that the query heads of a KV head share one page set:
+ * Eq. 3 with the score of a page summed over the group,
+ *   score_p = sum_{h in group} sum_c max(q_{h,c} * min_{p,c}, q_{h,c} * max_{p,c}),
+ * still an upper bound of the group's summed logit of any token of the page.  Same rules
+ * for always-kept pages, ties and order as quest_select_decode.
+ *   idx_out    [B, Hkv, K] int32, ascending
+ *   scores_out [B, Hkv, Np] float32 or NULL
+ * sparse_attn_decode_group attends such a list (idx [B, Hkv, K], used by every query head
+ * of the KV head), or with idx == NULL and meta != NULL selects and then attends (two
+ * launches; idx_out [B, Hkv, K] or NULL).  It has no dense mode (RS_INVALID_ARG).
+ * Workspaces are sized by the functions of the per-head forms. */
+int32_t quest_select_decode_group(const rs_shape *s, const void *q, const void *meta,
+                                  int64_t T_valid, int32_t K, int32_t n_first, int32_t n_local,
+                                  int32_t *idx_out, float *scores_out, void *ws,
+                                  size_t ws_bytes, void *stream);
+int32_t sparse_attn_decode_group(const rs_shape *s, const void *q, const void *k_cache,
+                                 const void *v_cache, int64_t T_valid, float scale,
+                                 const int32_t *idx, int32_t K, const void *meta,
+                                 int32_t n_first, int32_t n_local, void *out, float *lse_out,
+                                 int32_t *idx_out, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- MoBA routing at prefill: Sec. 2.2, Eq. 3; App. A.1, MoBA paragraph ----------------
  * Block representative = mean of the stored keys of a block of `block` tokens (the

@@ -106,6 +106,16 @@ def quest_scores(q, meta, Np):
     return s
 
 
+def quest_scores_group(q, meta, Np):
+    """Group-shared selection (an option for grouped-query attention, not in the paper): the
+    page score of a KV head is the sum of the page scores of its query heads.
+    q: [B, Hq, D]; meta: [B, Hkv, Np_cap, 2, D] -> scores [B, Hkv, Np] float64."""
+    per_head = quest_scores(q, meta, Np)
+    B, Hq, _ = per_head.shape
+    Hkv = np.asarray(meta).shape[1]
+    return per_head.reshape(B, Hkv, Hq // Hkv, Np).sum(axis=2)
+
+
 def quest_select(scores, K, n_first, n_local):
     """scores: [B, Hq, Np] -> idx [B, Hq, K] int32 ascending."""
     scores = _f64(scores)

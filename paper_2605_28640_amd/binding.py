@@ -42,6 +42,9 @@ SIGNATURES = {
     "quest_page_meta": (_i32, [_shp, _vp, _vp, _i64, _i64, _vp]),
     "quest_select_decode_workspace_bytes": (_sz, [_shp, _i64]),
     "quest_select_decode": (_i32, [_shp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "quest_select_decode_group": (_i32, [_shp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "sparse_attn_decode_group": (_i32, [_shp, _vp, _vp, _vp, _i64, _f32, _vp, _i32, _vp, _i32, _i32, _vp,
+                                        _vp, _vp, _vp, _sz, _vp]),
     "sparse_attn_decode_workspace_bytes": (_sz, [_shp, _i64, _i32]),
     "sparse_attn_decode": (_i32, [_shp, _vp, _vp, _vp, _i64, _f32, _vp, _i32, _vp, _i32, _i32, _vp,
                                   _vp, _vp, _vp, _sz, _vp]),
@@ -149,6 +152,18 @@ def quest_select_decode_workspace_bytes(s, T_valid):
 def quest_select_decode(s, q, meta, T_valid, K, n_first, n_local, idx_out, scores_out, ws):
     _check(load().quest_select_decode(ctypes.byref(s), _ptr(q), _ptr(meta), T_valid, K, n_first, n_local,
                                       _ptr(idx_out), _ptr(scores_out), ws.ptr, ws.nbytes, _stream()))
+
+
+def quest_select_decode_group(s, q, meta, T_valid, K, n_first, n_local, idx_out, scores_out, ws):
+    _check(load().quest_select_decode_group(ctypes.byref(s), _ptr(q), _ptr(meta), T_valid, K, n_first, n_local,
+                                            _ptr(idx_out), _ptr(scores_out), ws.ptr, ws.nbytes, _stream()))
+
+
+def sparse_attn_decode_group(s, q, k_cache, v_cache, T_valid, scale, idx, K, meta, n_first, n_local, out,
+                             lse_out, idx_out, ws):
+    _check(load().sparse_attn_decode_group(ctypes.byref(s), _ptr(q), _ptr(k_cache), _ptr(v_cache), T_valid,
+                                           scale, _ptr(idx), K, _ptr(meta), n_first, n_local, _ptr(out),
+                                           _ptr(lse_out), _ptr(idx_out), ws.ptr, ws.nbytes, _stream()))
 
 
 def sparse_attn_decode_workspace_bytes(s, T_valid, K):

@@ -16,14 +16,14 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
 // quest.hip
 void page_meta_dispatch(int dtype, int D, const void *k_cache, void *meta, int BH, long Tcap, int P,
                         int p_begin, int n_pages, long t_end, hipStream_t stream);
-int score_select_dispatch(int dtype, int D, const void *q, const void *meta, uint64_t *scores, float *scores_out,
-                          int32_t *idx_out, int B, int Hq, int Hkv, long Np_cap, int Np, int K, int n_first,
-                          int n_local, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit,
-                          hipStream_t stream);
+int score_select_dispatch(int dtype, int D, int GQ, const void *q, const void *meta, uint64_t *scores,
+                          float *scores_out, int32_t *idx_out, int B, int Hq, int Hkv, long Np_cap, int Np, int K,
+                          int n_first, int n_local, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag,
+                          int spin_limit, hipStream_t stream);
 void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache, const void *v_cache,
                             const int32_t *idx, void *out, float *lse_out, uint64_t *partial, int B, int Hq,
                             int Hkv, long Tcap, int P, long T_valid, int K, float scale, int splits,
-                            uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit, hipStream_t stream);
+                            uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit, int idx_per_kv, hipStream_t stream);
 // moba.hip / prefill.hip / snapkv.hip
 size_t moba_select_ws_bytes(const rs_shape *s, long T, int block);
 int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, long T, int block, int K,
@@ -113,6 +113,7 @@ static int env_int(const char *name, int dflt)
 }
 
 constexpr int kMaxAttSplits = 64;
+constexpr int kFusedGroupedMaxUnits = 64;  // grouped-query attention with at most this many units: two launches
 
 struct DecodeLayout {
     int Np, splits_score, splits_att_max;
@@ -299,12 +300,15 @@ size_t quest_select_decode_workspace_bytes(const rs_shape *s, int64_t T_valid)
     return decode_layout(s, T_valid, 1).total;
 }
 
-int32_t quest_select_decode(const rs_shape *s, const void *q, const void *meta, int64_t T_valid, int32_t K,
-                            int32_t n_first, int32_t n_local, int32_t *idx_out, float *scores_out, void *ws,
-                            size_t ws_bytes, void *stream)
+// group: one page list per (batch, KV head) from the summed scores of its query heads
+static int32_t select_decode_impl(bool group, const rs_shape *s, const void *q, const void *meta, int64_t T_valid,
+                                  int32_t K, int32_t n_first, int32_t n_local, int32_t *idx_out, float *scores_out,
+                                  void *ws, size_t ws_bytes, void *stream)
 {
     int st = check_shape(s, true);
     if (st != RS_OK) return st;
+    const int GQ = group ? s->Hq / s->Hkv : 1;
+    if (GQ != 1 && GQ != 2 && GQ != 4 && GQ != 8) return RS_UNSUPPORTED;
     if (!q || !meta || !idx_out || !aligned16(q) || !aligned16(meta) || !aligned16(idx_out)) return RS_INVALID_ARG;
     if (scores_out && !aligned16(scores_out)) return RS_INVALID_ARG;
     st = check_select(s, T_valid, K, n_first, n_local);
@@ -312,12 +316,28 @@ int32_t quest_select_decode(const rs_shape *s, const void *q, const void *meta, 
     const DecodeLayout L = decode_layout(s, T_valid, 1);
     if (!ws || !aligned16(ws) || ws_bytes < L.total) return RS_WORKSPACE_TOO_SMALL;
     char *w = (char *)ws;
-    st = score_select_dispatch(s->dtype, s->D, q, meta, (uint64_t *)(w + L.off_scores), scores_out, idx_out, s->B,
-                               s->Hq, s->Hkv, s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score,
+    st = score_select_dispatch(s->dtype, s->D, GQ, q, meta, (uint64_t *)(w + L.off_scores), scores_out, idx_out,
+                               s->B, s->Hq, s->Hkv, s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score,
                                (uint32_t *)w + kCtrlUnit0, (uint32_t *)w + kCtrlAsyncErr, next_tag(),
                                g_spin_limit.load(), (hipStream_t)stream);
     if (st != RS_OK) return st;
     return launch_status();
+}
+
+int32_t quest_select_decode(const rs_shape *s, const void *q, const void *meta, int64_t T_valid, int32_t K,
+                            int32_t n_first, int32_t n_local, int32_t *idx_out, float *scores_out, void *ws,
+                            size_t ws_bytes, void *stream)
+{
+    return select_decode_impl(false, s, q, meta, T_valid, K, n_first, n_local, idx_out, scores_out, ws, ws_bytes,
+                              stream);
+}
+
+int32_t quest_select_decode_group(const rs_shape *s, const void *q, const void *meta, int64_t T_valid, int32_t K,
+                                  int32_t n_first, int32_t n_local, int32_t *idx_out, float *scores_out, void *ws,
+                                  size_t ws_bytes, void *stream)
+{
+    return select_decode_impl(true, s, q, meta, T_valid, K, n_first, n_local, idx_out, scores_out, ws, ws_bytes,
+                              stream);
 }
 
 size_t sparse_attn_decode_workspace_bytes(const rs_shape *s, int64_t T_valid, int32_t K)
@@ -326,13 +346,15 @@ size_t sparse_attn_decode_workspace_bytes(const rs_shape *s, int64_t T_valid, in
     return decode_layout(s, T_valid, K).total;
 }
 
-int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache, const void *v_cache,
-                           int64_t T_valid, float scale, const int32_t *idx, int32_t K, const void *meta,
-                           int32_t n_first, int32_t n_local, void *out, float *lse_out, int32_t *idx_out, void *ws,
-                           size_t ws_bytes, void *stream)
+static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, const void *k_cache, const void *v_cache,
+                                int64_t T_valid, float scale, const int32_t *idx, int32_t K, const void *meta,
+                                int32_t n_first, int32_t n_local, void *out, float *lse_out, int32_t *idx_out,
+                                void *ws, size_t ws_bytes, void *stream)
 {
     int st = check_shape(s, true);
     if (st != RS_OK) return st;
+    const int GQ = group ? s->Hq / s->Hkv : 1;
+    if (GQ != 1 && GQ != 2 && GQ != 4 && GQ != 8) return RS_UNSUPPORTED;
     if (!q || !k_cache || !v_cache || !out) return RS_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return RS_INVALID_ARG;
     if (T_valid <= 0 || T_valid > s->Tcap) return RS_INVALID_ARG;
@@ -353,7 +375,12 @@ int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache
     const long units = (long)s->B * s->Hq;
     const int32_t *use_idx = idx;
     const uint32_t tag = next_tag();
-    if (fused && !env_int("RATSPARSE_FUSED_TWO_LAUNCH", 0)) {
+    if (group && !listed && !fused) return RS_INVALID_ARG;  // the dense path has no selection to share
+    // one persistent launch, except under grouped-query attention with few units: there the two
+    // plain launches below measured faster (32 heads over 8 KV heads at 32K: 42 against 52 us at
+    // batch 1, 53 against 72 us at batch 2; from 96 units on, and without grouping, the one launch wins)
+    const int two_launch = env_int("RATSPARSE_FUSED_TWO_LAUNCH", (s->Hq > s->Hkv && units <= kFusedGroupedMaxUnits) ? 1 : 0);
+    if (fused && !group && !two_launch) {
         // one persistent launch: score -> select -> attend, handed over through tagged words
         FusedParams prm;
         prm.q = q; prm.meta = meta; prm.k_cache = k_cache; prm.v_cache = v_cache;
@@ -395,7 +422,7 @@ int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache
     }
     if (fused) {
         int32_t *sel = idx_out ? idx_out : (int32_t *)(w + L.off_idx);
-        st = score_select_dispatch(s->dtype, s->D, q, meta, (uint64_t *)(w + L.off_scores), nullptr, sel, s->B,
+        st = score_select_dispatch(s->dtype, s->D, GQ, q, meta, (uint64_t *)(w + L.off_scores), nullptr, sel, s->B,
                                    s->Hq, s->Hkv, s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score,
                                    ctr_score, (uint32_t *)w + kCtrlAsyncErr, tag, g_spin_limit.load(),
                                    (hipStream_t)stream);
@@ -408,9 +435,27 @@ int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache
     if (splits > L.splits_att_max) splits = L.splits_att_max;
     decode_attend_dispatch(s->dtype, s->D, q, k_cache, v_cache, use_idx, out, lse_out,
                            (uint64_t *)(w + L.off_partial), s->B, s->Hq, s->Hkv, s->Tcap, s->P, T_valid, K, scale,
-                           splits, ctr_att, (uint32_t *)w + kCtrlAsyncErr, tag, g_spin_limit.load(),
+                           splits, ctr_att, (uint32_t *)w + kCtrlAsyncErr, tag, g_spin_limit.load(), group ? 1 : 0,
                            (hipStream_t)stream);
     return launch_status();
+}
+
+int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache, const void *v_cache,
+                           int64_t T_valid, float scale, const int32_t *idx, int32_t K, const void *meta,
+                           int32_t n_first, int32_t n_local, void *out, float *lse_out, int32_t *idx_out, void *ws,
+                           size_t ws_bytes, void *stream)
+{
+    return attn_decode_impl(false, s, q, k_cache, v_cache, T_valid, scale, idx, K, meta, n_first, n_local, out,
+                            lse_out, idx_out, ws, ws_bytes, stream);
+}
+
+int32_t sparse_attn_decode_group(const rs_shape *s, const void *q, const void *k_cache, const void *v_cache,
+                                 int64_t T_valid, float scale, const int32_t *idx, int32_t K, const void *meta,
+                                 int32_t n_first, int32_t n_local, void *out, float *lse_out, int32_t *idx_out,
+                                 void *ws, size_t ws_bytes, void *stream)
+{
+    return attn_decode_impl(true, s, q, k_cache, v_cache, T_valid, scale, idx, K, meta, n_first, n_local, out,
+                            lse_out, idx_out, ws, ws_bytes, stream);
 }
 
 size_t moba_select_prefill_workspace_bytes(const rs_shape *s, int64_t T, int32_t block)

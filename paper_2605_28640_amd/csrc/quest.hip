@@ -77,9 +77,12 @@ void page_meta_dispatch(int dtype, int D, const void *k_cache, void *meta, int B
 constexpr int kSelThreads = 256;
 
 // ------------------------------------------------------------------------------------
-// page scores; the last workgroup of a (batch, query head) to arrive runs the selection
+// page scores; the last workgroup of a unit to arrive runs the selection.  GQ = 1: a unit
+// is a (batch, query head).  GQ = Hq / Hkv > 1 (group-shared selection, an option for
+// grouped-query attention that is not in the paper): a unit is a (batch, KV head), the
+// page score is the sum of the bounds of its GQ query heads and the list is theirs in common.
 // ------------------------------------------------------------------------------------
-template <typename ST, int D>
+template <typename ST, int D, int GQ>
 __global__ __launch_bounds__(kSelThreads) void quest_score_select_kernel(
     const ST *__restrict__ q, const ST *__restrict__ meta, uint64_t *scores, float *scores_out, int32_t *idx_out,
     int Hq, int Hkv, long Np_cap, int Np, int K, int n_first, int n_local, int splits, uint32_t *unit_ctr,
@@ -97,14 +100,16 @@ __global__ __launch_bounds__(kSelThreads) void quest_score_select_kernel(
     const int lane = tid & 63, wave = tid >> 6;
     const int rg = lane / LPR;
     const int c0 = (lane % LPR) * 8;
-    const int unit = blockIdx.y;  // b * Hq + h
-    const int b = unit / Hq, h = unit % Hq;
+    const int unit = blockIdx.y;  // b * Hq + h (GQ = 1) or b * Hkv + kvh
+    const int u0 = unit * GQ;     // first (batch, query head) of the unit
+    const int b = u0 / Hq, h = u0 % Hq;
     const int kvh = h / (Hq / Hkv);
     const ST *mbase = meta + ((long)(b * Hkv + kvh) * Np_cap) * 2 * D;
     uint64_t *srow = scores + (long)unit * Np;
 
-    float qv[8];
-    R::load(q + (long)unit * D + c0, qv);
+    float qv[GQ][8];
+#pragma unroll
+    for (int g = 0; g < GQ; ++g) R::load(q + (long)(u0 + g) * D + c0, qv[g]);
 
     // this workgroup's pages: a contiguous slice, walked UNR * RPW pages per wave step.
     // The LPR lanes of a row group share their page numbers, so the group-local
@@ -134,7 +139,9 @@ __global__ __launch_bounds__(kSelThreads) void quest_score_select_kernel(
             R::unpack(mx[u], hi);
             float s = 0.f;
 #pragma unroll
-            for (int c = 0; c < 8; ++c) s += fmaxf(qv[c] * lo[c], qv[c] * hi[c]);
+            for (int g = 0; g < GQ; ++g)
+#pragma unroll
+                for (int c = 0; c < 8; ++c) s += fmaxf(qv[g][c] * lo[c], qv[g][c] * hi[c]);
             s = group_sum<LPR>(s);
             if (p < pe && (lane % LPR) == 0) publish_f32(&srow[p], s, tag);
         }
@@ -154,25 +161,35 @@ __global__ __launch_bounds__(kSelThreads) void quest_score_select_kernel(
     select_topk_lds<kSelThreads>(s_keys, Np, K, sh, [dst](int pos, int p) { dst[pos] = p; });
 }
 
-int score_select_dispatch(int dtype, int D, const void *q, const void *meta, uint64_t *scores, float *scores_out,
-                          int32_t *idx_out, int B, int Hq, int Hkv, long Np_cap, int Np, int K, int n_first,
-                          int n_local, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit,
-                          hipStream_t stream)
+// GQ: query heads per unit: 1, or Hq / Hkv (2, 4 or 8) for group-shared selection
+int score_select_dispatch(int dtype, int D, int GQ, const void *q, const void *meta, uint64_t *scores,
+                          float *scores_out, int32_t *idx_out, int B, int Hq, int Hkv, long Np_cap, int Np, int K,
+                          int n_first, int n_local, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag,
+                          int spin_limit, hipStream_t stream)
 {
-    const dim3 grid((unsigned)splits, (unsigned)(B * Hq));
+    const dim3 grid((unsigned)splits, (unsigned)(B * Hq / GQ));
     if (Np > 15360) return RS_UNSUPPORTED;  // keys must fit 60 KiB of LDS
+    if (GQ != 1 && GQ != 2 && GQ != 4 && GQ != 8) return RS_UNSUPPORTED;
     const size_t lds = (size_t)Np * 4;
-#define RS_LAUNCH(ST, DD)                                                                                          \
-    quest_score_select_kernel<ST, DD><<<grid, kSelThreads, lds, stream>>>(                                        \
+#define RS_LAUNCH(ST, DD, GG)                                                                                      \
+    quest_score_select_kernel<ST, DD, GG><<<grid, kSelThreads, lds, stream>>>(                                    \
         (const ST *)q, (const ST *)meta, scores, scores_out, idx_out, Hq, Hkv, Np_cap, Np, K, n_first, n_local, \
         splits, unit_ctr, err, tag, spin_limit)
+#define RS_LAUNCH_G(ST, DD)                     \
+    do {                                        \
+        if (GQ == 8) RS_LAUNCH(ST, DD, 8);      \
+        else if (GQ == 4) RS_LAUNCH(ST, DD, 4); \
+        else if (GQ == 2) RS_LAUNCH(ST, DD, 2); \
+        else RS_LAUNCH(ST, DD, 1);              \
+    } while (0)
     if (dtype == RS_BF16) {
-        if (D == 128) RS_LAUNCH(bf16, 128);
-        else RS_LAUNCH(bf16, 64);
+        if (D == 128) RS_LAUNCH_G(bf16, 128);
+        else RS_LAUNCH_G(bf16, 64);
     } else {
-        if (D == 128) RS_LAUNCH(float, 128);
-        else RS_LAUNCH(float, 64);
+        if (D == 128) RS_LAUNCH_G(float, 128);
+        else RS_LAUNCH_G(float, 64);
     }
+#undef RS_LAUNCH_G
 #undef RS_LAUNCH
     return RS_OK;
 }
@@ -188,7 +205,8 @@ template <typename ST, int D>
 __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
     const ST *__restrict__ q, const ST *__restrict__ k_cache, const ST *__restrict__ v_cache, const int32_t *idx,
     ST *__restrict__ out, float *__restrict__ lse_out, uint64_t *partial, int Hq, int Hkv, long Tcap, int P,
-    long T_valid, int K, float scale, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit)
+    long T_valid, int K, float scale, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit,
+    int idx_per_kv)
 {
     constexpr int LPR = D / 8;
     constexpr int RPW = 64 / LPR;  // rows per load instruction
@@ -209,6 +227,8 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
     const int kvh = h / (Hq / Hkv);
     const ST *kb = k_cache + (long)(b * Hkv + kvh) * Tcap * D;
     const ST *vb = v_cache + (long)(b * Hkv + kvh) * Tcap * D;
+    // a page list belongs to the query head, or (group-shared selection) to its KV head
+    const int32_t *idx_row = idx ? idx + (long)(idx_per_kv ? b * Hkv + kvh : unit) * K : nullptr;
 
     float qv[8];
     R::load(q + (long)unit * D + c0, qv);
@@ -235,7 +255,7 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
             row0[u] = T_valid;  // nothing to do
             if (tt < te) {
                 if (idx) {
-                    const int page = idx[(long)unit * K + tt / tiles_per_page];
+                    const int page = idx_row[tt / tiles_per_page];
                     if (page >= 0) row0[u] = (long)page * P + (tt % tiles_per_page) * TR;
                 } else {
                     row0[u] = tt * TR;
@@ -363,13 +383,14 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
 void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache, const void *v_cache,
                             const int32_t *idx, void *out, float *lse_out, uint64_t *partial, int B, int Hq,
                             int Hkv, long Tcap, int P, long T_valid, int K, float scale, int splits,
-                            uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit, hipStream_t stream)
+                            uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit, int idx_per_kv,
+                            hipStream_t stream)
 {
     const dim3 grid((unsigned)splits, (unsigned)(B * Hq));
 #define RS_LAUNCH(ST, DD)                                                                                   \
     decode_attend_kernel<ST, DD><<<grid, kAttThreads, 0, stream>>>(                                         \
         (const ST *)q, (const ST *)k_cache, (const ST *)v_cache, idx, (ST *)out, lse_out, partial, Hq, Hkv, \
-        Tcap, P, T_valid, K, scale, splits, unit_ctr, err, tag, spin_limit)
+        Tcap, P, T_valid, K, scale, splits, unit_ctr, err, tag, spin_limit, idx_per_kv)
     if (dtype == RS_BF16) {
         if (D == 128) RS_LAUNCH(bf16, 128);
         else RS_LAUNCH(bf16, 64);

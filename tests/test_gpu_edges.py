@@ -39,7 +39,7 @@ DECODE = [
 
 
 @pytest.mark.parametrize("case", range(len(DECODE)))
-def test_decode_edges(rs, case):
+def test_decode_edges(rs, monkeypatch, case):
     w, T, Tcap, P, K, n_first, n_local = DECODE[case]
     say("decode edge", case, w.name, T, Tcap, P, K, n_first, n_local)
     w, kc, vc = _cache(w, T, Tcap)
@@ -60,6 +60,13 @@ def test_decode_edges(rs, case):
     lse = torch.zeros(w.B, w.Hq, device="cuda")
     rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out, lse, idx, ws)
     gidx = to_np(idx)
+    for two_launch in ("0", "1"):  # the one persistent launch and the two-launch form agree
+        monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", two_launch)
+        out_m, idx_m = torch.zeros_like(out), torch.full_like(idx, -7)
+        rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out_m, None, idx_m, ws)
+        np.testing.assert_array_equal(to_np(idx_m), gidx)
+        assert attn_close(to_np(out_m), to_np(out).astype(np.float64), tol)[0]
+    monkeypatch.delenv("RATSPARSE_FUSED_TWO_LAUNCH")
     for b in range(w.B):
         for h in range(w.Hq):
             row = gidx[b, h]

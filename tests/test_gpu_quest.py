@@ -82,7 +82,7 @@ CASES += _random_cases(20260528, 12)
 
 
 @pytest.mark.parametrize("case", range(len(CASES)))
-def test_meta_select_attend(rs, case):
+def test_meta_select_attend(rs, monkeypatch, case):
     w, T, Tcap, P, K, n_first, n_local = CASES[case]
     say("quest case", case, w.name, T, Tcap, P, K, n_first, n_local)
     w, kc, vc = _cache_from_oracle(w, T, Tcap)
@@ -126,16 +126,20 @@ def test_meta_select_attend(rs, case):
     assert ok, worst
     np.testing.assert_allclose(to_np(lse), olse, rtol=1e-4, atol=1e-4)
 
-    # fused select-then-attend, emitting its selection
-    out2 = torch.zeros_like(out)
-    idx2 = torch.full_like(idx, -7)
-    rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out2, None, idx2, ws)
-    np.testing.assert_array_equal(to_np(idx2), gidx)
+    # select-then-attend in one call, emitting its selection: as one persistent launch and as
+    # two launches (the library picks by shape; the knob forces either)
     oout2, _ = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, gidx)
-    assert attn_close(to_np(out2), oout2, 2e-2 if w.dtype == "bf16" else 1e-4)[0]
-    out3 = torch.zeros_like(out)
-    rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out3, None, None, ws)
-    assert torch.equal(out3, out2)  # same result when the selection is not emitted
+    for two_launch in ("0", "1"):
+        monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", two_launch)
+        out2 = torch.zeros_like(out)
+        idx2 = torch.full_like(idx, -7)
+        rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out2, None, idx2, ws)
+        np.testing.assert_array_equal(to_np(idx2), gidx)
+        assert attn_close(to_np(out2), oout2, 2e-2 if w.dtype == "bf16" else 1e-4)[0]
+        out3 = torch.zeros_like(out)
+        rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out3, None, None, ws)
+        assert torch.equal(out3, out2)  # same result when the selection is not emitted
+    monkeypatch.delenv("RATSPARSE_FUSED_TWO_LAUNCH")
 
     # dense path, and full budget = dense
     outd = torch.zeros_like(out)
@@ -267,5 +271,69 @@ def test_random_selector_five_seeds(rs):
         ok, worst = attn_close(to_np(out), want)
         assert ok, (seed, worst)
         np.testing.assert_allclose(to_np(lse), wlse, rtol=1e-4, atol=1e-4)
+    torch.cuda.synchronize()
+    ws.async_status()
+
+
+GROUP_CASES = [
+    # workload, T_valid, Tcap, P, K, n_first, n_local
+    (synth.C2.scaled(Hq=8, Hkv=2), 4096 + 5, 4096 + 64, 16, 32, 1, 1),   # G = 4, bf16
+    (synth.C1.scaled(Hq=4, Hkv=2), 2041, 2048 + 16, 16, 16, 1, 1),       # G = 2, fp32, D = 64
+    (synth.C2.scaled(B=2, Hq=8, Hkv=1), 3000, 3072, 64, 6, 0, 2),        # G = 8, 64-token pages
+    (synth.C2.scaled(Hq=6, Hkv=2), 1000, 1024, 16, 8, 1, 1),             # G = 3: not offered
+]
+
+
+@pytest.mark.parametrize("case", range(len(GROUP_CASES)))
+def test_group_shared_selection(rs, case):
+    """The option for grouped-query attention: one page list per KV head from the summed
+    scores of its query heads, attended by all of them."""
+    w, T, Tcap, P, K, n_first, n_local = GROUP_CASES[case]
+    say("group case", case, w.name, w.Hq, w.Hkv, T, P, K)
+    w, kc, vc = _cache_from_oracle(w, T, Tcap)
+    _, _, _, q = synth.decode_step(w, 0)
+    Np = -(-T // P)
+    G = w.Hq // w.Hkv
+    scale = 1.0 / np.sqrt(w.D)
+    dt = tdtype(w.dtype)
+    tol = 2e-2 if w.dtype == "bf16" else 1e-4
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tcap, P, dt)
+    tkc, tvc, tq = to_dev(kc, w.dtype), to_dev(vc, w.dtype), to_dev(q, w.dtype)
+    meta = torch.zeros(w.B, w.Hkv, Tcap // P, 2, w.D, dtype=dt, device="cuda")
+    ws = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, T, Np))
+    rs.quest_page_meta(s, tkc, meta, 0, T)
+    ometa = oracle.quest_page_meta(kc, P, T)
+    idx = torch.full((w.B, w.Hkv, K), -7, dtype=torch.int32, device="cuda")
+    scores = torch.zeros(w.B, w.Hkv, Np, device="cuda")
+    if G not in (2, 4, 8):
+        with pytest.raises(rs.RatsparseError, match="status 2"):
+            rs.quest_select_decode_group(s, tq, meta, T, K, n_first, n_local, idx, scores, ws)
+        return
+    rs.quest_select_decode_group(s, tq, meta, T, K, n_first, n_local, idx, scores, ws)
+    osc = oracle.quest_scores_group(q, ometa, Np)
+    np.testing.assert_allclose(to_np(scores), osc, rtol=4e-6, atol=2e-5)
+    gidx = to_np(idx)
+    forced = _forced(Np, n_first, n_local)
+    for b in range(w.B):
+        for kvh in range(w.Hkv):
+            ok, why = topk_set_ok(osc[b, kvh], forced, K, gidx[b, kvh])
+            assert ok, (b, kvh, why)
+    # every query head of the group attends the group's list
+    per_head = np.repeat(gidx, G, axis=1)
+    want, wlse = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, per_head)
+    out = torch.zeros(w.B, w.Hq, w.D, dtype=dt, device="cuda")
+    lse = torch.zeros(w.B, w.Hq, device="cuda")
+    rs.sparse_attn_decode_group(s, tq, tkc, tvc, T, scale, idx, K, None, 0, 0, out, lse, None, ws)
+    ok, worst = attn_close(to_np(out), want, tol)
+    assert ok, worst
+    np.testing.assert_allclose(to_np(lse), wlse, rtol=1e-4, atol=1e-4)
+    # select, then attend, in one call; same list, same result
+    out2 = torch.zeros_like(out)
+    idx2 = torch.full_like(idx, -7)
+    rs.sparse_attn_decode_group(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out2, None, idx2, ws)
+    np.testing.assert_array_equal(to_np(idx2), gidx)
+    assert torch.equal(out2, out)
+    with pytest.raises(rs.RatsparseError, match="status 1"):  # no dense mode
+        rs.sparse_attn_decode_group(s, tq, tkc, tvc, T, scale, None, 0, None, 0, 0, out2, None, None, ws)
     torch.cuda.synchronize()
     ws.async_status()

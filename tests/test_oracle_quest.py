@@ -126,3 +126,30 @@ def test_budget_arithmetic_of_the_paper():
     s = np.random.default_rng(11).standard_normal((1, 1, 64))
     idx = oracle.quest_select(s, 4, 1, 1)[0, 0]
     assert len(idx) == 4 and idx[0] == 0 and idx[-1] == 63
+
+
+def test_group_score_bounds_the_groups_summed_logit_and_reduces_to_per_head():
+    """Group-shared selection (an option, not in the paper): the group's page score is the sum
+    of its heads' bounds, so it bounds the largest summed logit of any token of the page; with
+    one query head per KV head it is the per-head score; with a page of one key it is the
+    summed logit itself."""
+    B, Hq, Hkv, D, P, T = 2, 8, 2, 16, 8, 160
+    G = Hq // Hkv
+    kc = _cache(B, Hkv, T, D, seed=13)
+    q = np.random.default_rng(14).standard_normal((B, Hq, D)).astype(np.float32)
+    meta = oracle.quest_page_meta(kc, P, T)
+    sg = oracle.quest_scores_group(q, meta, T // P)
+    assert sg.shape == (B, Hkv, T // P)
+    for b in range(B):
+        for kvh in range(Hkv):
+            qsum = q[b, kvh * G:(kvh + 1) * G].astype(np.float64).sum(axis=0)
+            logits = kc[b, kvh].astype(np.float64) @ qsum  # sum over the group of q_h . k
+            assert np.all(sg[b, kvh] >= logits.reshape(T // P, P).max(axis=1) - 1e-12)
+    q1 = q[:, :Hkv]
+    np.testing.assert_array_equal(oracle.quest_scores_group(q1, meta, T // P), oracle.quest_scores(q1, meta, T // P))
+    meta1 = oracle.quest_page_meta(kc, 1, T)
+    s1 = oracle.quest_scores_group(q, meta1, T)
+    for b in range(B):
+        for kvh in range(Hkv):
+            qsum = q[b, kvh * G:(kvh + 1) * G].astype(np.float64).sum(axis=0)
+            np.testing.assert_allclose(s1[b, kvh], kc[b, kvh].astype(np.float64) @ qsum, rtol=1e-12, atol=1e-12)
