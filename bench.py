@@ -176,7 +176,10 @@ def main():
     roofline = {"bound": "hbm", "kernel": "decode_fused_kernel (sparse_attn_decode, fused select+attend, one launch per step)",
                 "achieved": round(achieved / 1e9, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK, 4), "traffic": traffic,
-                "algorithmic_bytes_per_step": int(mean_bytes), "launches_timed": len(fused_ms),
+                "algorithmic_bytes_per_step": int(mean_bytes),
+                "mean_pages_per_sequence": round(sum((T + args.warmup + j + 1 + P - 1) // P
+                                                     for j in range(0, args.steps, EV_EVERY)) / len(bytes_per_step), 1),
+                "launches_timed": len(fused_ms),
                 "mean_ms": round(mean_fused_ms, 5),
                 "min_ms": round(min(fused_ms), 5), "median_ms": round(sorted(fused_ms)[len(fused_ms) // 2], 5)}
     log("decode: %.4f ms/step wall, fused pair %.4f ms mean -> %.0f GB/s (%.1f%% of HBM peak)" %
