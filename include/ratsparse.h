@@ -171,6 +171,31 @@ int32_t sparse_attn_decode_group(const rs_shape *s, const void *q, const void *k
                                  int32_t n_first, int32_t n_local, void *out, float *lse_out,
                                  int32_t *idx_out, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- One decode step whose length lives on the device (replayable) --------------------
+ * The decode loop of Sec. 3 with Quest (App. A.1): append token T of the gated cache
+ * (Eq. 1 step, as rat_scan with T_new = 1 and meta), then select K pages (Eq. 3) and
+ * attend them (Eq. 4) over the T + 1 stored tokens, as sparse_attn_decode's fused mode.
+ * T is not an argument: it is a 64-bit word of the workspace's control block, read by the
+ * kernels and advanced by one when the step has finished, together with the step's tag.
+ * No argument changes from step to step, so a stream capture of one call can be replayed
+ * for every following token (the caller refreshes the contents of k, v, g, q in place).
+ *   rat_decode_state_set   enqueue: tokens already in the cache := T (after a prefill)
+ *   rat_decode_state_get   waits for `stream`, then reads the token count into *T (host)
+ *   k, v [B, Hkv, 1, D] dtype; g [B, Hkv, 1, D] float32; q [B, Hq, D]; the rest as in
+ *   rat_scan and sparse_attn_decode.  T_max: the largest T + 1 the workspace is sized for
+ *   (<= Tcap).  Always the one-launch form, per query head.
+ * A step that would pass T_max, or that finds fewer than K pages, changes nothing (neither
+ * caches nor count) except that it sets the asynchronous error word
+ * (ratsparse_async_status -> RS_ASYNC_TIMEOUT).  n_first + n_local <= K is required. */
+size_t rat_decode_step_workspace_bytes(const rs_shape *s, int64_t T_max, int32_t K);
+int32_t rat_decode_state_set(void *ws, size_t ws_bytes, int64_t T, void *stream);
+int32_t rat_decode_state_get(void *ws, int64_t *T, void *stream);
+int32_t rat_decode_step(const rs_shape *s, const void *k, const void *v, const float *g,
+                        float *state_k, float *state_v, void *k_cache, void *v_cache,
+                        void *meta, const void *q, float scale, int32_t K, int32_t n_first,
+                        int32_t n_local, int64_t T_max, void *out, float *lse_out,
+                        int32_t *idx_out, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- MoBA routing at prefill: Sec. 2.2, Eq. 3; App. A.1, MoBA paragraph ----------------
  * Block representative = mean of the stored keys of a block of `block` tokens (the
  * tail block over its valid tokens).  Each query token t, in block b(t) = t / block,

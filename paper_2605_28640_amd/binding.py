@@ -48,6 +48,11 @@ SIGNATURES = {
     "sparse_attn_decode_workspace_bytes": (_sz, [_shp, _i64, _i32]),
     "sparse_attn_decode": (_i32, [_shp, _vp, _vp, _vp, _i64, _f32, _vp, _i32, _vp, _i32, _i32, _vp,
                                   _vp, _vp, _vp, _sz, _vp]),
+    "rat_decode_step_workspace_bytes": (_sz, [_shp, _i64, _i32]),
+    "rat_decode_state_set": (_i32, [_vp, _sz, _i64, _vp]),
+    "rat_decode_state_get": (_i32, [_vp, ctypes.POINTER(ctypes.c_int64), _vp]),
+    "rat_decode_step": (_i32, [_shp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _i32, _i32, _i32, _i64,
+                               _vp, _vp, _vp, _vp, _sz, _vp]),
     "moba_select_prefill_workspace_bytes": (_sz, [_shp, _i64, _i32]),
     "moba_select_prefill": (_i32, [_shp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "sparse_attn_prefill_workspace_bytes": (_sz, [_shp, _i64, _i32, _i32]),
@@ -164,6 +169,27 @@ def sparse_attn_decode_group(s, q, k_cache, v_cache, T_valid, scale, idx, K, met
     _check(load().sparse_attn_decode_group(ctypes.byref(s), _ptr(q), _ptr(k_cache), _ptr(v_cache), T_valid,
                                            scale, _ptr(idx), K, _ptr(meta), n_first, n_local, _ptr(out),
                                            _ptr(lse_out), _ptr(idx_out), ws.ptr, ws.nbytes, _stream()))
+
+
+def rat_decode_step_workspace_bytes(s, T_max, K):
+    return load().rat_decode_step_workspace_bytes(ctypes.byref(s), T_max, K)
+
+
+def rat_decode_state_set(ws, T):
+    _check(load().rat_decode_state_set(ws.ptr, ws.nbytes, T, _stream()))
+
+
+def rat_decode_state_get(ws):
+    T = ctypes.c_int64(0)
+    _check(load().rat_decode_state_get(ws.ptr, ctypes.byref(T), _stream()))
+    return T.value
+
+
+def rat_decode_step(s, k, v, g, state_k, state_v, k_cache, v_cache, meta, q, scale, K, n_first, n_local, T_max,
+                    out, lse_out, idx_out, ws):
+    _check(load().rat_decode_step(ctypes.byref(s), _ptr(k), _ptr(v), _ptr(g), _ptr(state_k), _ptr(state_v),
+                                  _ptr(k_cache), _ptr(v_cache), _ptr(meta), _ptr(q), scale, K, n_first, n_local,
+                                  T_max, _ptr(out), _ptr(lse_out), _ptr(idx_out), ws.ptr, ws.nbytes, _stream()))
 
 
 def sparse_attn_decode_workspace_bytes(s, T_valid, K):

@@ -16,6 +16,9 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
 // quest.hip
 void page_meta_dispatch(int dtype, int D, const void *k_cache, void *meta, int BH, long Tcap, int P,
                         int p_begin, int n_pages, long t_end, hipStream_t stream);
+void step_at_state_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
+                            float *state_v, void *k_cache, void *v_cache, void *meta, int P, int BH, long Tcap,
+                            const uint32_t *pos_state, long T_max, hipStream_t stream);
 int score_select_dispatch(int dtype, int D, int GQ, const void *q, const void *meta, uint64_t *scores,
                           float *scores_out, int32_t *idx_out, int B, int Hq, int Hkv, long Np_cap, int Np, int K,
                           int n_first, int n_local, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag,
@@ -41,6 +44,14 @@ __global__ void fill_zero_kernel(uint32_t *p, long n)
 {
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;
+}
+
+__global__ void decode_state_set_kernel(uint32_t *ctrl, long T, uint32_t tag)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        *reinterpret_cast<long *>(ctrl + kCtrlStateT) = T;
+        ctrl[kCtrlStateTag] = tag;
+    }
 }
 
 static std::atomic<int> g_spin_limit{1 << 22};
@@ -142,6 +153,52 @@ static DecodeLayout decode_layout(const rs_shape *s, long T_valid, int K)
     if (env_int("RATSPARSE_TRACE", 0)) off += (size_t)4096 * 64 * 8;
     L.total = off;
     return L;
+}
+
+// work split and buffers of the one-launch decode (score -> select -> attend) for a sequence of
+// T_valid tokens laid out by L; returns the grid
+static long fused_setup(FusedParams &prm, const rs_shape *s, const DecodeLayout &L, char *w, const void *q,
+                        const void *meta, const void *k_cache, const void *v_cache, void *out, float *lse_out,
+                        int32_t *idx_out, long T_valid, int K, int n_first, int n_local, float scale, int *threads_out)
+{
+    const long units = (long)s->B * s->Hq;
+    uint32_t *ctr_score = (uint32_t *)w + kCtrlUnit0;
+    uint32_t *ctr_att = ctr_score + kMaxUnits;
+    prm.q = q; prm.meta = meta; prm.k_cache = k_cache; prm.v_cache = v_cache;
+    prm.out = out; prm.lse_out = lse_out; prm.idx_out = idx_out;
+    prm.scores = (uint64_t *)(w + L.off_scores);
+    prm.idx_tagged = (uint64_t *)(w + L.off_idx_tagged);
+    prm.partial = (uint64_t *)(w + L.off_partial);
+    prm.ctr_score = ctr_score; prm.ctr_att = ctr_att;
+    prm.ticket = (uint32_t *)w + kCtrlTicket; prm.done = (uint32_t *)w + kCtrlDone;
+    prm.err = (uint32_t *)w + kCtrlAsyncErr;
+    prm.Hq = s->Hq; prm.Hkv = s->Hkv; prm.units = (int)units;
+    prm.Tcap = s->Tcap; prm.Np_cap = s->Tcap / s->P; prm.T_valid = T_valid;
+    prm.P = s->P; prm.Np = L.Np; prm.K = K; prm.n_first = n_first; prm.n_local = n_local;
+    int ss = env_int("RATSPARSE_FUSED_SSCORE", 0), sa = env_int("RATSPARSE_FUSED_SATT", 0);
+    if (ss <= 0) ss = (L.Np + 511) / 512;                      // ~512 pages (256 KiB of bf16 metadata) per item
+    if (sa <= 0) sa = (int)(((long)K * (s->P / 16) + 31) / 32);  // ~32 tiles (256 KiB of bf16 K+V) per item
+    if (ss > L.Np) ss = L.Np;
+    if (sa > kMaxAttSplits) sa = kMaxAttSplits;
+    if (sa > K) sa = K;
+    prm.S_score = ss < 1 ? 1 : ss; prm.S_att = sa < 1 ? 1 : sa;
+    int fine = env_int("RATSPARSE_FUSED_FINE", 2) * prm.S_att;
+    if (fine > kMaxAttSplits) fine = kMaxAttSplits;
+    if (fine > K) fine = K;
+    prm.S_att_fine = fine < prm.S_att ? prm.S_att : fine;
+    prm.units_fine = (int)(units * env_int("RATSPARSE_FUSED_FINE_PCT", 6) / 100);
+    prm.S_max = kMaxAttSplits;
+    prm.reverse = env_int("RATSPARSE_FUSED_PINGPONG", 1) ? (int)(T_valid & 1) : 0;
+    prm.nt_kv = env_int("RATSPARSE_FUSED_NT", 1);  // bit 0: K/V pages, bit 1: page metadata
+    prm.scale = scale; prm.tag = 0; prm.spin_limit = g_spin_limit.load();
+    prm.trace = env_int("RATSPARSE_TRACE", 0) ? (uint64_t *)(w + L.off_trace) : nullptr;
+    prm.state = nullptr; prm.T_max = 0;
+    const long items = units * (prm.S_score + prm.S_att) + (long)prm.units_fine * (prm.S_att_fine - prm.S_att);
+    // two 512-thread workgroups per CU: one streams while the other selects or merges
+    *threads_out = env_int("RATSPARSE_FUSED_THREADS", 512) == 256 ? 256 : 512;
+    long grid = env_int("RATSPARSE_FUSED_GRID", 2 * num_cus());
+    if (grid > items) grid = items;
+    return grid;
 }
 
 }  // namespace rs
@@ -383,40 +440,11 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     if (fused && !group && !two_launch) {
         // one persistent launch: score -> select -> attend, handed over through tagged words
         FusedParams prm;
-        prm.q = q; prm.meta = meta; prm.k_cache = k_cache; prm.v_cache = v_cache;
-        prm.out = out; prm.lse_out = lse_out; prm.idx_out = idx_out;
-        prm.scores = (uint64_t *)(w + L.off_scores);
-        prm.idx_tagged = (uint64_t *)(w + L.off_idx_tagged);
-        prm.partial = (uint64_t *)(w + L.off_partial);
-        prm.ctr_score = ctr_score; prm.ctr_att = ctr_att;
-        prm.ticket = (uint32_t *)w + kCtrlTicket; prm.done = (uint32_t *)w + kCtrlDone;
-        prm.err = (uint32_t *)w + kCtrlAsyncErr;
-        prm.Hq = s->Hq; prm.Hkv = s->Hkv; prm.units = (int)units;
-        prm.Tcap = s->Tcap; prm.Np_cap = s->Tcap / s->P; prm.T_valid = T_valid;
-        prm.P = s->P; prm.Np = L.Np; prm.K = K; prm.n_first = n_first; prm.n_local = n_local;
-        int ss = env_int("RATSPARSE_FUSED_SSCORE", 0), sa = env_int("RATSPARSE_FUSED_SATT", 0);
-        if (ss <= 0) ss = (L.Np + 511) / 512;                      // ~512 pages (256 KiB of bf16 metadata) per item
-        if (sa <= 0) sa = (int)(((long)K * (s->P / 16) + 31) / 32);  // ~32 tiles (256 KiB of bf16 K+V) per item
-        if (ss > L.Np) ss = L.Np;
-        if (sa > kMaxAttSplits) sa = kMaxAttSplits;
-        if (sa > K) sa = K;
-        prm.S_score = ss < 1 ? 1 : ss; prm.S_att = sa < 1 ? 1 : sa;
-        int fine = env_int("RATSPARSE_FUSED_FINE", 2) * prm.S_att;
-        if (fine > kMaxAttSplits) fine = kMaxAttSplits;
-        if (fine > K) fine = K;
-        prm.S_att_fine = fine < prm.S_att ? prm.S_att : fine;
-        prm.units_fine = (int)(units * env_int("RATSPARSE_FUSED_FINE_PCT", 6) / 100);
-        prm.S_max = kMaxAttSplits;
-        prm.reverse = env_int("RATSPARSE_FUSED_PINGPONG", 1) ? (int)(T_valid & 1) : 0;
-        prm.nt_kv = env_int("RATSPARSE_FUSED_NT", 1);  // bit 0: K/V pages, bit 1: page metadata
-        prm.scale = scale; prm.tag = tag; prm.spin_limit = g_spin_limit.load();
-        prm.trace = env_int("RATSPARSE_TRACE", 0) ? (uint64_t *)(w + L.off_trace) : nullptr;
-        long items = units * (prm.S_score + prm.S_att) + (long)prm.units_fine * (prm.S_att_fine - prm.S_att);
-        // two 512-thread workgroups per CU: one streams while the other selects or merges
-        const int threads = env_int("RATSPARSE_FUSED_THREADS", 512) == 256 ? 256 : 512;
-        long grid = env_int("RATSPARSE_FUSED_GRID", 2 * num_cus());
-        if (grid > items) grid = items;
-        st = decode_fused_dispatch(s->dtype, s->D, prm, (int)grid, threads, (hipStream_t)stream);
+        int threads = 512;
+        const long grid = fused_setup(prm, s, L, w, q, meta, k_cache, v_cache, out, lse_out, idx_out, T_valid, K, n_first,
+                                      n_local, scale, &threads);
+        prm.tag = tag;
+        st = decode_fused_dispatch(s->dtype, s->D, prm, L.Np, (int)grid, threads, (hipStream_t)stream);
         if (st != RS_OK) return st;
         return launch_status();
     }
@@ -456,6 +484,64 @@ int32_t sparse_attn_decode_group(const rs_shape *s, const void *q, const void *k
 {
     return attn_decode_impl(true, s, q, k_cache, v_cache, T_valid, scale, idx, K, meta, n_first, n_local, out,
                             lse_out, idx_out, ws, ws_bytes, stream);
+}
+
+size_t rat_decode_step_workspace_bytes(const rs_shape *s, int64_t T_max, int32_t K)
+{
+    if (check_shape(s, true) != RS_OK || T_max <= 0 || T_max > s->Tcap) return 0;
+    return decode_layout(s, T_max, K).total;
+}
+
+int32_t rat_decode_state_set(void *ws, size_t ws_bytes, int64_t T, void *stream)
+{
+    if (!ws || !aligned16(ws) || T < 0) return RS_INVALID_ARG;
+    if (ws_bytes < RS_WS_CTRL_BYTES) return RS_WORKSPACE_TOO_SMALL;
+    decode_state_set_kernel<<<1, 64, 0, (hipStream_t)stream>>>((uint32_t *)ws, (long)T, next_tag());
+    return launch_status();
+}
+
+int32_t rat_decode_state_get(void *ws, int64_t *T, void *stream)
+{
+    if (!ws || !T) return RS_INVALID_ARG;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return RS_LAUNCH_FAILED;
+    long t = 0;
+    if (hipMemcpy(&t, (const uint32_t *)ws + kCtrlStateT, 8, hipMemcpyDeviceToHost) != hipSuccess) return RS_LAUNCH_FAILED;
+    *T = t;
+    return RS_OK;
+}
+
+int32_t rat_decode_step(const rs_shape *s, const void *k, const void *v, const float *g, float *state_k,
+                        float *state_v, void *k_cache, void *v_cache, void *meta, const void *q, float scale,
+                        int32_t K, int32_t n_first, int32_t n_local, int64_t T_max, void *out, float *lse_out,
+                        int32_t *idx_out, void *ws, size_t ws_bytes, void *stream)
+{
+    int st = check_shape(s, true);
+    if (st != RS_OK) return st;
+    if (!k || !v || !g || !state_k || !state_v || !k_cache || !v_cache || !meta || !q || !out) return RS_INVALID_ARG;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(state_k) || !aligned16(state_v) ||
+        !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(meta) || !aligned16(q) || !aligned16(out) ||
+        (idx_out && !aligned16(idx_out)))
+        return RS_INVALID_ARG;
+    if (T_max <= 0 || T_max > s->Tcap || K < 1 || n_first < 0 || n_local < 0) return RS_INVALID_ARG;
+    if ((long)n_first + n_local > K) return RS_INVALID_ARG;  // holds at every length, whatever the page count
+    const DecodeLayout L = decode_layout(s, T_max, K);
+    if (K > L.Np) return RS_INVALID_ARG;
+    if (L.Np > 15360) return RS_UNSUPPORTED;  // the selection's keys must fit the LDS: before any launch
+    if (!ws || !aligned16(ws) || ws_bytes < L.total) return RS_WORKSPACE_TOO_SMALL;
+    char *w = (char *)ws;
+    step_at_state_dispatch(s->dtype, s->D, k, v, g, state_k, state_v, k_cache, v_cache, meta, s->P, s->B * s->Hkv,
+                           s->Tcap, (const uint32_t *)w, T_max, (hipStream_t)stream);
+    if (launch_status() != RS_OK) return RS_LAUNCH_FAILED;
+    FusedParams prm;
+    int threads = 512;
+    const long grid = fused_setup(prm, s, L, w, q, meta, k_cache, v_cache, out, lse_out, idx_out, T_max, K, n_first,
+                                  n_local, scale, &threads);
+    prm.reverse = env_int("RATSPARSE_FUSED_PINGPONG", 1);  // the kernel takes the parity of the length it reads
+    prm.state = (uint32_t *)w;
+    prm.T_max = T_max;
+    st = decode_fused_dispatch(s->dtype, s->D, prm, L.Np, (int)grid, threads, (hipStream_t)stream);
+    if (st != RS_OK) return st;
+    return launch_status();
 }
 
 size_t moba_select_prefill_workspace_bytes(const rs_shape *s, int64_t T, int32_t block)

@@ -15,6 +15,8 @@ constexpr int kWave = 64;
 constexpr int kCtrlAsyncErr = 0;  // set to 1 by a kernel whose bounded wait expired
 constexpr int kCtrlTicket = 1;    // dynamic chunk ticket of the scan
 constexpr int kCtrlDone = 2;      // finished-workgroup counter of the scan
+constexpr int kCtrlStateT = 4;     // replayable decode step: tokens in the cache (64 bits: words 4 and 5)
+constexpr int kCtrlStateTag = 6;   // replayable decode step: the tag of the next step
 constexpr int kCtrlUnit0 = 64;    // per-(batch, head) arrival counters start here
 constexpr int kCtrlWords = RS_WS_CTRL_BYTES / 4;
 constexpr int kMaxUnits = (kCtrlWords - kCtrlUnit0) / 2;

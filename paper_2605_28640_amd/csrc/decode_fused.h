@@ -27,8 +27,13 @@ struct FusedParams {
     uint32_t tag;
     int spin_limit;
     uint64_t *trace;  // optional timeline for tuning: [workgroup][64] of (time << 20 | item << 4 | phase)
+    // replayable step: T_valid, Np and tag are read from the workspace's state words (T_valid =
+    // tokens in the cache + 1: the step's append has run) and the last workgroup out advances them
+    uint32_t *state;  // control words of the workspace, or NULL: T_valid, Np, tag above are used
+    long T_max;       // replayable step: largest T_valid the buffers were sized for
 };
 
-int decode_fused_dispatch(int dtype, int D, const FusedParams &prm, int grid, int threads, hipStream_t stream);
+// np_lds: page keys the dynamic LDS must hold (Np, or its largest value over the replays)
+int decode_fused_dispatch(int dtype, int D, const FusedParams &prm, int np_lds, int grid, int threads, hipStream_t stream);
 
 }  // namespace rs

@@ -22,7 +22,7 @@
 
 namespace rs {
 
-template <typename ST, int D, int kFusedThreads>
+template <typename ST, int D, int kFusedThreads, bool STATE>
 __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void decode_fused_kernel(const FusedParams P_)
 {
     constexpr int kFusedWaves = kFusedThreads / 64;
@@ -30,6 +30,23 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
     constexpr int RPW = 64 / LPR;
     using R = Row8<ST>;
     const FusedParams &a = P_;
+    // sequence length, page count and tag: kernel arguments, or (replayable step) the workspace's state words
+    long T_valid_ = a.T_valid;
+    int Np_ = a.Np;
+    uint32_t tag_ = a.tag;
+    long score_stride = a.Np;
+    int reverse_ = a.reverse;
+    if constexpr (STATE) {
+        T_valid_ = *reinterpret_cast<const long *>(a.state + kCtrlStateT) + 1;
+        tag_ = a.state[kCtrlStateTag];
+        Np_ = (int)((T_valid_ + a.P - 1) / a.P);
+        score_stride = (a.T_max + a.P - 1) / a.P;
+        reverse_ = a.reverse ? (int)(T_valid_ & 1) : 0;
+        if (T_valid_ > a.T_max || a.K > Np_) {  // outside what the buffers were sized for: report, do nothing
+            if (blockIdx.x == 0 && threadIdx.x == 0) atomicExch(a.err, 1u);
+            return;
+        }
+    }
 
     __shared__ SelectShared<kFusedThreads> sh;
     __shared__ float s_m[kFusedWaves], s_l[kFusedWaves];
@@ -75,18 +92,18 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
             // ------------------------------ score item ------------------------------
             int unit = item / a.S_score;
             const int slice = item % a.S_score;
-            if (a.reverse) unit = a.units - 1 - unit;
+            if (reverse_) unit = a.units - 1 - unit;
             const int b = unit / a.Hq, h = unit % a.Hq, kvh = h / G;
             const ST *mbase = (const ST *)a.meta + ((long)(b * a.Hkv + kvh) * a.Np_cap) * 2 * D;
-            uint64_t *srow = a.scores + (long)unit * a.Np;
+            uint64_t *srow = a.scores + (long)unit * score_stride;
             float qv[8];
             R::load((const ST *)a.q + (long)unit * D + c0, qv);
 
             constexpr int UNR = 4;
             constexpr int PPI = UNR * RPW * kFusedWaves;  // pages per workgroup step
-            const int per = (a.Np + a.S_score - 1) / a.S_score;
+            const int per = (Np_ + a.S_score - 1) / a.S_score;
             const int pb = slice * per;
-            const int pe = (pb + per < a.Np) ? pb + per : a.Np;
+            const int pe = (pb + per < Np_) ? pb + per : Np_;
             const bool sel_here = (slice == a.S_score - 1);
             for (int base = pb + wave * (UNR * RPW) + rg; base < pe; base += PPI) {
                 if (!sel_here && base + PPI >= pe) fetch_next();
@@ -117,7 +134,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
 #pragma unroll
                     for (int c = 0; c < 8; ++c) s += fmaxf(qv[c] * lo[c], qv[c] * hi[c]);
                     s = group_sum<LPR>(s);
-                    if (p < pe && cl == 0) publish_f32(&srow[p], s, a.tag);
+                    if (p < pe && cl == 0) publish_f32(&srow[p], s, tag_);
                 }
             }
             mark(item, 1);
@@ -125,13 +142,13 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
             // running or done, so it can wait for their scores and run the selection
             if (sel_here) {
                 __builtin_amdgcn_s_setprio(3);  // the unit's attention waits on this: go first on the CU
-                gather_page_keys<kFusedThreads>(srow, a.Np, a.n_first, a.n_local, a.tag, a.spin_limit, a.err, nullptr,
+                gather_page_keys<kFusedThreads>(srow, Np_, a.n_first, a.n_local, tag_, a.spin_limit, a.err, nullptr,
                                                 s_keys);
                 mark(item, 7);
                 uint64_t *dst = a.idx_tagged + (long)unit * a.K;
                 int32_t *plain = a.idx_out ? a.idx_out + (long)unit * a.K : nullptr;
-                const uint32_t tag = a.tag;
-                select_topk_lds<kFusedThreads>(s_keys, a.Np, a.K, sh, [dst, plain, tag](int pos, int p) {
+                const uint32_t tag = tag_;
+                select_topk_lds<kFusedThreads>(s_keys, Np_, a.K, sh, [dst, plain, tag](int pos, int p) {
                     store_u64_agent(&dst[pos], ((uint64_t)tag << 32) | (uint32_t)p);
                     if (plain) plain[pos] = p;
                 }, [&](int ph) { mark(item, ph); });
@@ -151,7 +168,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                 unit = u_coarse + (it - n_att_coarse) / S_att;
                 slice = (it - n_att_coarse) % S_att;
             }
-            if (a.reverse) unit = a.units - 1 - unit;
+            if (reverse_) unit = a.units - 1 - unit;
             const int b = unit / a.Hq, h = unit % a.Hq, kvh = h / G;
             const ST *kb = (const ST *)a.k_cache + (long)(b * a.Hkv + kvh) * a.Tcap * D;
             const ST *vb = (const ST *)a.v_cache + (long)(b * a.Hkv + kvh) * a.Tcap * D;
@@ -187,13 +204,13 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                     wsel[u] = (t + u < te) ? load_u64_agent(&sel[(t + u) / tiles_per_page]) : 0ull;
 #pragma unroll
                 for (int u = 0; u < TPI; ++u) {
-                    row0[u] = a.T_valid;
+                    row0[u] = T_valid_;
                     if (t + u < te) {
                         uint32_t page = (uint32_t)wsel[u];
-                        if ((uint32_t)(wsel[u] >> 32) != a.tag) {  // the selection is still being written
+                        if ((uint32_t)(wsel[u] >> 32) != tag_) {  // the selection is still being written
                             int spins = 0;
                             uint64_t w2 = wsel[u];
-                            while ((uint32_t)(w2 >> 32) != a.tag) {
+                            while ((uint32_t)(w2 >> 32) != tag_) {
                                 if (++spins > a.spin_limit) {
                                     atomicExch(a.err, 1u);
                                     break;
@@ -202,9 +219,9 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                                 w2 = load_u64_agent(&sel[(t + u) / tiles_per_page]);
                             }
                             page = (uint32_t)w2;
-                            if ((uint32_t)(w2 >> 32) != a.tag) page = 0xffffffffu;  // gave up: skip
+                            if ((uint32_t)(w2 >> 32) != tag_) page = 0xffffffffu;  // gave up: skip
                         }
-                        if (page < (uint32_t)a.Np) row0[u] = (long)page * a.P + ((t + u) % tiles_per_page) * TR;
+                        if (page < (uint32_t)Np_) row0[u] = (long)page * a.P + ((t + u) % tiles_per_page) * TR;
                     }
                 }
 #pragma unroll
@@ -212,7 +229,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
 #pragma unroll
                     for (int i = 0; i < RPL; ++i) {
                         const long row = row0[u] + i * RPW + rg;
-                        if (row < a.T_valid) {
+                        if (row < T_valid_) {
                             if (a.nt_kv & 1) {
                                 kr[u][i] = R::load_raw_nt(kb + row * D + c0);
                                 vr[u][i] = R::load_raw_nt(vb + row * D + c0);
@@ -239,7 +256,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                         for (int c = 0; c < 8; ++c) d = fmaf(qv[c], x[c], d);
                         d = group_sum<LPR>(d);
                         const long row = row0[u] + i * RPW + rg;
-                        s[i] = (row < a.T_valid) ? d : -INFINITY;
+                        s[i] = (row < T_valid_) ? d : -INFINITY;
                         mt = fmaxf(mt, s[i]);
                     }
                     if (mt != -INFINITY) {
@@ -301,14 +318,14 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
             if (!finish) {
                 uint64_t *part = a.partial + ((long)unit * a.S_max + slice) * (D + 2);
                 if (tid < D) {
-                    publish_f32(&part[2 + tid], O, a.tag);
+                    publish_f32(&part[2 + tid], O, tag_);
                     if (tid == 0) {
-                        publish_f32(&part[0], M, a.tag);
-                        publish_f32(&part[1], L, a.tag);
+                        publish_f32(&part[0], M, tag_);
+                        publish_f32(&part[1], L, tag_);
                     }
                 }
             } else if (S_att > 1 && tid < D) {
-                merge_partials(a.partial + (long)unit * a.S_max * (D + 2), S_att - 1, D + 2, tid, a.tag, a.spin_limit,
+                merge_partials(a.partial + (long)unit * a.S_max * (D + 2), S_att - 1, D + 2, tid, tag_, a.spin_limit,
                                a.err, M, L, O);
             }
             mark(item, 6);
@@ -327,26 +344,32 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
         if (atomicAdd(a.done, 1u) == gridDim.x - 1u) {  // last workgroup out resets the counters
             atomicExch(a.ticket, 0u);
             atomicExch(a.done, 0u);
+            if constexpr (STATE) {  // every workgroup has read the state: the next step's length and tag
+                *reinterpret_cast<long *>(a.state + kCtrlStateT) = T_valid_;
+                const uint32_t nt = tag_ + 0x85EBCA6Bu;
+                a.state[kCtrlStateTag] = nt ? nt : 0x5bd1e995u;
+            }
         }
     }
 }
 
 template <typename ST, int D, int NT>
-static int launch_fused(const FusedParams &prm, int grid, hipStream_t stream)
+static int launch_fused(const FusedParams &prm, int np_lds, int grid, hipStream_t stream)
 {
-    if (prm.Np > 15360) return RS_UNSUPPORTED;  // keys must fit 60 KiB of LDS
-    decode_fused_kernel<ST, D, NT><<<grid, NT, (size_t)prm.Np * 4, stream>>>(prm);
+    if (np_lds > 15360) return RS_UNSUPPORTED;  // keys must fit 60 KiB of LDS
+    if (prm.state) decode_fused_kernel<ST, D, NT, true><<<grid, NT, (size_t)np_lds * 4, stream>>>(prm);
+    else decode_fused_kernel<ST, D, NT, false><<<grid, NT, (size_t)np_lds * 4, stream>>>(prm);
     return RS_OK;
 }
 
-int decode_fused_dispatch(int dtype, int D, const FusedParams &prm, int grid, int threads, hipStream_t stream)
+int decode_fused_dispatch(int dtype, int D, const FusedParams &prm, int np_lds, int grid, int threads, hipStream_t stream)
 {
     if (threads == 512) {
-        if (dtype == RS_BF16) return D == 128 ? launch_fused<bf16, 128, 512>(prm, grid, stream) : launch_fused<bf16, 64, 512>(prm, grid, stream);
-        return D == 128 ? launch_fused<float, 128, 512>(prm, grid, stream) : launch_fused<float, 64, 512>(prm, grid, stream);
+        if (dtype == RS_BF16) return D == 128 ? launch_fused<bf16, 128, 512>(prm, np_lds, grid, stream) : launch_fused<bf16, 64, 512>(prm, np_lds, grid, stream);
+        return D == 128 ? launch_fused<float, 128, 512>(prm, np_lds, grid, stream) : launch_fused<float, 64, 512>(prm, np_lds, grid, stream);
     }
-    if (dtype == RS_BF16) return D == 128 ? launch_fused<bf16, 128, 256>(prm, grid, stream) : launch_fused<bf16, 64, 256>(prm, grid, stream);
-    return D == 128 ? launch_fused<float, 128, 256>(prm, grid, stream) : launch_fused<float, 64, 256>(prm, grid, stream);
+    if (dtype == RS_BF16) return D == 128 ? launch_fused<bf16, 128, 256>(prm, np_lds, grid, stream) : launch_fused<bf16, 64, 256>(prm, np_lds, grid, stream);
+    return D == 128 ? launch_fused<float, 128, 256>(prm, np_lds, grid, stream) : launch_fused<float, 64, 256>(prm, np_lds, grid, stream);
 }
 
 }  // namespace rs

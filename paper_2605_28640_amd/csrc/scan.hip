@@ -252,10 +252,15 @@ template <typename ST>
 __global__ __launch_bounds__(256) void rat_step_kernel(
     const ST *__restrict__ k, const ST *__restrict__ v, const float *__restrict__ g,
     float *__restrict__ state_k, float *__restrict__ state_v, ST *__restrict__ k_cache,
-    ST *__restrict__ v_cache, ST *__restrict__ meta, int P, int BH, int D, long T_new, long t0, long Tcap)
+    ST *__restrict__ v_cache, ST *__restrict__ meta, int P, int BH, int D, long T_new, long t0, long Tcap,
+    const uint32_t *__restrict__ pos_state, long T_max)
 {
     const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (long)BH * D) return;
+    if (pos_state) {  // replayable step: the write position is the workspace's token count
+        t0 = *reinterpret_cast<const long *>(pos_state + kCtrlStateT);
+        if (t0 + T_new > T_max) return;  // the step's attention kernel reports it
+    }
     const long bh = e / D;
     const int c = (int)(e % D);
     float sk = state_k[e], sv = state_v[e];
@@ -335,10 +340,10 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
         const unsigned blocks = (unsigned)((n + 255) / 256);
         if (dtype == RS_BF16)
             rat_step_kernel<bf16><<<blocks, 256, 0, stream>>>((const bf16 *)k, (const bf16 *)v, g, state_k, state_v,
-                                                             (bf16 *)k_cache, (bf16 *)v_cache, (bf16 *)meta, P, BH, D, T_new, t0, Tcap);
+                                                             (bf16 *)k_cache, (bf16 *)v_cache, (bf16 *)meta, P, BH, D, T_new, t0, Tcap, nullptr, 0);
         else
             rat_step_kernel<float><<<blocks, 256, 0, stream>>>((const float *)k, (const float *)v, g, state_k, state_v,
-                                                              (float *)k_cache, (float *)v_cache, (float *)meta, P, BH, D, T_new, t0, Tcap);
+                                                              (float *)k_cache, (float *)v_cache, (float *)meta, P, BH, D, T_new, t0, Tcap, nullptr, 0);
         return;
     }
     // few (batch, head) pairs and a long run: 32-channel slabs, so that the chunk chains are
@@ -354,6 +359,21 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
         else slab ? RS_SCAN(float, 64, 32) : RS_SCAN(float, 64, 64);
     }
 #undef RS_SCAN
+}
+
+// the decode-time append of one token at the position the workspace's state words hold
+void step_at_state_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
+                            float *state_v, void *k_cache, void *v_cache, void *meta, int P, int BH, long Tcap,
+                            const uint32_t *pos_state, long T_max, hipStream_t stream)
+{
+    const long n = (long)BH * D;
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    if (dtype == RS_BF16)
+        rat_step_kernel<bf16><<<blocks, 256, 0, stream>>>((const bf16 *)k, (const bf16 *)v, g, state_k, state_v,
+                                                         (bf16 *)k_cache, (bf16 *)v_cache, (bf16 *)meta, P, BH, D, 1, 0, Tcap, pos_state, T_max);
+    else
+        rat_step_kernel<float><<<blocks, 256, 0, stream>>>((const float *)k, (const float *)v, g, state_k, state_v,
+                                                          (float *)k_cache, (float *)v_cache, (float *)meta, P, BH, D, 1, 0, Tcap, pos_state, T_max);
 }
 
 }  // namespace rs

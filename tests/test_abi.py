@@ -73,6 +73,20 @@ def test_every_entry_point_rejects_bad_arguments_before_touching_the_gpu():
     assert lib.sparse_attn_decode(sp, A, A, A, 256, 0.1, None, 4, A, 1, 1, None, None, None, A, big, None) == 1
     assert lib.sparse_attn_decode(sp, A, A, A, 256, 0.1, None, 4, A, 1, 1, A, None, None, A, 16, None) == 3
 
+    # rat_decode_step(s, k, v, g, state_k, state_v, k_cache, v_cache, meta, q, scale, K, n_first, n_local,
+    #                 T_max, out, lse_out, idx_out, ws, ws_bytes, stream)
+    assert lib.rat_decode_step(sp, A, A, A, A, A, A, A, None, A, 0.1, 4, 1, 1, 256, A, None, None, A, big, None) == 1
+    assert lib.rat_decode_step(sp, A, A, A, A, A, A, A, A, A, 0.1, 17, 1, 1, 256, A, None, None, A, big, None) == 1
+    assert lib.rat_decode_step(sp, A, A, A, A, A, A, A, A, A, 0.1, 4, 3, 2, 256, A, None, None, A, big, None) == 1
+    assert lib.rat_decode_step(sp, A, A, A, A, A, A, A, A, A, 0.1, 4, 1, 1, 257, A, None, None, A, big, None) == 1
+    assert lib.rat_decode_step(sp, A, A, A, A, A, A, A, A, A + 4, 0.1, 4, 1, 1, 256, A, None, None, A, big, None) == 1
+    assert lib.rat_decode_step(sp, A, A, A, A, A, A, A, A, A, 0.1, 4, 1, 1, 256, A, None, None, A, 16, None) == 3
+    assert lib.rat_decode_state_set(None, big, 0, None) == 1
+    assert lib.rat_decode_state_set(A, big, -1, None) == 1
+    assert lib.rat_decode_state_set(A, 16, 0, None) == 3
+    assert lib.rat_decode_state_get(None, None, None) == 1
+    assert lib.rat_decode_step_workspace_bytes(sp, 257, 4) == 0
+
     # moba_select_prefill(s, q, k_cache, T, block, K, n_first, means_out, idx_out, ws, ws_bytes, stream)
     assert lib.moba_select_prefill(sp, A, A, 256, 24, 3, 0, A, A, A, big, None) == 1     # block not a multiple of 16
     assert lib.moba_select_prefill(sp, A, A, 256, 64, 33, 0, A, A, A, big, None) == 1    # K > 32
@@ -102,6 +116,7 @@ def test_every_entry_point_rejects_bad_arguments_before_touching_the_gpu():
     n = lib.sparse_attn_decode_workspace_bytes(hp, 15361 * 16, 4)
     assert lib.quest_select_decode(hp, A, A, 15361 * 16, 4, 1, 1, A, None, A, n, None) == 2
     assert lib.sparse_attn_decode(hp, A, A, A, 15361 * 16, 0.1, None, 4, A, 1, 1, A, None, None, A, n, None) == 2
+    assert lib.rat_decode_step(hp, A, A, A, A, A, A, A, A, A, 0.1, 4, 1, 1, 15361 * 16, A, None, None, A, n, None) == 2
 
     # shapes
     for bad in (binding.make_shape(0, 4, 2, 128, 256, 16, binding.RS_BF16),

@@ -1,0 +1,196 @@
+"""The replayable decode step (append one token of the gated cache, select pages, attend them,
+with the sequence length held on the device) against the two calls it stands for (rat_scan
+with one token, then sparse_attn_decode in its fused mode), bit for bit, eagerly and replayed
+from a captured HIP graph; and its last step against the float64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import say, tdtype, to_dev, to_np
+from helpers import attn_close, bf16_store_ok, scan_close, topk_set_ok
+from paper_2605_28640_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+class _Side:
+    """One copy of the recurrent state, the caches and the page metadata after a prefill of T0 tokens."""
+
+    def __init__(self, rs, w, s, T0, Tcap, P, k, v, g):
+        dt = tdtype(w.dtype)
+        self.sk = torch.zeros(w.B, w.Hkv, w.D, device="cuda")
+        self.sv = torch.zeros_like(self.sk)
+        self.kc = torch.zeros(w.B, w.Hkv, Tcap, w.D, dtype=dt, device="cuda")
+        self.vc = torch.zeros_like(self.kc)
+        self.meta = torch.zeros(w.B, w.Hkv, Tcap // P, 2, w.D, dtype=dt, device="cuda")
+        ws = rs.Workspace(rs.rat_scan_workspace_bytes(s, T0))
+        rs.rat_scan(s, k, v, g, self.sk, self.sv, self.kc, self.vc, 0, T0, ws, self.meta)
+        torch.cuda.synchronize()
+
+    def same_as(self, o):
+        return all(torch.equal(a, b) for a, b in ((self.sk, o.sk), (self.sv, o.sv), (self.kc, o.kc),
+                                                   (self.vc, o.vc), (self.meta, o.meta)))
+
+
+CASES = [
+    # workload, T0, steps, Tcap, P, K, n_first, n_local
+    (synth.C2.scaled(B=2, Hq=8, Hkv=2), 300, 40, 1024, 16, 8, 1, 1),   # GQA bf16, crosses three page edges
+    (synth.C1.scaled(B=1, Hq=4, Hkv=4), 2040, 20, 2304, 64, 5, 0, 1),   # f32 D=64, 64-token pages, one edge
+    (synth.C3.scaled(B=1, Hq=8, Hkv=8), 9000, 12, 9216, 16, 36, 1, 2),  # several attention slices per unit
+]
+
+
+def _setup(rs, case):
+    w, T0, steps, Tcap, P, K, n_first, n_local = CASES[case]
+    w = w.scaled(T=T0)
+    dt = tdtype(w.dtype)
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tcap, P, dt)
+    k, v, g = synth.prefill(w)
+    tk, tv, tg = to_dev(k, w.dtype), to_dev(v, w.dtype), to_dev(g)
+    a = _Side(rs, w, s, T0, Tcap, P, tk, tv, tg)
+    b = _Side(rs, w, s, T0, Tcap, P, tk, tv, tg)
+    assert a.same_as(b)
+    return w, s, (k, v, g), a, b
+
+
+def _step_inputs(w, step):
+    k, v, g, q = synth.decode_step(w, step)
+    return to_dev(k, w.dtype), to_dev(v, w.dtype), to_dev(g), to_dev(q, w.dtype), (k, v, g, q)
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_step_equals_scan_then_fused_decode(rs, monkeypatch, case):
+    monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0")  # the step is the one-launch form
+    _, T0, steps, Tcap, P, K, n_first, n_local = CASES[case]
+    say("decode step case", case, T0, steps, Tcap, P, K)
+    w, s, pre, a, b = _setup(rs, case)
+    dt = tdtype(w.dtype)
+    T_max = T0 + steps
+    scale = 1.0 / np.sqrt(w.D)
+    ws_a = rs.Workspace(rs.rat_decode_step_workspace_bytes(s, T_max, K))
+    ws_b = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, T_max, K))
+    rs.rat_decode_state_set(ws_a, T0)
+    assert rs.rat_decode_state_get(ws_a) == T0
+    out_a = torch.zeros(w.B, w.Hq, w.D, dtype=dt, device="cuda")
+    out_b = torch.zeros_like(out_a)
+    lse_a, lse_b = torch.zeros(w.B, w.Hq, device="cuda"), torch.zeros(w.B, w.Hq, device="cuda")
+    idx_a = torch.zeros(w.B, w.Hq, K, dtype=torch.int32, device="cuda")
+    idx_b = torch.zeros_like(idx_a)
+    hist = list(pre)  # k, v, g of every token so far, for the oracle
+    for t in range(steps):
+        tk, tv, tg, tq, host = _step_inputs(w, t)
+        rs.rat_decode_step(s, tk, tv, tg, a.sk, a.sv, a.kc, a.vc, a.meta, tq, scale, K, n_first, n_local, T_max,
+                           out_a, lse_a, idx_a, ws_a)
+        rs.rat_scan(s, tk, tv, tg, b.sk, b.sv, b.kc, b.vc, T0 + t, 1, None, b.meta)
+        rs.sparse_attn_decode(s, tq, b.kc, b.vc, T0 + t + 1, scale, None, K, b.meta, n_first, n_local, out_b, lse_b,
+                              idx_b, ws_b)
+        torch.cuda.synchronize()
+        assert torch.equal(idx_a, idx_b), t
+        assert torch.equal(out_a, out_b) and torch.equal(lse_a, lse_b), t
+        hist = [np.concatenate([hist[i], host[i]], axis=2) for i in range(3)]
+    assert a.same_as(b)
+    assert rs.rat_decode_state_get(ws_a) == T_max
+    ws_a.async_status()
+    ws_b.async_status()
+
+    # the last step against the oracle: scan of every token, selection on the stored keys, attention
+    ko, vo, _, _ = oracle.rat_scan(*hist)
+    kc = to_np(a.kc)[:, :, :T_max]
+    if w.dtype == "bf16":
+        assert bf16_store_ok(kc, ko)
+    else:
+        assert scan_close(kc, ko)[0]
+    kfull, vfull = to_np(a.kc), to_np(a.vc)
+    Np = -(-T_max // P)
+    ometa = oracle.quest_page_meta(kfull, P, T_max)
+    np.testing.assert_array_equal(to_np(a.meta)[:, :, :Np], ometa[:, :, :Np])
+    osc = oracle.quest_scores(host[3], ometa, Np)
+    forced = np.zeros(Np, dtype=bool)
+    forced[:n_first] = True
+    if n_local:
+        forced[Np - n_local:] = True
+    gidx = to_np(idx_a)
+    for bb in range(w.B):
+        for h in range(w.Hq):
+            ok, why = topk_set_ok(osc[bb, h], forced, K, gidx[bb, h])
+            assert ok, (bb, h, why)
+    oout, _ = oracle.sparse_attn_decode(host[3], kfull, vfull, P, T_max, scale, gidx)
+    ok, worst = attn_close(to_np(out_a), oout, 2e-2 if w.dtype == "bf16" else 1e-4)
+    assert ok, worst
+
+
+def test_step_past_the_sized_length_changes_nothing_and_reports(rs):
+    w, T0, steps, Tcap, P, K, n_first, n_local = CASES[0]
+    w, s, pre, a, b = _setup(rs, 0)
+    dt = tdtype(w.dtype)
+    scale = 1.0 / np.sqrt(w.D)
+    T_max = T0 + 1
+    ws = rs.Workspace(rs.rat_decode_step_workspace_bytes(s, T_max, K))
+    rs.rat_decode_state_set(ws, T0)
+    out = torch.zeros(w.B, w.Hq, w.D, dtype=dt, device="cuda")
+    tk, tv, tg, tq, _ = _step_inputs(w, 0)
+
+    def step():
+        rs.rat_decode_step(s, tk, tv, tg, a.sk, a.sv, a.kc, a.vc, a.meta, tq, scale, K, n_first, n_local, T_max, out,
+                           None, None, ws)
+
+    step()
+    ws.async_status()
+    assert rs.rat_decode_state_get(ws) == T_max
+    keep = (a.sk.clone(), a.kc.clone(), a.meta.clone(), out.clone())
+    step()  # one more than the workspace was sized for
+    with pytest.raises(rs.RatsparseError):
+        ws.async_status()
+    assert rs.rat_decode_state_get(ws) == T_max
+    assert torch.equal(keep[0], a.sk) and torch.equal(keep[1], a.kc) and torch.equal(keep[2], a.meta)
+    assert torch.equal(keep[3], out)
+
+
+def test_step_replays_from_a_captured_graph(rs, monkeypatch):
+    monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0")
+    _, T0, steps, Tcap, P, K, n_first, n_local = CASES[0]
+    w, s, pre, a, b = _setup(rs, 0)
+    dt = tdtype(w.dtype)
+    T_max = T0 + steps + 1
+    scale = 1.0 / np.sqrt(w.D)
+    ws_a = rs.Workspace(rs.rat_decode_step_workspace_bytes(s, T_max, K))
+    ws_b = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, T_max, K))
+    rs.rat_decode_state_set(ws_a, T0)
+    out_a = torch.zeros(w.B, w.Hq, w.D, dtype=dt, device="cuda")
+    out_b = torch.zeros_like(out_a)
+    idx_a = torch.zeros(w.B, w.Hq, K, dtype=torch.int32, device="cuda")
+    idx_b = torch.zeros_like(idx_a)
+    tk, tv, tg, tq, _ = _step_inputs(w, 0)
+
+    def step():
+        rs.rat_decode_step(s, tk, tv, tg, a.sk, a.sv, a.kc, a.vc, a.meta, tq, scale, K, n_first, n_local, T_max,
+                           out_a, None, idx_a, ws_a)
+
+    def eager(t):
+        rs.rat_scan(s, tk, tv, tg, b.sk, b.sv, b.kc, b.vc, T0 + t, 1, None, b.meta)
+        rs.sparse_attn_decode(s, tq, b.kc, b.vc, T0 + t + 1, scale, None, K, b.meta, n_first, n_local, out_b, None,
+                              idx_b, ws_b)
+
+    step()  # step 0 eagerly, outside the capture: it advances the device's count like any other
+    eager(0)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    assert rs.rat_decode_state_get(ws_a) == T0 + 1  # a capture runs nothing
+    for t in range(1, steps + 1):
+        nk, nv, ng, nq, _ = _step_inputs(w, t)
+        tk.copy_(nk), tv.copy_(nv), tg.copy_(ng), tq.copy_(nq)
+        torch.cuda.synchronize()
+        graph.replay()
+        eager(t)
+        torch.cuda.synchronize()
+        assert torch.equal(idx_a, idx_b), t
+        assert torch.equal(out_a, out_b), t
+    assert a.same_as(b)
+    assert rs.rat_decode_state_get(ws_a) == T0 + steps + 1
+    ws_a.async_status()
