@@ -34,6 +34,7 @@
  *     HIP graph and replayed.  rat_scan, quest_select_decode and sparse_attn_decode (and
  *     their _group forms) hand a fresh call tag to their kernels on every call (it tells this call's
  *     words in the workspace from stale ones) and must be called, not replayed.
+ *     rat_decode_step keeps its tag and the sequence length on the device and may be replayed.
  */
 #ifndef RATSPARSE_H
 #define RATSPARSE_H
