@@ -85,6 +85,11 @@ int32_t ratsparse_async_status(void *ws, void *stream);
  * never written.  The achieved rate is the read ceiling to hold a read-bound kernel against. */
 int32_t ratsparse_probe_read(const void *src, size_t bytes, void *sink, void *stream);
 
+/* Test hook: the bound, in polls, of every in-kernel wait of calls made from now on (the
+ * default is 1 << 22).  With 0 a kernel that would have to wait gives up at once, exits
+ * normally and records RS_ASYNC_TIMEOUT: the error path can be tested without a hang. */
+void ratsparse_debug_set_spin_limit(int32_t polls);
+
 /* ---- Exponentially decaying memory: Sec. 2.1, Eq. 1 --------------------------------
  * For every (batch, KV head, channel):  s_t = g_t * s_{t-1} + (1 - g_t) * x_t  for the
  * T_new tokens given, for x = k and x = v with the same gate, starting from the carry.

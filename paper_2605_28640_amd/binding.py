@@ -37,6 +37,7 @@ SIGNATURES = {
     "ratsparse_workspace_init": (_i32, [_vp, _sz, _vp]),
     "ratsparse_async_status": (_i32, [_vp, _vp]),
     "ratsparse_probe_read": (_i32, [_vp, _sz, _vp, _vp]),
+    "ratsparse_debug_set_spin_limit": (None, [_i32]),
     "rat_scan_workspace_bytes": (_sz, [_shp, _i64]),
     "rat_scan": (_i32, [_shp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _sz, _vp]),
     "quest_page_meta": (_i32, [_shp, _vp, _vp, _i64, _i64, _vp]),
@@ -76,8 +77,6 @@ def load():
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)
             fn.restype, fn.argtypes = res, args
-        lib.ratsparse_debug_set_spin_limit.restype = None
-        lib.ratsparse_debug_set_spin_limit.argtypes = [_i32]
         _lib = lib
     return _lib
 

@@ -194,3 +194,53 @@ def test_step_replays_from_a_captured_graph(rs, monkeypatch):
     assert a.same_as(b)
     assert rs.rat_decode_state_get(ws_a) == T0 + steps + 1
     ws_a.async_status()
+
+
+def test_step_at_the_measured_size_equals_the_two_calls(rs, monkeypatch):
+    """The measured configuration (batch 4, 32 heads, 64K context, 256 of 4096+ pages): several
+    score and attention slices per unit, page count growing under the fixed work split."""
+    monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0")
+    B, H, D, P, K = 4, 32, 128, 16, 256
+    T0, steps = 65536 - 6, 14  # crosses the edge of page 4096
+    Tcap = 65536 + 64
+    T_max = T0 + steps
+    dt = torch.bfloat16
+    s = rs.make_shape(B, H, H, D, Tcap, P, dt)
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    sides = []
+    kc0 = (torch.randn(B, H, Tcap, D, device="cuda", generator=gen) * 0.5).to(dt)
+    vc0 = torch.randn(B, H, Tcap, D, device="cuda", generator=gen).to(dt)
+    sk0 = torch.randn(B, H, D, device="cuda", generator=gen)
+    sv0 = torch.randn(B, H, D, device="cuda", generator=gen)
+    for _ in range(2):
+        kc, vc = kc0.clone(), vc0.clone()
+        meta = torch.zeros(B, H, Tcap // P, 2, D, dtype=dt, device="cuda")
+        rs.quest_page_meta(s, kc, meta, 0, T0)
+        sides.append((sk0.clone(), sv0.clone(), kc, vc, meta))
+    del kc0, vc0
+    a, b = sides
+    scale = 1.0 / np.sqrt(D)
+    ws_a = rs.Workspace(rs.rat_decode_step_workspace_bytes(s, T_max, K))
+    ws_b = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, T_max, K))
+    rs.rat_decode_state_set(ws_a, T0)
+    out_a = torch.zeros(B, H, D, dtype=dt, device="cuda")
+    out_b = torch.zeros_like(out_a)
+    idx_a = torch.zeros(B, H, K, dtype=torch.int32, device="cuda")
+    idx_b = torch.zeros_like(idx_a)
+    for t in range(steps):
+        say("full-size decode step", t)
+        k = torch.randn(B, H, 1, D, device="cuda", generator=gen).to(dt)
+        v = torch.randn(B, H, 1, D, device="cuda", generator=gen).to(dt)
+        g = torch.rand(B, H, 1, D, device="cuda", generator=gen)
+        q = torch.randn(B, H, D, device="cuda", generator=gen).to(dt)
+        rs.rat_decode_step(s, k, v, g, a[0], a[1], a[2], a[3], a[4], q, scale, K, 1, 1, T_max, out_a, None, idx_a, ws_a)
+        rs.rat_scan(s, k, v, g, b[0], b[1], b[2], b[3], T0 + t, 1, None, b[4])
+        rs.sparse_attn_decode(s, q, b[2], b[3], T0 + t + 1, scale, None, K, b[4], 1, 1, out_b, None, idx_b, ws_b)
+        torch.cuda.synchronize()
+        assert torch.equal(idx_a, idx_b), t
+        assert torch.equal(out_a, out_b), t
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    assert rs.rat_decode_state_get(ws_a) == T_max
+    ws_a.async_status()
+    ws_b.async_status()
