@@ -244,10 +244,7 @@ int score_select_dispatch(int dtype, int D, int GQ, const void *q, const void *m
 // decode attention over a list of 16-row tiles (selected pages, or all rows), split over
 // workgroups; partial (m, l, o) per split; the last split to arrive merges them.
 // ------------------------------------------------------------------------------------
-constexpr int kAttThreads = 256;
-constexpr int kAttWaves = kAttThreads / 64;
-
-template <typename ST, int D>
+template <typename ST, int D, int kAttThreads>
 __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
     const ST *__restrict__ q, const ST *__restrict__ k_cache, const ST *__restrict__ v_cache, const int32_t *idx,
     ST *__restrict__ out, float *__restrict__ lse_out, uint64_t *partial, int Hq, int Hkv, long Tcap, int P,
@@ -259,6 +256,7 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
     constexpr int TR = 16;         // rows per tile
     constexpr int RPL = TR / RPW;  // rows per lane per tile (4 for D=128, 2 for D=64)
     constexpr int TPI = 2;         // tiles in flight per wave
+    constexpr int kAttWaves = kAttThreads / 64;
     using R = Row8<ST>;
     __shared__ float s_m[kAttWaves], s_l[kAttWaves];
     __shared__ float s_o[kAttWaves][D];
@@ -433,10 +431,18 @@ void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache
                             hipStream_t stream)
 {
     const dim3 grid((unsigned)splits, (unsigned)(B * Hq));
-#define RS_LAUNCH(ST, DD)                                                                                   \
-    decode_attend_kernel<ST, DD><<<grid, kAttThreads, 0, stream>>>(                                         \
+    const char *e = std::getenv("RATSPARSE_ATTEND_THREADS");
+    const int nt = e ? std::atoi(e) : 512;
+#define RS_LAUNCH1(ST, DD, NT)                                                                              \
+    decode_attend_kernel<ST, DD, NT><<<grid, NT, 0, stream>>>(                                              \
         (const ST *)q, (const ST *)k_cache, (const ST *)v_cache, idx, (ST *)out, lse_out, partial, Hq, Hkv, \
         Tcap, P, T_valid, K, scale, splits, unit_ctr, err, tag, spin_limit, idx_per_kv)
+#define RS_LAUNCH(ST, DD)                          \
+    do {                                           \
+        if (nt == 1024) RS_LAUNCH1(ST, DD, 1024);  \
+        else if (nt == 512) RS_LAUNCH1(ST, DD, 512); \
+        else RS_LAUNCH1(ST, DD, 256);              \
+    } while (0)
     if (dtype == RS_BF16) {
         if (D == 128) RS_LAUNCH(bf16, 128);
         else RS_LAUNCH(bf16, 64);
@@ -444,6 +450,7 @@ void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache
         if (D == 128) RS_LAUNCH(float, 128);
         else RS_LAUNCH(float, 64);
     }
+#undef RS_LAUNCH1
 #undef RS_LAUNCH
 }
 
