@@ -39,7 +39,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (every box has one; the path shards over batch "
-              "and heads with no exchange, see DESIGN.md). --gpus %d is not supported." % args.gpus,
+              "and heads with no exchange). --gpus %d is not supported." % args.gpus,
               file=sys.stderr)
         sys.exit(2)
 
