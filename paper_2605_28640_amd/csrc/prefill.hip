@@ -22,6 +22,8 @@
 // than 2^8, and masks only on steps a boundary crosses.  Partials are kept as bfloat16 o
 // (float32 log-sum-exp).  Output rows and partial records pass through LDS on their way out
 // and in, so that global memory sees whole 2 D-byte rows.
+#include <cstdlib>
+
 #include "common.h"
 
 #include <type_traits>
@@ -172,7 +174,11 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
 }
 
-template <int D>
+// MASKED: the routed form for dense routings (small blocks, many picks per row): contiguous
+// causal tiles as in the dense case, each lane carrying the bit set of its row's listed blocks;
+// a 64-key step lies inside one block (block % 64 == 0), a lane whose row did not list it adds
+// nothing there, and a wave none of whose rows listed it skips the step's arithmetic.
+template <int D, bool MASKED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_attn_kernel(const PrefillParams a)
 {
     constexpr int NC = D / 16;     // 16-wide d chunks of the QK^T contraction
@@ -216,7 +222,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     uint32_t lbase = 0, lcount = 0;
     {
         const int x = xtile;
-        if (a.idx == nullptr) {  // dense causal: heavy tiles first
+        if (MASKED || a.idx == nullptr) {  // dense causal (or routed by bit sets): heavy tiles first
             const int tile = a.n_diag - 1 - x;
             r0 = (long)tile * kMT;
             kv_begin = 0;
@@ -268,7 +274,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         tq = r0 + rq;
     }
     const bool causal = !gathered;
-    const long own_begin = (a.idx != nullptr && !gathered && tq >= 0) ? (tq / a.block) * a.block : 0;
+    const long own_begin = (!MASKED && a.idx != nullptr && !gathered && tq >= 0) ? (tq / a.block) * a.block : 0;
     // last key any lane of this wave may see (contiguous tiles): later steps are skipped by the wave
     // (a wave none of whose 32 rows exists skips every step; it still stages its share of the tiles)
     const bool wave_live = gathered ? ((uint32_t)(wave * 32) < lcount) : (r0 + wave * 32 < a.T);
@@ -290,6 +296,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const bf16 *qrow = a.q + ((long)unit * a.T + (tq >= 0 ? tq : 0)) * D;
 #pragma unroll
         for (int c = 0; c < NC; ++c) qf[c] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * c + 8 * h);
+    }
+
+    // ---- routed by bit sets: the blocks this lane's row listed (its own block always) ----
+    uint64_t selmask = ~0ull;
+    if constexpr (MASKED) {
+        selmask = 0ull;
+        if (tq >= 0) {
+            const int32_t *row = a.idx + ((long)unit * a.T + tq) * a.K;
+            for (int kk = 0; kk < a.K; ++kk) {
+                const int j = row[kk];
+                if (j >= 0 && j < 64) selmask |= 1ull << j;
+            }
+            selmask |= 1ull << (int)(tq / a.block);
+        }
+    }
+    // the blocks any row of this wave listed, as a scalar: steps outside it are skipped by the wave
+    uint64_t wave_mask = ~0ull;
+    if constexpr (MASKED) {
+        uint32_t lo = (uint32_t)selmask, hi = (uint32_t)(selmask >> 32);
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            lo |= (uint32_t)__shfl_xor((int)lo, m);
+            hi |= (uint32_t)__shfl_xor((int)hi, m);
+        }
+        wave_mask = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)hi) << 32) |
+                    (uint32_t)__builtin_amdgcn_readfirstlane((int)lo);
     }
 
     // ---- operand addresses inside a tile (elements), fixed per lane ----
@@ -325,6 +357,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     float m = -INFINITY, l = 0.f;
 
     const int n_steps = (int)((kv_end - kv_begin + kKT - 1) / kKT);
+    const int steps_per_block = a.block / kKT;
+    int cur_blk = 0, cur_rem = steps_per_block;  // MASKED: kv_begin = 0
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's part of tile 0 is in LDS
     __syncthreads();
 
@@ -339,7 +373,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         uint16_t *nK = BUF ? sK0 : sK1, *nV = BUF ? sV0 : sV1;
         const long kn = k0 + kKT;
 
-        if (k0 > wave_last) {
+        bool sel = true;
+        if constexpr (MASKED) sel = (selmask >> cur_blk) & 1ull;
+        if (k0 > wave_last || (MASKED && !((wave_mask >> cur_blk) & 1ull))) {
             if constexpr (NEXT) {
 #pragma unroll
                 for (int i = 0; i < CPT; ++i) {
@@ -401,6 +437,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                 for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[sub][v]);
             mx = half_pair_max(mx) * cs;  // cs > 0: scaling commutes with max
+            if (MASKED && !sel) mx = -INFINITY;
             // the reference point of the exponentials follows the running maximum lazily: it moves
             // only when the maximum has grown by more than kLazy (p then stays below 2^kLazy,
             // harmless in float32 and bfloat16), so the accumulators are rarely rescaled
@@ -417,11 +454,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 m = m_new;
             }
             float psum = 0.f;
+            // a row that did not list this step's block: every exponent is -inf, p = 0
+            const float ebias = (MASKED && !sel) ? -INFINITY : -m_safe;
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    sacc[sub][v] = __builtin_amdgcn_exp2f(fmaf(sacc[sub][v], cs, -m_safe));
+                    sacc[sub][v] = __builtin_amdgcn_exp2f(fmaf(sacc[sub][v], cs, ebias));
                     psum += sacc[sub][v];
                 }
             l += half_pair_sum(psum);
@@ -464,6 +503,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
             __builtin_amdgcn_s_setprio(0);
+        }
+        if constexpr (MASKED) {  // block of the next step (wave-uniform counters, no division)
+            if (--cur_rem == 0) {
+                cur_rem = steps_per_block;
+                ++cur_blk;
+            }
         }
         if constexpr (NEXT) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's loads have landed
         __syncthreads();
@@ -517,7 +562,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
     const float inv = (l > 0.f) ? 1.f / l : 0.f;
     const float lse = (l > 0.f) ? (m + __log2f(l)) * 0.6931471805599453f : -INFINITY;
-    if (a.idx != nullptr && gathered) {
+    if (!MASKED && a.idx != nullptr && gathered) {
         // a partial record: the row's normalised output over one listed block as bf16 (channel
         // order), its log-sum-exp as float32 in an array of its own
         uint32_t ent[32 / RW];  // list entries of the rows this lane helps to flush
@@ -539,7 +584,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const long wrow0 = r0 + wave * 32;  // contiguous tiles: the wave's first row
     float out_scale = inv;
     float out_lse = lse;
-    if (a.idx != nullptr) {
+    if (!MASKED && a.idx != nullptr) {
         // own-block tile: fold in the partials the listed-row tiles left for this row's other
         // blocks (they ran in the previous launch).  Two slots at a time: their records of the
         // wave's 32 rows come in by row-contiguous direct loads, the lanes then pick their channels.
@@ -669,6 +714,12 @@ static PrefillLayout prefill_layout(const rs_shape *s, long T, int block, int K)
     return L;
 }
 
+static int env_int_pf(const char *name, int dflt)
+{
+    const char *e = std::getenv(name);
+    return e ? std::atoi(e) : dflt;
+}
+
 size_t prefill_ws_bytes(const rs_shape *s, long T, int block, int K) { return prefill_layout(s, T, block, K).total; }
 
 int prefill_dispatch(const rs_shape *s, const void *q, const void *k_cache, const void *v_cache, long T, int block,
@@ -701,8 +752,25 @@ int prefill_dispatch(const rs_shape *s, const void *q, const void *k_cache, cons
     p.part_lse = nullptr;
     p.list_stride = 0;
     p.phase = 2;
+    if (idx && Nb > 256) return RS_UNSUPPORTED;
+    // Routings that are dense for their length (small blocks, many picks: the paper's 64- and
+    // 128-token blocks with top-8 / top-16 at 4K) run as causal tiles with a bit set per row
+    // instead of being regrouped by block.  Regrouped, a row costs (K - 1) listed tiles' worth of
+    // steps plus a fixed cost per tile (row list, scattered queries, partial records: about 4.3
+    // steps) and the fold (about 9); by bit sets it costs the causal steps of its tile, some
+    // skipped.  Measured at 8 x 32 heads x 4096 tokens (regrouped / bit sets / plain causal, ms):
+    // blocks of 64: top-16 3.14 / 1.20 / 1.30, top-8 1.75 / 1.16, top-4 0.98 / 1.08;
+    // blocks of 128: top-8 1.72 / 1.19, top-4 0.98 / 1.15; 8192 tokens, 128, top-8: 0.92 / 1.03.
+    const bool can_mask = idx && Nb <= 64 && block % kKT == 0;
+    const double by_sets = 0.85 * (p.n_diag + 4.0), regrouped = (K - 1) * (4.3 + block / 64.0) + 9.0;
+    const int masked = can_mask ? env_int_pf("RATSPARSE_PREFILL_MASKED", by_sets < regrouped ? 1 : 0) : 0;
+    if (masked) {
+        const dim3 grid((unsigned)p.n_diag, (unsigned)units);
+        if (s->D == 128) prefill_attn_kernel<128, true><<<grid, 256, 0, stream>>>(p);
+        else prefill_attn_kernel<64, true><<<grid, 256, 0, stream>>>(p);
+        return hipGetLastError() == hipSuccess ? RS_OK : RS_LAUNCH_FAILED;
+    }
     if (idx) {
-        if (Nb > 256) return RS_UNSUPPORTED;
         const PrefillLayout L = prefill_layout(s, T, block, K);
         uint32_t *cnt = (uint32_t *)(ws + L.off_cnt), *off = (uint32_t *)(ws + L.off_off);
         uint32_t *tile_off = (uint32_t *)(ws + L.off_tile), *cursor = (uint32_t *)(ws + L.off_cursor);
@@ -730,14 +798,14 @@ int prefill_dispatch(const rs_shape *s, const void *q, const void *k_cache, cons
         p.phase = 0;
         const dim3 g0((unsigned)gathered_tiles, (unsigned)units);
         if (K > 1) {
-            if (s->D == 128) prefill_attn_kernel<128><<<g0, 256, 0, stream>>>(p);
-            else prefill_attn_kernel<64><<<g0, 256, 0, stream>>>(p);
+            if (s->D == 128) prefill_attn_kernel<128, false><<<g0, 256, 0, stream>>>(p);
+            else prefill_attn_kernel<64, false><<<g0, 256, 0, stream>>>(p);
         }
         p.phase = 1;
     }
     const dim3 grid((unsigned)p.n_diag, (unsigned)units);
-    if (s->D == 128) prefill_attn_kernel<128><<<grid, 256, 0, stream>>>(p);
-    else prefill_attn_kernel<64><<<grid, 256, 0, stream>>>(p);
+    if (s->D == 128) prefill_attn_kernel<128, false><<<grid, 256, 0, stream>>>(p);
+    else prefill_attn_kernel<64, false><<<grid, 256, 0, stream>>>(p);
     return hipGetLastError() == hipSuccess ? RS_OK : RS_LAUNCH_FAILED;
 }
 

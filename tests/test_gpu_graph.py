@@ -12,7 +12,9 @@ from paper_2605_28640_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def test_prefill_path_replays_from_a_captured_graph(rs):
+@pytest.mark.parametrize("form", ["0", "1"])  # routed attention regrouped by block / by bit sets
+def test_prefill_path_replays_from_a_captured_graph(rs, monkeypatch, form):
+    monkeypatch.setenv("RATSPARSE_PREFILL_MASKED", form)
     B, H, D, T, block, K = 1, 8, 128, 1024, 128, 3
     dt = torch.bfloat16
     s = rs.make_shape(B, H, H, D, T, 16, dt)

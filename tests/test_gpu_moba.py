@@ -63,7 +63,7 @@ CASES += _random_cases(20260528, 8)
 
 
 @pytest.mark.parametrize("case", range(len(CASES)))
-def test_moba_select_and_sparse_prefill(rs, case):
+def test_moba_select_and_sparse_prefill(rs, monkeypatch, case):
     w, T, Tcap, block, K, n_first = CASES[case]
     say("moba case", case, T, Tcap, block, K, n_first)
     w, q, kc, vc = _setup(w, T, Tcap)
@@ -100,12 +100,21 @@ def test_moba_select_and_sparse_prefill(rs, case):
     # block-sparse attention over the GPU's own routing
     out = torch.zeros(w.B, w.Hq, T, w.D, dtype=torch.bfloat16, device="cuda")
     lse = torch.zeros(w.B, w.Hq, T, device="cuda")
-    rs.sparse_attn_prefill(s, tq, tkc, tvc, T, block, scale, idx, K, out, lse, ws)
     oout, olse = oracle.sparse_attn_prefill(q, kc, vc, T, block, scale, gidx)
-    ok, worst = attn_close(to_np(out), oout)
-    assert ok, worst
-    np.testing.assert_allclose(to_np(lse), olse, rtol=2e-3, atol=2e-3)
-    say("  sparse prefill worst relative row error", worst)
+    # both forms of the routed kernel (the library picks by shape; the knob forces either):
+    # regrouped by block, and - for up to 64 blocks of a multiple of 64 tokens - causal tiles
+    # with a bit set of listed blocks per row
+    for form in ("0", "1"):
+        monkeypatch.setenv("RATSPARSE_PREFILL_MASKED", form)
+        out.zero_(), lse.zero_()
+        rs.sparse_attn_prefill(s, tq, tkc, tvc, T, block, scale, idx, K, out, lse, ws)
+        ok, worst = attn_close(to_np(out), oout)
+        assert ok, (form, worst)
+        np.testing.assert_allclose(to_np(lse), olse, rtol=2e-3, atol=2e-3)
+        say("  sparse prefill, form", form, "worst relative row error", worst)
+    monkeypatch.delenv("RATSPARSE_PREFILL_MASKED")
+    rs.sparse_attn_prefill(s, tq, tkc, tvc, T, block, scale, idx, K, out, lse, ws)  # the library's own choice
+    assert attn_close(to_np(out), oout)[0]
 
     # dense causal path, and enough blocks = dense
     outd = torch.zeros_like(out)
