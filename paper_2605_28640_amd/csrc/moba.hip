@@ -159,7 +159,8 @@ __global__ __launch_bounds__(64) void moba_gate_topk_kernel(const ST *__restrict
 typedef __bf16 gate_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float gate_f32x16 __attribute__((ext_vector_type(16)));
 
-template <int D, bool REG>  // REG: picks in registers (K <= 4, at most 64 blocks)
+// KL > 0: picks in registers (at most 64 blocks, K <= KL, KL in {4, 8, 16}); KL = 0: picks by LDS sweeps
+template <int D, int KL>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void moba_gate_mfma_kernel(const bf16 *__restrict__ q, const uint16_t *__restrict__ split,
                                                            int32_t *__restrict__ idx_out, int Hq, int Hkv, long T,
                                                            int block, int Nb, int K, int n_first)
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     }
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the operands are in registers, the LDS tile is free again
     // accumulator value v of lane (lq, h): block j0 + 8 (v / 4) + 4 h + v % 4, query lq
-    if constexpr (REG) {
+    if constexpr (KL > 0) {
         float sc[2][2][16];  // [block group][query tile][value]; -inf: not a candidate
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
@@ -273,22 +274,35 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         uint64_t picks = 0;
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
-            // the four largest of this half-lane's values, then of both halves
-            float a4 = -INFINITY, b4 = -INFINITY, c4 = -INFINITY, d4 = -INFINITY;
+            // the KL largest of this half-lane's values, then of both halves: a descending list,
+            // a new value x enters by top[i] <- median(top[i-1], top[i], x) (old values), top[0] <- max
+            float top[KL];
+#pragma unroll
+            for (int i = 0; i < KL; ++i) top[i] = -INFINITY;
             auto put = [&](float x) __attribute__((always_inline)) {
-                const float na = fmaxf(a4, x), nb = __builtin_amdgcn_fmed3f(a4, b4, x);
-                const float nc = __builtin_amdgcn_fmed3f(b4, c4, x), nd = __builtin_amdgcn_fmed3f(c4, d4, x);
-                a4 = na, b4 = nb, c4 = nc, d4 = nd;
+                float prev = top[0];
+                top[0] = fmaxf(prev, x);
+#pragma unroll
+                for (int i = 1; i < KL; ++i) {
+                    const float cur = top[i];
+                    top[i] = __builtin_amdgcn_fmed3f(prev, cur, x);
+                    prev = cur;
+                }
             };
 #pragma unroll
             for (int g = 0; g < 2; ++g)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) put(sc[g][qt][v]);
-            const float pa = shfl_xor_f(a4, 32), pb = shfl_xor_f(b4, 32), pc = shfl_xor_f(c4, 32), pd = shfl_xor_f(d4, 32);
-            put(pa), put(pb), put(pc), put(pd);
+            float other[KL];
+#pragma unroll
+            for (int i = 0; i < KL; ++i) other[i] = shfl_xor_f(top[i], 32);
+#pragma unroll
+            for (int i = 0; i < KL; ++i) put(other[i]);
             const int avail = own_q[qt] + 1;
             const int take = (K < avail) ? K : avail;
-            const float thr = (take == 1) ? a4 : (take == 2) ? b4 : (take == 3) ? c4 : d4;
+            float thr = top[0];
+#pragma unroll
+            for (int i = 1; i < KL; ++i) thr = (take > i) ? top[i] : thr;  // top[take - 1]
             // blocks of this query (both halves) whose score passes `test` against the threshold
             auto blocks_where = [&](auto test) __attribute__((always_inline)) {
                 uint32_t w[2];
@@ -406,7 +420,8 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     const size_t lds_wave = (size_t)((Nb + 31) / 32 * 32) * 64 * 4;
     // the gate kernel: one-wave workgroups, about eight per CU, each walking over the 64-token
     // tiles of one (batch, head)
-    const bool in_registers = K <= 4 && Nb <= 64;  // its register picks need no score columns
+    const bool in_registers = K <= 16 && Nb <= 64;  // its register picks need no score columns
+    const int kl = K <= 4 ? 4 : K <= 8 ? 8 : 16;
     const size_t lds_mfma = in_registers ? 0 : lds_wave;
     const long n_tiles = (T + 63) / 64, units = (long)s->B * s->Hq;
     long per_unit = (2048 + units - 1) / units;
@@ -422,13 +437,19 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     if (s->dtype == RS_BF16) {
         if (s->D == 128) {
             moba_block_means_kernel<bf16, 128><<<g1p, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
-            if (in_registers) moba_gate_mfma_kernel<128, true><<<g3, 64, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
-            else moba_gate_mfma_kernel<128, false><<<g3, 64, lds_mfma, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
+#define RS_GATE(DD)                                                                                                 \
+    do {                                                                                                            \
+        if (!in_registers) moba_gate_mfma_kernel<DD, 0><<<g3, 64, lds_mfma, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first); \
+        else if (kl == 4) moba_gate_mfma_kernel<DD, 4><<<g3, 64, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);  \
+        else if (kl == 8) moba_gate_mfma_kernel<DD, 8><<<g3, 64, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);  \
+        else moba_gate_mfma_kernel<DD, 16><<<g3, 64, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);            \
+    } while (0)
+            RS_GATE(128);
         } else {
             moba_block_means_kernel<bf16, 64><<<g1p, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
-            if (in_registers) moba_gate_mfma_kernel<64, true><<<g3, 64, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
-            else moba_gate_mfma_kernel<64, false><<<g3, 64, lds_mfma, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);
+            RS_GATE(64);
         }
+#undef RS_GATE
     } else {
         if (s->D == 128) RS_LAUNCH(float, 128);
         else RS_LAUNCH(float, 64);
