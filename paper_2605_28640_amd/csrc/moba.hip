@@ -159,8 +159,11 @@ __global__ __launch_bounds__(64) void moba_gate_topk_kernel(const ST *__restrict
 typedef __bf16 gate_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float gate_f32x16 __attribute__((ext_vector_type(16)));
 
-// KL > 0: picks in registers (at most 64 blocks, K <= KL, KL in {4, 8, 16}); KL = 0: picks by LDS sweeps
-template <int D, int KL>
+// KL > 0 (K <= KL, KL in {4, 8, 16}): the K-th largest score of a query comes from sorted top
+// lists kept in registers while the scores are formed; with at most 64 blocks (WIDE = false)
+// the scores stay in registers too, with more (WIDE) they go to LDS columns and are read back
+// once against the threshold.  KL = 0: picks by K sweeps over the LDS columns (K up to 32).
+template <int D, int KL, bool WIDE>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void moba_gate_mfma_kernel(const bf16 *__restrict__ q, const uint16_t *__restrict__ split,
                                                            int32_t *__restrict__ idx_out, int Hq, int Hkv, long T,
                                                            int block, int Nb, int K, int n_first)
@@ -246,7 +249,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     }
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the operands are in registers, the LDS tile is free again
     // accumulator value v of lane (lq, h): block j0 + 8 (v / 4) + 4 h + v % 4, query lq
-    if constexpr (KL > 0) {
+    if constexpr (KL > 0 && !WIDE) {
         float sc[2][2][16];  // [block group][query tile][value]; -inf: not a candidate
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
@@ -339,6 +342,106 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             }
         }
         continue;
+    } else if constexpr (KL > 0) {
+        // more than 64 blocks: sorted top lists per query tile while the scores go to LDS columns
+        float top[2][KL];
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+            for (int i = 0; i < KL; ++i) top[qt][i] = -INFINITY;
+        auto put = [&](float (&tl)[KL], float x) __attribute__((always_inline)) {
+            float prev = tl[0];
+            tl[0] = fmaxf(prev, x);
+#pragma unroll
+            for (int i = 1; i < KL; ++i) {
+                const float cur = tl[i];
+                tl[i] = __builtin_amdgcn_fmed3f(prev, cur, x);
+                prev = cur;
+            }
+        };
+        for (int j0 = 0; j0 <= own_max; j0 += 32) {
+            gate_f32x16 acc[2];
+            scores(j0, qf, acc);
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int j = j0 + 8 * (v / 4) + 4 * h + (v % 4);
+                    float x = acc[qt][v];
+                    if (j == own_q[qt] || j < n_first) x = INFINITY;  // always kept
+                    s_score[j * 64 + 32 * qt + lq] = x;
+                    put(top[qt], (j <= own_q[qt]) ? x : -INFINITY);
+                }
+        }
+        if (more) stage_q((tile + gridDim.x) * 64);  // lands under the picks
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            float other[KL];
+#pragma unroll
+            for (int i = 0; i < KL; ++i) other[i] = shfl_xor_f(top[qt][i], 32);
+#pragma unroll
+            for (int i = 0; i < KL; ++i) put(top[qt], other[i]);
+        }
+        // from here thread = query token t_tile + lane = query tile h, row lq
+        const long t = t_tile + lane;
+        const int own = h ? own_q[1] : own_q[0];
+        const int avail = own + 1;
+        const int take = (K < avail) ? K : avail;
+        float thr = h ? top[1][0] : top[0][0];
+#pragma unroll
+        for (int i = 1; i < KL; ++i) thr = (take > i) ? (h ? top[1][i] : top[0][i]) : thr;  // top[take - 1]
+        __syncthreads();  // the score columns are complete
+        uint64_t ge[4] = {0ull, 0ull, 0ull, 0ull}, gt[4] = {0ull, 0ull, 0ull, 0ull};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (64 * w > own_max) break;  // uniform
+            for (int jj = 0; jj < 64 && 64 * w + jj <= own_max; jj += 4) {
+                float v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = s_score[(64 * w + jj + i) * 64 + lane];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool cand = 64 * w + jj + i <= own;
+                    if (cand && v[i] >= thr) ge[w] |= 1ull << (jj + i);
+                    if (cand && v[i] > thr) gt[w] |= 1ull << (jj + i);
+                }
+            }
+        }
+        int n_ge = 0, n_gt = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            n_ge += __popcll(ge[w]);
+            n_gt += __popcll(gt[w]);
+        }
+        if (n_ge != take) {
+            // an exact tie at the threshold: everything above it, then the tied blocks in index order
+            int r = take - n_gt;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                uint64_t tied = ge[w] & ~gt[w];
+                ge[w] = gt[w];
+                while (r > 0 && tied) {
+                    ge[w] |= tied & (0 - tied);
+                    tied &= tied - 1;
+                    --r;
+                }
+            }
+        }
+        if (t < T) {
+            int32_t *dst = idx_out + ((long)unit * T + t) * K;
+            int n = 0;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                uint64_t word = ge[w];
+                while (word && n < K) {
+                    dst[n++] = 64 * w + (int32_t)__builtin_ctzll(word);
+                    word &= word - 1;
+                }
+            }
+            for (; n < K; ++n) dst[n] = -1;
+        }
+        __syncthreads();  // the score columns are rewritten by the next tile
+        continue;
     } else {
         for (int j0 = 0; j0 <= own_max; j0 += 32) {
             gate_f32x16 acc[2];
@@ -421,7 +524,7 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     // the gate kernel: one-wave workgroups, about eight per CU, each walking over the 64-token
     // tiles of one (batch, head)
     const bool in_registers = K <= 16 && Nb <= 64;  // its register picks need no score columns
-    const int kl = K <= 4 ? 4 : K <= 8 ? 8 : 16;
+    const int kl = K <= 4 ? 4 : K <= 8 ? 8 : K <= 16 ? 16 : 0;
     const size_t lds_mfma = in_registers ? 0 : lds_wave;
     const long n_tiles = (T + 63) / 64, units = (long)s->B * s->Hq;
     long per_unit = (2048 + units - 1) / units;
@@ -437,12 +540,17 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     if (s->dtype == RS_BF16) {
         if (s->D == 128) {
             moba_block_means_kernel<bf16, 128><<<g1p, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
-#define RS_GATE(DD)                                                                                                 \
-    do {                                                                                                            \
-        if (!in_registers) moba_gate_mfma_kernel<DD, 0><<<g3, 64, lds_mfma, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first); \
-        else if (kl == 4) moba_gate_mfma_kernel<DD, 4><<<g3, 64, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);  \
-        else if (kl == 8) moba_gate_mfma_kernel<DD, 8><<<g3, 64, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);  \
-        else moba_gate_mfma_kernel<DD, 16><<<g3, 64, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);            \
+#define RS_GATE1(DD, KLL, WW, LDS) moba_gate_mfma_kernel<DD, KLL, WW><<<g3, 64, LDS, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first)
+#define RS_GATE(DD)                                            \
+    do {                                                       \
+        if (kl == 0) RS_GATE1(DD, 0, true, lds_mfma);          \
+        else if (!in_registers) {                              \
+            if (kl == 4) RS_GATE1(DD, 4, true, lds_mfma);      \
+            else if (kl == 8) RS_GATE1(DD, 8, true, lds_mfma); \
+            else RS_GATE1(DD, 16, true, lds_mfma);             \
+        } else if (kl == 4) RS_GATE1(DD, 4, false, 0);         \
+        else if (kl == 8) RS_GATE1(DD, 8, false, 0);           \
+        else RS_GATE1(DD, 16, false, 0);                       \
     } while (0)
             RS_GATE(128);
         } else {
@@ -450,6 +558,7 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
             RS_GATE(64);
         }
 #undef RS_GATE
+#undef RS_GATE1
     } else {
         if (s->D == 128) RS_LAUNCH(float, 128);
         else RS_LAUNCH(float, 64);

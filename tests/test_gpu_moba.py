@@ -133,14 +133,18 @@ def test_moba_select_and_sparse_prefill(rs, monkeypatch, case):
     ws.async_status()
 
 
-@pytest.mark.parametrize("K,n_first", [(3, 0), (4, 1), (8, 0)])
-def test_moba_exact_ties_pick_lowest_blocks(rs, K, n_first):
+# (K, n_first, block): register picks (at most 64 blocks; lists of 4, 8, 16), score columns in LDS
+# with top lists (more than 64 blocks), and LDS sweeps (K above 16)
+@pytest.mark.parametrize("K,n_first,block", [(3, 0, 64), (4, 1, 64), (8, 0, 64), (16, 2, 64), (3, 0, 16), (8, 1, 16),
+                                             (13, 0, 16), (20, 0, 64), (24, 1, 16)])
+def test_moba_exact_ties_pick_lowest_blocks(rs, K, n_first, block):
     """A cache that repeats with the block length has identical block means, so every gate
     score of a query ties exactly: the routing must keep the query's own block, the first
     n_first blocks, and fill up with the lowest block indices (the oracle's tie rule)."""
     say("moba ties", K, n_first)
     w = synth.C4.scaled(B=1, Hq=2, Hkv=2, T=1024)
-    T, block = 1024, 64
+    T = 1024 if block == 64 else 1600  # 16 blocks, or 100 blocks of 16 tokens
+    w = w.scaled(T=T)
     Nb = T // block
     rng = np.random.default_rng(7)
     one = oracle.round_to_bf16(rng.standard_normal((w.B, w.Hkv, block, w.D)).astype(np.float32))
@@ -154,9 +158,10 @@ def test_moba_exact_ties_pick_lowest_blocks(rs, K, n_first):
     omeans = oracle.moba_block_means(kc, T, block)
     oidx = oracle.moba_select(q, omeans, T, block, K, n_first)
     gidx = to_np(idx)
-    for t in (0, 63, 64, 200, 511, 1023):
+    for t in (0, 63, 64, 200, 511, 1023, T - 1):
         own = t // block
-        want = sorted(set(list(range(min(K - 1, own))) + [own]))  # lowest blocks, then own
+        # always kept: own block and the first n_first; the rest ties: lowest indices first
+        want = sorted(set(list(range(min(K - 1, own))) + [own]))
         want = want + [-1] * (K - len(want))
         assert list(oidx[0, 0, t]) == want, (t, oidx[0, 0, t], want)  # the oracle follows the stated rule
     np.testing.assert_array_equal(gidx, oidx)
