@@ -124,7 +124,6 @@ static int env_int(const char *name, int dflt)
 }
 
 constexpr int kMaxAttSplits = 64;
-constexpr int kFusedGroupedMaxUnits = 64;  // grouped-query attention with at most this many units: two launches
 
 struct DecodeLayout {
     int Np, splits_score, splits_att_max;
@@ -433,10 +432,14 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     const int32_t *use_idx = idx;
     const uint32_t tag = next_tag();
     if (group && !listed && !fused) return RS_INVALID_ARG;  // the dense path has no selection to share
-    // one persistent launch, except under grouped-query attention with few units: there the two
-    // plain launches below measured faster (32 heads over 8 KV heads at 32K: 42 against 52 us at
-    // batch 1, 53 against 72 us at batch 2; from 96 units on, and without grouping, the one launch wins)
-    const int two_launch = env_int("RATSPARSE_FUSED_TWO_LAUNCH", (s->Hq > s->Hkv && units <= kFusedGroupedMaxUnits) ? 1 : 0);
+    // One persistent launch when the step is long enough to be bound by bandwidth: at least about
+    // 450 MB of page metadata and selected pages (some 90 us) over at least 512 pages per sequence.
+    // Shorter steps are bound by latency, and there the two plain launches below measured faster:
+    // 32 heads at 4096 tokens, batch 8, 8 of 64 pages 23 against 38 us; batch 64 117 against 130 us;
+    // 32 query over 8 KV heads at 32K, batch 1, 29 against 33 us.  Long ones the other way: batch 4
+    // at 64K (538 MB) 95 against 143 us, batch 32 at 8K 98 against 112 us.
+    const double step_bytes = ((double)s->B * s->Hkv * Np * 2 + (double)units * K * s->P * 2) * s->D * esize(s->dtype);
+    const int two_launch = env_int("RATSPARSE_FUSED_TWO_LAUNCH", (step_bytes >= 450e6 && Np >= 512) ? 0 : 1);
     if (fused && !group && !two_launch) {
         // one persistent launch: score -> select -> attend, handed over through tagged words
         FusedParams prm;
