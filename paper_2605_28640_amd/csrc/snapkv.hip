@@ -9,6 +9,7 @@
 // a lane owns one query row and gets its softmax max / sum cheaply; sweep 2 forms S = Q K^T
 // so that a lane owns one key column and its vote is an in-lane sum over the query rows.
 #include "common.h"
+#include "select.h"
 
 #include <type_traits>
 
@@ -17,7 +18,7 @@ namespace rs {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kSnapKeysPerWg = 2048;  // keys per workgroup
+constexpr int kSnapKeysPerWg = 2048;  // keys per workgroup, at most (fewer when that leaves the chip idle)
 constexpr int kSnapKT = 128;          // keys per step: four 32-key sub-tiles
 
 // K tiles of 128 keys are double-buffered in LDS and filled by direct global -> LDS loads
@@ -53,7 +54,7 @@ struct SnapStage {
 template <int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void snapkv_stats_kernel(
     const bf16 *__restrict__ q_win, const bf16 *__restrict__ k_cache, float *__restrict__ stats, int Hq, int Hkv, long T,
-    long Tcap, int W, int n_chunks, float scale)
+    long Tcap, int W, int n_chunks, float scale, int keys_per_wg)
 {
     constexpr int NC = D / 16;
     using Stage = SnapStage<D>;
@@ -69,8 +70,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int R = G * W;  // query rows of this KV head
     const long L = T - W;
     const bf16 *kb = k_cache + (long)bk * Tcap * D;
-    const long kc0 = (long)chunk * kSnapKeysPerWg;
-    const long kc1 = (kc0 + kSnapKeysPerWg < T) ? kc0 + kSnapKeysPerWg : T;
+    const long kc0 = (long)chunk * keys_per_wg;
+    const long kc1 = (kc0 + keys_per_wg < T) ? kc0 + keys_per_wg : T;
     const int n_steps = (int)((kc1 - kc0 + kSnapKT - 1) / kSnapKT);
     const int n_row_tiles = (R + 127) / 128;
     const Stage st;
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 template <int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void snapkv_votes_kernel(
     const bf16 *__restrict__ q_win, const bf16 *__restrict__ k_cache, const float *__restrict__ lse,
-    float *__restrict__ votes, int Hq, int Hkv, long T, long Tcap, int W, float scale)
+    float *__restrict__ votes, int Hq, int Hkv, long T, long Tcap, int W, float scale, int keys_per_wg)
 {
     constexpr int NC = D / 16;
     using Stage = SnapStage<D>;
@@ -210,8 +211,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int R = G * W;
     const long L = T - W;
     const bf16 *kb = k_cache + (long)bk * Tcap * D;
-    const long kc0 = (long)chunk * kSnapKeysPerWg;
-    const long kc1 = (kc0 + kSnapKeysPerWg < L) ? kc0 + kSnapKeysPerWg : L;  // prefix keys only
+    const long kc0 = (long)chunk * keys_per_wg;
+    const long kc1 = (kc0 + keys_per_wg < L) ? kc0 + keys_per_wg : L;  // prefix keys only
     const int n_steps = (int)((kc1 - kc0 + kSnapKT - 1) / kSnapKT);
     const int n_row_tiles = (R + 127) / 128;
     const Stage st;
@@ -574,10 +575,42 @@ __global__ void snapkv_gather_kernel(const ST *__restrict__ k_cache, const ST *_
     reinterpret_cast<uint4 *>(vc_out + (bk * Tcap_out + r) * D)[c] = *vs;
 }
 
+// Short prefixes (at most kSnapOneWgKeys positions per head): pooling, the top-K_keep selection
+// and the ascending output in one launch, one 1024-thread workgroup per (batch, KV head) with
+// the order-preserving keys of the pooled votes in LDS (the selection the decode kernels use:
+// keys above the K-th, then equal ones by lowest position).  At these sizes the seven launches
+// of the spread-out selection below cost more than the work in them.
+constexpr int kSnapOneWgKeys = 15360;  // 60 KiB of keys
+constexpr int kSnapOneWgThreads = 1024;
+
+__global__ __launch_bounds__(kSnapOneWgThreads) void snapkv_pool_select_kernel(const float *__restrict__ votes,
+                                                                               float *__restrict__ pooled_out,
+                                                                               int32_t *__restrict__ idx_out, int L,
+                                                                               int kernel, int K_keep)
+{
+    __shared__ SelectShared<kSnapOneWgThreads> sh;
+    extern __shared__ uint32_t s_keys[];  // L keys
+    const long bk = blockIdx.x;
+    const float *row = votes + bk * L;
+    const int half = kernel / 2;
+    for (int p = threadIdx.x; p < L; p += kSnapOneWgThreads) {
+        const int lo = (p - half < 0) ? 0 : p - half;
+        const int hi = (p + half > L - 1) ? L - 1 : p + half;
+        float m = row[lo];
+        for (int j = lo + 1; j <= hi; ++j) m = fmaxf(m, row[j]);
+        if (pooled_out) pooled_out[bk * L + p] = m;
+        s_keys[p] = float_to_key(m);
+    }
+    __syncthreads();
+    if (K_keep <= 0) return;
+    int32_t *dst = idx_out + bk * K_keep;
+    select_topk_lds<kSnapOneWgThreads>(s_keys, L, K_keep, sh, [dst](int pos, int p) { dst[pos] = p; });
+}
+
 static size_t al256s(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct SnapLayout {
-    int n_chunks, R;
+    int n_chunks, R, keys_per_wg;
     size_t off_stats, off_lse, off_votes, off_pooled, off_hist, off_cnt, total;
     int n_slices;
 };
@@ -587,7 +620,12 @@ static SnapLayout snap_layout(const rs_shape *s, long T, int W)
     SnapLayout L;
     const long BK = (long)s->B * s->Hkv;
     L.R = (s->Hq / s->Hkv) * W;
-    L.n_chunks = (int)((T + kSnapKeysPerWg - 1) / kSnapKeysPerWg);
+    // keys per workgroup of the two sweeps: 2048, or fewer (a multiple of the 128-key step, at
+    // least 256) when that many would leave fewer than about 512 workgroups
+    long kpw = (T * BK / 512 + kSnapKT - 1) / kSnapKT * kSnapKT;
+    kpw = kpw < 256 ? 256 : kpw > kSnapKeysPerWg ? kSnapKeysPerWg : kpw;
+    L.keys_per_wg = (int)kpw;
+    L.n_chunks = (int)((T + kpw - 1) / kpw);
     size_t o = RS_WS_CTRL_BYTES;
     L.off_stats = o;
     o += al256s((size_t)BK * L.n_chunks * L.R * 2 * 4);
@@ -622,26 +660,31 @@ int snapkv_dispatch(const rs_shape *s, const void *q_win, const void *k_cache, c
     const dim3 grid((unsigned)Ly.n_chunks, (unsigned)BK);
     const bf16 *qw = (const bf16 *)q_win, *kc = (const bf16 *)k_cache;
     if (s->D == 128)
-        snapkv_stats_kernel<128><<<grid, 256, 0, stream>>>(qw, kc, stats, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
+        snapkv_stats_kernel<128><<<grid, 256, 0, stream>>>(qw, kc, stats, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale, Ly.keys_per_wg);
     else
-        snapkv_stats_kernel<64><<<grid, 256, 0, stream>>>(qw, kc, stats, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale);
+        snapkv_stats_kernel<64><<<grid, 256, 0, stream>>>(qw, kc, stats, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale, Ly.keys_per_wg);
     const long rows_total = BK * Ly.R;
     snapkv_lse_kernel<<<(unsigned)((rows_total + 3) / 4), 256, 0, stream>>>(stats, lse, Ly.R, Ly.n_chunks, rows_total);
     // votes exist for prefix keys only: chunks that start past the prefix are not needed
-    const dim3 grid2((unsigned)((L + kSnapKeysPerWg - 1) / kSnapKeysPerWg), (unsigned)BK);
+    const dim3 grid2((unsigned)((L + Ly.keys_per_wg - 1) / Ly.keys_per_wg), (unsigned)BK);
     if (s->D == 128)
-        snapkv_votes_kernel<128><<<grid2, 256, 0, stream>>>(qw, kc, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, scale);
+        snapkv_votes_kernel<128><<<grid2, 256, 0, stream>>>(qw, kc, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, scale, Ly.keys_per_wg);
     else
-        snapkv_votes_kernel<64><<<grid2, 256, 0, stream>>>(qw, kc, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, scale);
+        snapkv_votes_kernel<64><<<grid2, 256, 0, stream>>>(qw, kc, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, scale, Ly.keys_per_wg);
     const long tot = BK * L;
-    uint32_t *sel_hist = (uint32_t *)(ws + Ly.off_hist), *sel_cnt = (uint32_t *)(ws + Ly.off_cnt);
-    snapkv_pool_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, stream>>>(votes, pooled, L, pool_kernel, tot, sel_hist, BK * 1024);
-    if (K_keep > 0) {
-        const dim3 gs((unsigned)Ly.n_slices, (unsigned)BK);
-        for (int pass = 0; pass < 4; ++pass)
-            snapkv_sel_hist_kernel<<<gs, kSelThreads, 0, stream>>>(pooled, sel_hist, L, K_keep, pass);
-        snapkv_sel_count_kernel<<<gs, kSelThreads, 0, stream>>>(pooled, sel_hist, sel_cnt, L, K_keep);
-        snapkv_sel_emit_kernel<<<gs, kSelThreads, 0, stream>>>(pooled, sel_hist, sel_cnt, idx_out, L, K_keep);
+    if (L <= kSnapOneWgKeys) {
+        snapkv_pool_select_kernel<<<(unsigned)BK, kSnapOneWgThreads, (size_t)L * 4, stream>>>(
+            votes, votes_out, idx_out, (int)L, pool_kernel, K_keep);
+    } else {
+        uint32_t *sel_hist = (uint32_t *)(ws + Ly.off_hist), *sel_cnt = (uint32_t *)(ws + Ly.off_cnt);
+        snapkv_pool_kernel<<<(unsigned)((tot + 255) / 256), 256, 0, stream>>>(votes, pooled, L, pool_kernel, tot, sel_hist, BK * 1024);
+        if (K_keep > 0) {
+            const dim3 gs((unsigned)Ly.n_slices, (unsigned)BK);
+            for (int pass = 0; pass < 4; ++pass)
+                snapkv_sel_hist_kernel<<<gs, kSelThreads, 0, stream>>>(pooled, sel_hist, L, K_keep, pass);
+            snapkv_sel_count_kernel<<<gs, kSelThreads, 0, stream>>>(pooled, sel_hist, sel_cnt, L, K_keep);
+            snapkv_sel_emit_kernel<<<gs, kSelThreads, 0, stream>>>(pooled, sel_hist, sel_cnt, idx_out, L, K_keep);
+        }
     }
     const int cpr = s->D * 2 / 16;
     const long total = BK * (long)(K_keep + W) * cpr;
