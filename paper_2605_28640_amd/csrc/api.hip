@@ -135,7 +135,8 @@ static DecodeLayout decode_layout(const rs_shape *s, long T_valid, int K)
     DecodeLayout L;
     const long units = (long)s->B * s->Hq;
     L.Np = (int)((T_valid + s->P - 1) / s->P);
-    L.splits_score = pick_splits(units, L.Np, 64, env_int("RATSPARSE_SCORE_WGS", 512));
+    // 512-thread workgroups, about one per CU (128 pages per workgroup step)
+    L.splits_score = pick_splits(units, L.Np, 128, env_int("RATSPARSE_SCORE_WGS", 256));
     const long dense_tiles = (T_valid + 15) / 16;
     L.splits_att_max = pick_splits(units, dense_tiles, 8, env_int("RATSPARSE_ATTEND_WGS", 512));
     if (L.splits_att_max < kMaxAttSplits) L.splits_att_max = kMaxAttSplits;

@@ -120,7 +120,7 @@ void page_meta_dispatch(int dtype, int D, const void *k_cache, void *meta, int B
     }
 }
 
-constexpr int kSelThreads = 256;
+constexpr int kSelThreads = 512;
 
 // ------------------------------------------------------------------------------------
 // page scores; the last workgroup of a unit to arrive runs the selection.  GQ = 1: a unit
