@@ -163,8 +163,12 @@ typedef float gate_f32x16 __attribute__((ext_vector_type(16)));
 // lists kept in registers while the scores are formed; with at most 64 blocks (WIDE = false)
 // the scores stay in registers too, with more (WIDE) they go to LDS columns and are read back
 // once against the threshold.  KL = 0: picks by K sweeps over the LDS columns (K up to 32).
-template <int D, int KL, bool WIDE>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void moba_gate_mfma_kernel(const bf16 *__restrict__ q, const uint16_t *__restrict__ split,
+// NWV > 1 (register picks only): the waves of a workgroup share the unit's block-mean operands
+// through LDS (at most 64 blocks: 48 KB at D = 128), fetched once per workgroup instead of once per
+// 64-token tile from L2 -- with operands two chunks ahead, a wave otherwise waits an L2 round
+// trip every other chunk.
+template <int D, int KL, bool WIDE, int NWV>
+__global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(NWV == 1 ? 2 : 1, 2))) void moba_gate_mfma_kernel(const bf16 *__restrict__ q, const uint16_t *__restrict__ split,
                                                            int32_t *__restrict__ idx_out, int Hq, int Hkv, long T,
                                                            int block, int Nb, int K, int n_first)
 {
@@ -177,13 +181,26 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     // row in 16-byte pieces would touch 64 cache lines per instruction), issued one tile ahead --
     // once the current tile's operands sit in registers and its matrix work is done -- so that
     // they land under the picks of the current tile.
-    __shared__ __attribute__((aligned(1024))) uint16_t sQ[64 * D];
+    static_assert(NWV == 1 || (KL > 0 && !WIDE), "shared operands: register picks only");
+    __shared__ __attribute__((aligned(1024))) uint16_t sQ_all[NWV * 64 * D];
+    __shared__ __attribute__((aligned(1024))) uint16_t sM[NWV == 1 ? 8 : 2 * 3 * 32 * D];  // [group][term][chunk][lane][8]
     extern __shared__ float s_score[];  // [Nb rounded up to 32][64], only for the LDS picks
     const int lane = threadIdx.x & 63, lq = lane & 31, h = lane >> 5;
+    const int wave = (NWV == 1) ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint16_t *sQ = sQ_all + wave * 64 * D;
     const int unit = blockIdx.y;  // b * Hq + h
     const int b = unit / Hq, hq = unit % Hq, kvh = hq / (Hq / Hkv);
     const long n_tiles = (T + 63) / 64;
-    if ((long)blockIdx.x >= n_tiles) return;
+    const long tile0 = (long)blockIdx.x * NWV + wave, tile_step = (long)gridDim.x * NWV;
+    if constexpr (NWV > 1) {
+        // the unit's operands into LDS: 1 KB per direct load, the waves take turns
+        const LdsSource msrc = lds_source(split + (long)(b * Hkv + kvh) * ((Nb + 31) / 32) * 3 * 32 * D);
+        const int n_kb = ((Nb + 31) / 32) * 3 * 32 * D * 2 / 1024;
+        for (int i = wave; i < n_kb; i += NWV) load16_to_lds(msrc, (uint32_t)(i * 1024 + lane * 16), sM + i * 512);
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        __syncthreads();
+    }
+    if (tile0 >= n_tiles) return;
 
     const int srow = lane / CR;
     auto stage_q = [&](long t_tile) __attribute__((always_inline)) {
@@ -196,7 +213,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             load16_to_lds(src, (uint32_t)(r * D + (((lane % CR) ^ chunk_swizzle<D>(row)) * 8)) * 2u, sQ + i * RW * D);
         }
     };
-    stage_q((long)blockIdx.x * 64);
+    stage_q(tile0 * 64);
 
     const uint16_t *sbase = split + (long)(b * Hkv + kvh) * ((Nb + 31) / 32) * 3 * 32 * D;  // wave-uniform
     const LdsSource means_src = lds_source(sbase);  // operand loads: descriptor + scalar offset + 16 bytes per lane
@@ -211,8 +228,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         gate_bf16x8 m[3][3];
         auto fetch = [&](int c) __attribute__((always_inline)) {
 #pragma unroll
-            for (int term = 0; term < 3; ++term)
-                m[c % 3][term] = __builtin_bit_cast(gate_bf16x8, __builtin_amdgcn_raw_buffer_load_b128(means_src, lane * 16, frag + (term * NC + c) * 1024, 0));
+            for (int term = 0; term < 3; ++term) {
+                if constexpr (NWV > 1)
+                    m[c % 3][term] = *reinterpret_cast<const gate_bf16x8 *>(sM + (frag + (term * NC + c) * 1024) / 2 + lane * 8);
+                else
+                    m[c % 3][term] = __builtin_bit_cast(gate_bf16x8, __builtin_amdgcn_raw_buffer_load_b128(means_src, lane * 16, frag + (term * NC + c) * 1024, 0));
+            }
         };
         fetch(0);
         fetch(1);
@@ -228,11 +249,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             __builtin_amdgcn_sched_barrier(0);  // keep the fetch distance: no sinking of the loads to their uses
         }
     };
-    for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    for (long tile = tile0; tile < n_tiles; tile += tile_step) {
     const long t_tile = tile * 64;
     const long t_last = (t_tile + 63 < T) ? t_tile + 63 : T - 1;
     const int own_max = (int)(t_last / block);  // uniform over the wave
-    const bool more = tile + gridDim.x < n_tiles;
+    const bool more = tile + tile_step < n_tiles;
     // B operands: this lane's two query rows (tokens t_tile + lq and t_tile + 32 + lq, clamped)
     gate_bf16x8 qf[2][NC];
     int own_q[2];
@@ -272,7 +293,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                     for (int v = 0; v < 16; ++v) sc[g][qt][v] = -INFINITY;
             }
         }
-        if (more) stage_q((tile + gridDim.x) * 64);  // lands under the picks
+        if (more) stage_q((tile + tile_step) * 64);  // lands under the picks
         // half h writes the picks of query tile h (token t_tile + 32 h + lq) as a 64-bit mask of blocks
         uint64_t picks = 0;
 #pragma unroll
@@ -373,7 +394,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                     put(top[qt], (j <= own_q[qt]) ? x : -INFINITY);
                 }
         }
-        if (more) stage_q((tile + gridDim.x) * 64);  // lands under the picks
+        if (more) stage_q((tile + tile_step) * 64);  // lands under the picks
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
             float other[KL];
@@ -457,7 +478,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 }
         }
     }
-    if (more) stage_q((tile + gridDim.x) * 64);  // lands under the picks
+    if (more) stage_q((tile + tile_step) * 64);  // lands under the picks
     __syncthreads();
     // the picks: thread = query token, candidates 0 .. own.  The sweeps run to the wave-uniform
     // bound own_max in steps of four (rows up to the next multiple of 32 exist in LDS), so that
@@ -531,6 +552,18 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     if (const char *e = getenv("RATSPARSE_GATE_WAVES")) per_unit = (atol(e) + units - 1) / units;
     if (per_unit < 1) per_unit = 1;
     const dim3 g3((unsigned)(n_tiles < per_unit ? n_tiles : per_unit), (unsigned)units);
+    // six-wave workgroups with the operands in LDS (48 KB + 6 x 16 KB of query rows): one per CU
+    long wg_per_unit = (256 + units - 1) / units;
+    if (const char *e = getenv("RATSPARSE_GATE_WGS")) wg_per_unit = (atol(e) + units - 1) / units;
+    if (wg_per_unit < 1) wg_per_unit = 1;
+    const char *enw = getenv("RATSPARSE_GATE_NWV");
+    const int nwv = (enw && atoi(enw) == 4) ? 4 : 6;
+    if (wg_per_unit > (n_tiles + nwv - 1) / nwv) wg_per_unit = (n_tiles + nwv - 1) / nwv;
+    const dim3 g4((unsigned)wg_per_unit, (unsigned)units);
+    const char *eso = getenv("RATSPARSE_GATE_SHARED");
+    // worth its set-up from about 8192 tiles on (C4 0.148 -> 0.138 ms; 8 x 32 heads x 4096 tokens, blocks of 64,
+    // top-8: 0.184 -> 0.150 ms; 32 heads x 4096 tokens: 0.026 against 0.031 ms the other way)
+    const bool shared_ops = in_registers && (eso ? atoi(eso) != 0 : units * n_tiles >= 8192);
 #define RS_LAUNCH(ST, DD)                                                                                          \
     do {                                                                                                           \
         moba_block_means_kernel<ST, DD><<<g1, 256, 0, stream>>>((const ST *)k_cache, means_out, nullptr, s->Tcap, T, block, Nb); \
@@ -540,7 +573,12 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     if (s->dtype == RS_BF16) {
         if (s->D == 128) {
             moba_block_means_kernel<bf16, 128><<<g1p, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
-#define RS_GATE1(DD, KLL, WW, LDS) moba_gate_mfma_kernel<DD, KLL, WW><<<g3, 64, LDS, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first)
+#define RS_GATE1(DD, KLL, WW, LDS) moba_gate_mfma_kernel<DD, KLL, WW, 1><<<g3, 64, LDS, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first)
+#define RS_GATE4(DD, KLL)                                                                                                                   \
+    do {                                                                                                                                    \
+        if (nwv == 6) moba_gate_mfma_kernel<DD, KLL, false, 6><<<g4, 384, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first); \
+        else moba_gate_mfma_kernel<DD, KLL, false, 4><<<g4, 256, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);        \
+    } while (0)
 #define RS_GATE(DD)                                            \
     do {                                                       \
         if (kl == 0) RS_GATE1(DD, 0, true, lds_mfma);          \
@@ -548,6 +586,10 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
             if (kl == 4) RS_GATE1(DD, 4, true, lds_mfma);      \
             else if (kl == 8) RS_GATE1(DD, 8, true, lds_mfma); \
             else RS_GATE1(DD, 16, true, lds_mfma);             \
+        } else if (shared_ops) {                               \
+            if (kl == 4) RS_GATE4(DD, 4);                      \
+            else if (kl == 8) RS_GATE4(DD, 8);                 \
+            else RS_GATE4(DD, 16);                             \
         } else if (kl == 4) RS_GATE1(DD, 4, false, 0);         \
         else if (kl == 8) RS_GATE1(DD, 8, false, 0);           \
         else RS_GATE1(DD, 16, false, 0);                       \
@@ -559,6 +601,7 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
         }
 #undef RS_GATE
 #undef RS_GATE1
+#undef RS_GATE4
     } else {
         if (s->D == 128) RS_LAUNCH(float, 128);
         else RS_LAUNCH(float, 64);

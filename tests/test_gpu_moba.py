@@ -96,6 +96,14 @@ def test_moba_select_and_sparse_prefill(rs, monkeypatch, case):
                 assert ok, (b, h, t, why, row)
                 same += np.array_equal(row, oidx[b, h, t])
     say("  rows with identical block lists:", same, "of", w.B * w.Hq * T)
+    # the gate's other form (block-mean operands shared through LDS by six-wave workgroups, or
+    # fetched by each one-wave workgroup; the library picks by size): the same routing bit for bit
+    for form in ("0", "1"):
+        monkeypatch.setenv("RATSPARSE_GATE_SHARED", form)
+        idx2 = torch.full_like(idx, -9)
+        rs.moba_select_prefill(s, tq, tkc, T, block, K, n_first, means, idx2, ws)
+        assert torch.equal(idx2, idx), form
+    monkeypatch.delenv("RATSPARSE_GATE_SHARED")
 
     # block-sparse attention over the GPU's own routing
     out = torch.zeros(w.B, w.Hq, T, w.D, dtype=torch.bfloat16, device="cuda")
