@@ -349,7 +349,7 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
     // few (batch, head) pairs and a long run: 32-channel slabs, so that the chunk chains are
     // shorter and there are more of them
     const char *es = std::getenv("RATSPARSE_SCAN_SLAB");
-    const bool slab = es ? std::atoi(es) != 0 : (BH <= 16 && T_new >= 16384);
+    const bool slab = es ? std::atoi(es) != 0 : (BH <= 16 && T_new >= 2048);
 #define RS_SCAN(ST, DD, DSS) launch_scan<ST, DD, DSS>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream)
     if (dtype == RS_BF16) {
         if (D == 128) slab ? RS_SCAN(bf16, 128, 32) : RS_SCAN(bf16, 128, 128);
