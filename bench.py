@@ -352,6 +352,52 @@ def main():
                                         "GB/s": round(w5.B * w5.Hkv * w5.T * w5.D * 12 / scan5_ms / 1e6, 1)}
         del kc5, vc5, kco, vco, ws5
         torch.cuda.empty_cache()
+        # The paper's own sparse settings (App. A.1; Tables 3-4: 4096 tokens; Quest pages of 64 with
+        # top-8, MoBA blocks of 64 with top-16, SnapKV window 64 keeping 512) at batch 8, 32 heads,
+        # on random tensors of that shape: timings only.
+        gp = torch.Generator(device=dev).manual_seed(4096)
+        Bp, Hp, Tp, Dp = 8, 32, 4096, 128
+        sp = rs.make_shape(Bp, Hp, Hp, Dp, Tp + 64, 64, dt)
+        kcp = (torch.randn(Bp, Hp, Tp + 64, Dp, device=dev, generator=gp) * 0.5).to(dt)
+        vcp = torch.randn(Bp, Hp, Tp + 64, Dp, device=dev, generator=gp).to(dt)
+        qp = torch.randn(Bp, Hp, Tp, Dp, device=dev, generator=gp).to(dt)
+        scp = 1.0 / math.sqrt(Dp)
+        paper = {"shape": "B=8, 32 heads, T=4096, D=128, bf16"}
+        metap = torch.zeros(Bp, Hp, (Tp + 64) // 64, 2, Dp, dtype=dt, device=dev)
+        rs.quest_page_meta(sp, kcp, metap, 0, Tp)
+        outp = torch.zeros(Bp, Hp, Dp, dtype=dt, device=dev)
+        wsp = rs.Workspace(max(rs.sparse_attn_decode_workspace_bytes(sp, Tp, 8),
+                               rs.moba_select_prefill_workspace_bytes(sp, Tp, 64),
+                               rs.sparse_attn_prefill_workspace_bytes(sp, Tp, 64, 16),
+                               rs.snapkv_compress_workspace_bytes(sp, Tp, 64)))
+        q1 = qp[:, :, -1].contiguous()
+        paper["quest_P64_top8_decode_us"] = round(1e3 * timed(
+            lambda: rs.sparse_attn_decode(sp, q1, kcp, vcp, Tp, scp, None, 8, metap, 1, 1, outp, None, None, wsp),
+            reps=50, warm=5), 2)
+        paper["dense_decode_us"] = round(1e3 * timed(
+            lambda: rs.sparse_attn_decode(sp, q1, kcp, vcp, Tp, scp, None, 0, None, 0, 0, outp, None, None, wsp),
+            reps=50, warm=5), 2)
+        meansp = torch.zeros(Bp, Hp, Tp // 64, Dp, device=dev)
+        idxp = torch.zeros(Bp, Hp, Tp, 16, dtype=torch.int32, device=dev)
+        outpp = torch.zeros(Bp, Hp, Tp, Dp, dtype=dt, device=dev)
+        paper["moba_B64_top16_select_ms"] = round(timed(
+            lambda: rs.moba_select_prefill(sp, qp, kcp, Tp, 64, 16, 0, meansp, idxp, wsp)), 4)
+        paper["moba_B64_top16_attention_ms"] = round(timed(
+            lambda: rs.sparse_attn_prefill(sp, qp, kcp, vcp, Tp, 64, scp, idxp, 16, outpp, None, wsp)), 4)
+        paper["dense_causal_attention_ms"] = round(timed(
+            lambda: rs.sparse_attn_prefill(sp, qp, kcp, vcp, Tp, 64, scp, None, 0, outpp, None, wsp)), 4)
+        keepp = 512
+        kcop = torch.zeros(Bp, Hp, keepp + 64 + 64, Dp, dtype=dt, device=dev)
+        vcop = torch.zeros_like(kcop)
+        idxs = torch.zeros(Bp, Hp, keepp, dtype=torch.int32, device=dev)
+        qwp = qp[:, :, -64:].contiguous()
+        paper["snapkv_W64_keep512_us"] = round(1e3 * timed(
+            lambda: rs.snapkv_compress(sp, qwp, kcp, vcp, Tp, 64, keepp, 7, scp, kcop, vcop, keepp + 128, idxs, None,
+                                       wsp), reps=10), 2)
+        wsp.async_status()
+        extra["paper_settings_T4096"] = paper
+        del kcp, vcp, qp, outpp, idxp, kcop, vcop, wsp
+        torch.cuda.empty_cache()
         log("extras done")
 
     if args.calibrate:
