@@ -92,7 +92,8 @@ static int check_shape(const rs_shape *s, bool need_page)
 
 static int launch_status() { return hipGetLastError() == hipSuccess ? RS_OK : RS_LAUNCH_FAILED; }
 
-// work split heuristics: enough workgroups to cover 256 CUs several times over
+// work split of the two-launch kernels: `target_wgs` workgroups in all (about one 512-thread
+// workgroup per CU), never less than `min_items_per_split` items in a split
 static int pick_splits(long units, long items, long min_items_per_split, long target_wgs)
 {
     long s = (target_wgs + units - 1) / units;

@@ -148,13 +148,14 @@ __global__ __launch_bounds__(64) void moba_gate_topk_kernel(const ST *__restrict
 // kernel) and the three products accumulate in float32, so the scores keep float32 accuracy
 // (the top-K needs it: a block mean rounded to bfloat16 would move scores by 2^-9).  A lane
 // of the accumulator holds 16 blocks of ONE query.
-// Picks, K <= 4 and at most 64 candidate blocks: the scores stay in registers.  Each half-lane
-// keeps the four largest of its values (three v_med3 and a v_max per value), the two halves
-// of a query merge their lists, the take-th largest is the threshold, and the picked set is
-// the bit mask of scores >= threshold; if that mask does not hold exactly `take` blocks (an
-// exact tie at the threshold) the blocks above the threshold are taken and the tied ones fill
-// up in index order.  This path uses no LDS.  For larger K / more blocks the scores go to a
-// per-thread LDS column as in the scalar kernel and the K picks are K sweeps over it.
+// Picks, K <= 16: each half-lane keeps a sorted list of the KL = 4, 8 or 16 largest of its
+// values (a v_max and KL - 1 v_med3 per value), the two halves of a query merge their lists,
+// the take-th largest is the threshold, and the picked set is the bit mask of scores >=
+// threshold; if that mask does not hold exactly `take` blocks (an exact tie at the threshold)
+// the blocks above the threshold are taken and the tied ones fill up in index order.  With at
+// most 64 candidate blocks the scores themselves stay in registers and no LDS is used; with
+// more they go to a per-thread LDS column and are read back once against the threshold.
+// K > 16: the scores go to the LDS column as in the scalar kernel and the picks are K sweeps.
 // ------------------------------------------------------------------------------------
 typedef __bf16 gate_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float gate_f32x16 __attribute__((ext_vector_type(16)));
