@@ -19,6 +19,9 @@ void page_meta_dispatch(int dtype, int D, const void *k_cache, void *meta, int B
 void step_at_state_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
                             float *state_v, void *k_cache, void *v_cache, void *meta, int P, int BH, long Tcap,
                             const uint32_t *pos_state, long T_max, hipStream_t stream);
+void unit_decode_dispatch(int dtype, int D, const void *q, const void *meta, const void *k_cache, const void *v_cache,
+                          void *out, float *lse_out, int32_t *idx_out, int B, int Hq, int Hkv, long Tcap, int P,
+                          long T_valid, int Np, int K, int n_first, int n_local, float scale, hipStream_t stream);
 int score_select_dispatch(int dtype, int D, int GQ, const void *q, const void *meta, uint64_t *scores,
                           float *scores_out, int32_t *idx_out, int B, int Hq, int Hkv, long Np_cap, int Np, int K,
                           int n_first, int n_local, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag,
@@ -442,6 +445,21 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     // at 64K (538 MB) 95 against 143 us, batch 32 at 8K 98 against 112 us.
     const double step_bytes = ((double)s->B * s->Hkv * Np * 2 + (double)units * K * s->P * 2) * s->D * esize(s->dtype);
     const int two_launch = env_int("RATSPARSE_FUSED_TWO_LAUNCH", (step_bytes >= 450e6 && Np >= 512) ? 0 : 1);
+    // Short contexts (the paper's 4096 tokens): the whole step of a (batch, query head) inside one
+    // workgroup, one launch, nothing handed between workgroups.  Taken when a unit's metadata and
+    // picked pages are small (at most 1.5 MB, and at most 512 KB unless there are 128 units or
+    // more) and the step is not one of the long ones above.  32 heads at 4096 tokens, 64-token
+    // pages, top-8 (one workgroup per unit / two launches / persistent launch, us): batch 1
+    // 13 / 16 / 21, batch 8 20 / 24 / 39, batch 64 112 / 123 / 130; 8K and 16K at batch 8:
+    // 28 / 32 / 44 and 47 / 52 / 59; the other way at 32K, batch 2: 51 / 34 / 47.
+    const double unit_bytes = ((double)Np * 2 + (double)K * s->P * 2) * s->D * esize(s->dtype);
+    const bool unit_rule = two_launch && unit_bytes <= 1.5e6 && (units >= 128 || unit_bytes <= 512e3);
+    const int one_wg = env_int("RATSPARSE_FUSED_ONE_WG", unit_rule ? 1 : 0);
+    if (fused && !group && one_wg && Np <= 4096 && K <= 1024) {
+        unit_decode_dispatch(s->dtype, s->D, q, meta, k_cache, v_cache, out, lse_out, idx_out, s->B, s->Hq, s->Hkv,
+                             s->Tcap, s->P, T_valid, (int)Np, K, n_first, n_local, scale, (hipStream_t)stream);
+        return launch_status();
+    }
     if (fused && !group && !two_launch) {
         // one persistent launch: score -> select -> attend, handed over through tagged words
         FusedParams prm;

@@ -424,6 +424,214 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Short contexts (the paper's 4096 tokens): select-then-attend of one (batch, query head)
+// inside one 512-thread workgroup -- page scores into LDS keys, the top-K selection, then
+// attention over the picked pages with the waves splitting the tiles -- so nothing is handed
+// between workgroups and the step is one launch.  Same score arithmetic, forced pages and tie
+// rule as quest_score_select_kernel; the attention loop is decode_attend_kernel's.
+// Dynamic LDS: Np keys, then K picked pages.
+// ------------------------------------------------------------------------------------
+constexpr int kUnitThreads = 512;
+
+template <typename ST, int D>
+__global__ __launch_bounds__(kUnitThreads) void quest_unit_decode_kernel(
+    const ST *__restrict__ q, const ST *__restrict__ meta, const ST *__restrict__ k_cache,
+    const ST *__restrict__ v_cache, ST *__restrict__ out, float *__restrict__ lse_out, int32_t *__restrict__ idx_out,
+    int Hq, int Hkv, long Tcap, int P, long T_valid, int Np, int K, int n_first, int n_local, float scale)
+{
+    constexpr int LPR = D / 8;
+    constexpr int RPW = 64 / LPR;
+    constexpr int UNR = 4;
+    constexpr int NW = kUnitThreads / 64;
+    constexpr int TR = 16;
+    constexpr int RPL = TR / RPW;
+    constexpr int TPI = 2;
+    using R = Row8<ST>;
+    __shared__ SelectShared<kUnitThreads> sh;
+    __shared__ float s_m[NW], s_l[NW];
+    __shared__ float s_o[NW][D];
+    extern __shared__ uint32_t s_dyn[];
+    uint32_t *s_keys = s_dyn;
+    int *s_sel = reinterpret_cast<int *>(s_dyn + Np);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int rg = lane / LPR;
+    const int c0 = (lane % LPR) * 8;
+    const int unit = blockIdx.x;
+    const int b = unit / Hq, h = unit % Hq;
+    const int kvh = h / (Hq / Hkv);
+    const long Np_cap = Tcap / P;
+    const ST *mbase = meta + ((long)(b * Hkv + kvh) * Np_cap) * 2 * D;
+    const ST *kb = k_cache + (long)(b * Hkv + kvh) * Tcap * D;
+    const ST *vb = v_cache + (long)(b * Hkv + kvh) * Tcap * D;
+
+    float qv[8];
+    R::load(q + (long)unit * D + c0, qv);
+
+    // page scores (Eq. 3 with the min/max bound) -> order-preserving keys
+    constexpr int PPI = UNR * RPW * NW;
+    for (int base = wave * (UNR * RPW) + rg; base < Np; base += PPI) {
+        typename R::raw_t mn[UNR], mx[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int p = base + u * RPW;
+            if (p < Np) {
+                mn[u] = R::load_raw(mbase + ((long)p * 2) * D + c0);
+                mx[u] = R::load_raw(mbase + ((long)p * 2 + 1) * D + c0);
+            } else {
+                mn[u] = R::zero_raw();
+                mx[u] = R::zero_raw();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int p = base + u * RPW;
+            float lo[8], hi[8];
+            R::unpack(mn[u], lo);
+            R::unpack(mx[u], hi);
+            float s = 0.f;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) s += fmaxf(qv[c] * lo[c], qv[c] * hi[c]);
+            s = group_sum<LPR>(s);
+            if (p < Np && (lane % LPR) == 0) s_keys[p] = (p < n_first || p >= Np - n_local) ? 0xffffffffu : float_to_key(s);
+        }
+    }
+    __syncthreads();
+    int32_t *dst = idx_out ? idx_out + (long)unit * K : nullptr;
+    select_topk_lds<kUnitThreads>(s_keys, Np, K, sh, [s_sel, dst](int pos, int p) {
+        s_sel[pos] = p;
+        if (dst) dst[pos] = p;
+    });
+    __syncthreads();
+
+    // attention over the picked pages (Eq. 4): 16-row tiles, the waves take them in turn
+#pragma unroll
+    for (int c = 0; c < 8; ++c) qv[c] *= scale;
+    const int tiles_per_page = P / TR;
+    const int n_tiles = K * tiles_per_page;
+    float m = -INFINITY, l = 0.f;
+    float o[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[c] = 0.f;
+    for (int t = wave * TPI; t < n_tiles; t += NW * TPI) {
+        long row0[TPI];
+        typename R::raw_t kr[TPI][RPL], vr[TPI][RPL];
+#pragma unroll
+        for (int u = 0; u < TPI; ++u) {
+            const int tt = t + u;
+            row0[u] = T_valid;  // nothing to do
+            if (tt < n_tiles) row0[u] = (long)s_sel[tt / tiles_per_page] * P + (tt % tiles_per_page) * TR;
+        }
+#pragma unroll
+        for (int u = 0; u < TPI; ++u)
+#pragma unroll
+            for (int i = 0; i < RPL; ++i) {
+                const long row = row0[u] + i * RPW + rg;
+                if (row < T_valid) {
+                    kr[u][i] = R::load_raw(kb + row * D + c0);
+                    vr[u][i] = R::load_raw(vb + row * D + c0);
+                } else {
+                    kr[u][i] = R::zero_raw();
+                    vr[u][i] = R::zero_raw();
+                }
+            }
+#pragma unroll
+        for (int u = 0; u < TPI; ++u) {
+            float s[RPL];
+            float mt = m;
+#pragma unroll
+            for (int i = 0; i < RPL; ++i) {
+                float x[8];
+                R::unpack(kr[u][i], x);
+                float d = 0.f;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) d = fmaf(qv[c], x[c], d);
+                d = group_sum<LPR>(d);
+                const long row = row0[u] + i * RPW + rg;
+                s[i] = (row < T_valid) ? d : -INFINITY;
+                mt = fmaxf(mt, s[i]);
+            }
+            if (mt != -INFINITY) {
+                const float corr = __expf(m - mt);
+                l *= corr;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) o[c] *= corr;
+#pragma unroll
+                for (int i = 0; i < RPL; ++i) {
+                    const float pr = __expf(s[i] - mt);
+                    l += pr;
+                    float x[8];
+                    R::unpack(vr[u][i], x);
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) o[c] = fmaf(pr, x[c], o[c]);
+                }
+                m = mt;
+            }
+        }
+    }
+    // merge the row groups of the wave, then the waves
+#pragma unroll
+    for (int mask = LPR; mask < 64; mask <<= 1) {
+        const float m2 = shfl_xor_f(m, mask);
+        const float l2 = shfl_xor_f(l, mask);
+        const float mn = fmaxf(m, m2);
+        const float a1 = (m == -INFINITY) ? 0.f : __expf(m - mn);
+        const float a2 = (m2 == -INFINITY) ? 0.f : __expf(m2 - mn);
+        l = l * a1 + l2 * a2;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const float o2 = shfl_xor_f(o[c], mask);
+            o[c] = o[c] * a1 + o2 * a2;
+        }
+        m = mn;
+    }
+    if (rg == 0) {
+        if ((lane % LPR) == 0) {
+            s_m[wave] = m;
+            s_l[wave] = l;
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) s_o[wave][c0 + c] = o[c];
+    }
+    __syncthreads();
+    if (tid < D) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, s_m[w]);
+        float L = 0.f, O = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float a = (s_m[w] == -INFINITY) ? 0.f : __expf(s_m[w] - M);
+            L += s_l[w] * a;
+            O += s_o[w][tid] * a;
+        }
+        const float inv = (L > 0.f) ? 1.f / L : 0.f;
+        from_f32(out[(long)unit * D + tid], O * inv);
+        if (tid == 0 && lse_out) lse_out[unit] = (L > 0.f) ? M + __logf(L) : -INFINITY;
+    }
+}
+
+void unit_decode_dispatch(int dtype, int D, const void *q, const void *meta, const void *k_cache, const void *v_cache,
+                          void *out, float *lse_out, int32_t *idx_out, int B, int Hq, int Hkv, long Tcap, int P,
+                          long T_valid, int Np, int K, int n_first, int n_local, float scale, hipStream_t stream)
+{
+    const size_t lds = (size_t)(Np + K) * 4;
+#define RS_LAUNCH(ST, DD)                                                                                        \
+    quest_unit_decode_kernel<ST, DD><<<(unsigned)(B * Hq), kUnitThreads, lds, stream>>>(                         \
+        (const ST *)q, (const ST *)meta, (const ST *)k_cache, (const ST *)v_cache, (ST *)out, lse_out, idx_out, \
+        Hq, Hkv, Tcap, P, T_valid, Np, K, n_first, n_local, scale)
+    if (dtype == RS_BF16) {
+        if (D == 128) RS_LAUNCH(bf16, 128);
+        else RS_LAUNCH(bf16, 64);
+    } else {
+        if (D == 128) RS_LAUNCH(float, 128);
+        else RS_LAUNCH(float, 64);
+    }
+#undef RS_LAUNCH
+}
+
 void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache, const void *v_cache,
                             const int32_t *idx, void *out, float *lse_out, uint64_t *partial, int B, int Hq,
                             int Hkv, long Tcap, int P, long T_valid, int K, float scale, int splits,

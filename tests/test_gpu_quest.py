@@ -126,20 +126,29 @@ def test_meta_select_attend(rs, monkeypatch, case):
     assert ok, worst
     np.testing.assert_allclose(to_np(lse), olse, rtol=1e-4, atol=1e-4)
 
-    # select-then-attend in one call, emitting its selection: as one persistent launch and as
-    # two launches (the library picks by shape; the knob forces either)
+    # select-then-attend in one call, emitting its selection: as one persistent launch, as two
+    # launches, and with the whole step of a (batch, head) inside one workgroup (the library
+    # picks by shape; the knobs force each)
     oout2, _ = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, gidx)
-    for two_launch in ("0", "1"):
+    for two_launch, one_wg in (("0", "0"), ("1", "0"), ("1", "1")):
         monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", two_launch)
+        monkeypatch.setenv("RATSPARSE_FUSED_ONE_WG", one_wg)
         out2 = torch.zeros_like(out)
         idx2 = torch.full_like(idx, -7)
         rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out2, None, idx2, ws)
         np.testing.assert_array_equal(to_np(idx2), gidx)
         assert attn_close(to_np(out2), oout2, 2e-2 if w.dtype == "bf16" else 1e-4)[0]
         out3 = torch.zeros_like(out)
-        rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out3, None, None, ws)
+        lse3 = torch.zeros_like(lse)
+        rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out3, lse3, None, ws)
         assert torch.equal(out3, out2)  # same result when the selection is not emitted
+        _, olse2 = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, gidx)
+        np.testing.assert_allclose(to_np(lse3), olse2, rtol=1e-4, atol=1e-4)
     monkeypatch.delenv("RATSPARSE_FUSED_TWO_LAUNCH")
+    monkeypatch.delenv("RATSPARSE_FUSED_ONE_WG")
+    out4 = torch.zeros_like(out)
+    rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out4, None, None, ws)  # own choice
+    assert attn_close(to_np(out4), oout2, 2e-2 if w.dtype == "bf16" else 1e-4)[0]
 
     # dense path, and full budget = dense
     outd = torch.zeros_like(out)
