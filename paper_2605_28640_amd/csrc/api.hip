@@ -21,7 +21,8 @@ void step_at_state_dispatch(int dtype, int D, const void *k, const void *v, cons
                             const uint32_t *pos_state, long T_max, hipStream_t stream);
 void unit_decode_dispatch(int dtype, int D, const void *q, const void *meta, const void *k_cache, const void *v_cache,
                           void *out, float *lse_out, int32_t *idx_out, int B, int Hq, int Hkv, long Tcap, int P,
-                          long T_valid, int Np, int K, int n_first, int n_local, float scale, hipStream_t stream);
+                          long T_valid, int Np, int K, int n_first, int n_local, float scale, uint32_t *state,
+                          hipStream_t stream);
 int score_select_dispatch(int dtype, int D, int GQ, const void *q, const void *meta, uint64_t *scores,
                           float *scores_out, int32_t *idx_out, int B, int Hq, int Hkv, long Np_cap, int Np, int K,
                           int n_first, int n_local, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag,
@@ -457,7 +458,7 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     const int one_wg = env_int("RATSPARSE_FUSED_ONE_WG", unit_rule ? 1 : 0);
     if (fused && !group && one_wg && Np <= 4096 && K <= 1024) {
         unit_decode_dispatch(s->dtype, s->D, q, meta, k_cache, v_cache, out, lse_out, idx_out, s->B, s->Hq, s->Hkv,
-                             s->Tcap, s->P, T_valid, (int)Np, K, n_first, n_local, scale, (hipStream_t)stream);
+                             s->Tcap, s->P, T_valid, (int)Np, K, n_first, n_local, scale, nullptr, (hipStream_t)stream);
         return launch_status();
     }
     if (fused && !group && !two_launch) {
@@ -564,6 +565,15 @@ int32_t rat_decode_step(const rs_shape *s, const void *k, const void *v, const f
     step_at_state_dispatch(s->dtype, s->D, k, v, g, state_k, state_v, k_cache, v_cache, meta, s->P, s->B * s->Hkv,
                            s->Tcap, (const uint32_t *)w, T_max, (hipStream_t)stream);
     if (launch_status() != RS_OK) return RS_LAUNCH_FAILED;
+    // short contexts: one workgroup per (batch, query head), as in sparse_attn_decode (sized at T_max)
+    const long units = (long)s->B * s->Hq;
+    const double unit_bytes = ((double)L.Np * 2 + (double)K * s->P * 2) * s->D * esize(s->dtype);
+    const bool unit_rule = unit_bytes <= 1.5e6 && (units >= 128 || unit_bytes <= 512e3);
+    if (env_int("RATSPARSE_FUSED_ONE_WG", unit_rule ? 1 : 0) && L.Np <= 4096 && K <= 1024) {
+        unit_decode_dispatch(s->dtype, s->D, q, meta, k_cache, v_cache, out, lse_out, idx_out, s->B, s->Hq, s->Hkv,
+                             s->Tcap, s->P, T_max, L.Np, K, n_first, n_local, scale, (uint32_t *)w, (hipStream_t)stream);
+        return launch_status();
+    }
     FusedParams prm;
     int threads = 512;
     const long grid = fused_setup(prm, s, L, w, q, meta, k_cache, v_cache, out, lse_out, idx_out, T_max, K, n_first,

@@ -434,12 +434,24 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
 // ------------------------------------------------------------------------------------
 constexpr int kUnitThreads = 512;
 
-template <typename ST, int D>
+// STATE (the replayable decode step): the sequence length is not an argument but the workspace's
+// token count + 1 (the step's append has run); Np_lds = the page count the LDS was sized for;
+// the last workgroup out advances the count and the tag word.
+template <typename ST, int D, bool STATE>
 __global__ __launch_bounds__(kUnitThreads) void quest_unit_decode_kernel(
     const ST *__restrict__ q, const ST *__restrict__ meta, const ST *__restrict__ k_cache,
     const ST *__restrict__ v_cache, ST *__restrict__ out, float *__restrict__ lse_out, int32_t *__restrict__ idx_out,
-    int Hq, int Hkv, long Tcap, int P, long T_valid, int Np, int K, int n_first, int n_local, float scale)
+    int Hq, int Hkv, long Tcap, int P, long T_valid, int Np, int K, int n_first, int n_local, float scale,
+    int Np_lds, uint32_t *state, long T_max)
 {
+    if constexpr (STATE) {
+        T_valid = *reinterpret_cast<const long *>(state + kCtrlStateT) + 1;
+        Np = (int)((T_valid + P - 1) / P);
+        if (T_valid > T_max || K > Np) {  // outside what the buffers were sized for: report, do nothing
+            if (blockIdx.x == 0 && threadIdx.x == 0) atomicExch(state + kCtrlAsyncErr, 1u);
+            return;
+        }
+    }
     constexpr int LPR = D / 8;
     constexpr int RPW = 64 / LPR;
     constexpr int UNR = 4;
@@ -453,7 +465,7 @@ __global__ __launch_bounds__(kUnitThreads) void quest_unit_decode_kernel(
     __shared__ float s_o[NW][D];
     extern __shared__ uint32_t s_dyn[];
     uint32_t *s_keys = s_dyn;
-    int *s_sel = reinterpret_cast<int *>(s_dyn + Np);
+    int *s_sel = reinterpret_cast<int *>(s_dyn + Np_lds);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -611,17 +623,32 @@ __global__ __launch_bounds__(kUnitThreads) void quest_unit_decode_kernel(
         from_f32(out[(long)unit * D + tid], O * inv);
         if (tid == 0 && lse_out) lse_out[unit] = (L > 0.f) ? M + __logf(L) : -INFINITY;
     }
+    if constexpr (STATE) {
+        if (tid == 0 && atomicAdd(state + kCtrlDone, 1u) == gridDim.x - 1u) {  // every workgroup has read the state
+            atomicExch(state + kCtrlDone, 0u);
+            *reinterpret_cast<long *>(state + kCtrlStateT) = T_valid;
+            const uint32_t nt = state[kCtrlStateTag] + 0x85EBCA6Bu;
+            state[kCtrlStateTag] = nt ? nt : 0x5bd1e995u;
+        }
+    }
 }
 
+// state != NULL: the replayable step (T_valid = the largest length, Np = its page count)
 void unit_decode_dispatch(int dtype, int D, const void *q, const void *meta, const void *k_cache, const void *v_cache,
                           void *out, float *lse_out, int32_t *idx_out, int B, int Hq, int Hkv, long Tcap, int P,
-                          long T_valid, int Np, int K, int n_first, int n_local, float scale, hipStream_t stream)
+                          long T_valid, int Np, int K, int n_first, int n_local, float scale, uint32_t *state,
+                          hipStream_t stream)
 {
     const size_t lds = (size_t)(Np + K) * 4;
-#define RS_LAUNCH(ST, DD)                                                                                        \
-    quest_unit_decode_kernel<ST, DD><<<(unsigned)(B * Hq), kUnitThreads, lds, stream>>>(                         \
+#define RS_LAUNCH1(ST, DD, SS)                                                                                   \
+    quest_unit_decode_kernel<ST, DD, SS><<<(unsigned)(B * Hq), kUnitThreads, lds, stream>>>(                     \
         (const ST *)q, (const ST *)meta, (const ST *)k_cache, (const ST *)v_cache, (ST *)out, lse_out, idx_out, \
-        Hq, Hkv, Tcap, P, T_valid, Np, K, n_first, n_local, scale)
+        Hq, Hkv, Tcap, P, T_valid, Np, K, n_first, n_local, scale, Np, state, T_valid)
+#define RS_LAUNCH(ST, DD)                  \
+    do {                                   \
+        if (state) RS_LAUNCH1(ST, DD, true); \
+        else RS_LAUNCH1(ST, DD, false);    \
+    } while (0)
     if (dtype == RS_BF16) {
         if (D == 128) RS_LAUNCH(bf16, 128);
         else RS_LAUNCH(bf16, 64);
@@ -630,6 +657,7 @@ void unit_decode_dispatch(int dtype, int D, const void *q, const void *meta, con
         else RS_LAUNCH(float, 64);
     }
 #undef RS_LAUNCH
+#undef RS_LAUNCH1
 }
 
 void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache, const void *v_cache,

@@ -59,9 +59,20 @@ def _step_inputs(w, step):
     return to_dev(k, w.dtype), to_dev(v, w.dtype), to_dev(g), to_dev(q, w.dtype), (k, v, g, q)
 
 
+def _force_form(monkeypatch, form):
+    """Both sides run the same form of select-then-attend: the persistent launch, or one workgroup
+    per (batch, head) (the step takes one of these two by shape; the knobs force either)."""
+    monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0" if form == "persistent" else "1")
+    monkeypatch.setenv("RATSPARSE_FUSED_ONE_WG", "0" if form == "persistent" else "1")
+
+
+FORMS = ["persistent", "one_wg"]
+
+
+@pytest.mark.parametrize("form", FORMS)
 @pytest.mark.parametrize("case", range(len(CASES)))
-def test_step_equals_scan_then_fused_decode(rs, monkeypatch, case):
-    monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0")  # the step is the one-launch form
+def test_step_equals_scan_then_fused_decode(rs, monkeypatch, case, form):
+    _force_form(monkeypatch, form)
     _, T0, steps, Tcap, P, K, n_first, n_local = CASES[case]
     say("decode step case", case, T0, steps, Tcap, P, K)
     w, s, pre, a, b = _setup(rs, case)
@@ -120,7 +131,9 @@ def test_step_equals_scan_then_fused_decode(rs, monkeypatch, case):
     assert ok, worst
 
 
-def test_step_past_the_sized_length_changes_nothing_and_reports(rs):
+@pytest.mark.parametrize("form", FORMS)
+def test_step_past_the_sized_length_changes_nothing_and_reports(rs, monkeypatch, form):
+    _force_form(monkeypatch, form)
     w, T0, steps, Tcap, P, K, n_first, n_local = CASES[0]
     w, s, pre, a, b = _setup(rs, 0)
     dt = tdtype(w.dtype)
@@ -147,8 +160,9 @@ def test_step_past_the_sized_length_changes_nothing_and_reports(rs):
     assert torch.equal(keep[3], out)
 
 
-def test_step_replays_from_a_captured_graph(rs, monkeypatch):
-    monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0")
+@pytest.mark.parametrize("form", FORMS)
+def test_step_replays_from_a_captured_graph(rs, monkeypatch, form):
+    _force_form(monkeypatch, form)
     _, T0, steps, Tcap, P, K, n_first, n_local = CASES[0]
     w, s, pre, a, b = _setup(rs, 0)
     dt = tdtype(w.dtype)
@@ -199,7 +213,7 @@ def test_step_replays_from_a_captured_graph(rs, monkeypatch):
 def test_step_at_the_measured_size_equals_the_two_calls(rs, monkeypatch):
     """The measured configuration (batch 4, 32 heads, 64K context, 256 of 4096+ pages): several
     score and attention slices per unit, page count growing under the fixed work split."""
-    monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0")
+    _force_form(monkeypatch, "persistent")
     B, H, D, P, K = 4, 32, 128, 16, 256
     T0, steps = 65536 - 6, 14  # crosses the edge of page 4096
     Tcap = 65536 + 64
