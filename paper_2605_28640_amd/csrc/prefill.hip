@@ -175,7 +175,8 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t *p)
 }
 
 // MASKED: the routed form for dense routings (small blocks, many picks per row): contiguous
-// causal tiles as in the dense case, each lane carrying the bit set of its row's listed blocks;
+// causal tiles as in the dense case, each lane carrying the bit set of its row's listed blocks
+// (nothing is attended that is not listed, the row's own block included);
 // a 64-key step lies inside one block (block % 64 == 0), a lane whose row did not list it adds
 // nothing there, and a wave none of whose rows listed it skips the step's arithmetic.
 template <int D, bool MASKED>
@@ -298,7 +299,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int c = 0; c < NC; ++c) qf[c] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * c + 8 * h);
     }
 
-    // ---- routed by bit sets: the blocks this lane's row listed (its own block always) ----
+    // ---- routed by bit sets: the blocks this lane's row listed (its own block only if listed) ----
     uint64_t selmask = ~0ull;
     if constexpr (MASKED) {
         selmask = 0ull;
@@ -308,7 +309,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 const int j = row[kk];
                 if (j >= 0 && j < 64) selmask |= 1ull << j;
             }
-            selmask |= 1ull << (int)(tq / a.block);
         }
     }
     // the blocks any row of this wave listed, as a scalar: steps outside it are skipped by the wave

@@ -174,3 +174,40 @@ def test_moba_exact_ties_pick_lowest_blocks(rs, K, n_first, block):
         assert list(oidx[0, 0, t]) == want, (t, oidx[0, 0, t], want)  # the oracle follows the stated rule
     np.testing.assert_array_equal(gidx, oidx)
     ws.async_status()
+
+
+@pytest.mark.parametrize("form", ["0", "1"])
+def test_lists_are_taken_as_given(rs, monkeypatch, form):
+    """The attention follows the lists it is handed, whatever wrote them: rows whose own block is
+    not listed do not attend it, rows with an empty list give zeros and a log-sum-exp of -inf,
+    entries may come in any order.  Both forms of the routed kernel."""
+    monkeypatch.setenv("RATSPARSE_PREFILL_MASKED", form)
+    w = synth.C4.scaled(B=1, Hq=4, Hkv=2, T=1536)
+    T, block, K = 1536, 128, 4
+    w, q, kc, vc = _setup(w, T, T)
+    Nb = T // block
+    rng = np.random.default_rng(99)
+    idx = np.full((w.B, w.Hq, T, K), -1, dtype=np.int32)
+    for b in range(w.B):
+        for h in range(w.Hq):
+            for t in range(T):
+                own = t // block
+                n = int(rng.integers(0, min(K, own + 1) + 1))  # sometimes nothing at all
+                pick = rng.choice(own + 1, size=n, replace=False)  # may or may not hold the own block
+                idx[b, h, t, :n] = pick  # unsorted
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, T, 16, torch.bfloat16)
+    ws = rs.Workspace(rs.sparse_attn_prefill_workspace_bytes(s, T, block, K))
+    out = torch.zeros(w.B, w.Hq, T, w.D, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(w.B, w.Hq, T, device="cuda")
+    scale = 1.0 / np.sqrt(w.D)
+    rs.sparse_attn_prefill(s, to_dev(q, "bf16"), to_dev(kc, "bf16"), to_dev(vc, "bf16"), T, block, scale,
+                           torch.from_numpy(idx).cuda(), K, out, lse, ws)
+    oout, olse = oracle.sparse_attn_prefill(q, kc, vc, T, block, scale, idx)
+    empty = np.all(idx < 0, axis=-1)
+    assert empty.any() and (~empty).any()
+    got, glse = to_np(out), to_np(lse)
+    assert np.all(got[empty] == 0) and np.all(np.isneginf(glse[empty]))
+    ok, worst = attn_close(got[~empty], oout[~empty])
+    assert ok, worst
+    np.testing.assert_allclose(glse[~empty], olse[~empty], rtol=2e-3, atol=2e-3)
+    ws.async_status()
