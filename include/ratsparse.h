@@ -220,7 +220,10 @@ int32_t moba_select_prefill(const rs_shape *s, const void *q, const void *k_cach
 /* ---- Sparse evaluation at prefill: Sec. 2.2, Eq. 4 ------------------------------------
  * For every query token t: softmax attention over the tokens i <= t of its listed
  * blocks (idx [B, Hq, T, K] as written by moba_select_prefill), or causal dense
- * attention when idx == NULL.
+ * attention when idx == NULL.  A row's entries are distinct block numbers not above the
+ * row's own block, in any order, negative entries are skipped; only listed blocks are
+ * attended (the own block too only if listed); a row with nothing listed gets zeros and a
+ * log-sum-exp of -inf.
  *   out     [B, Hq, T, D] dtype
  *   lse_out [B, Hq, T] float32 or NULL
  * Runs on the bf16 matrix cores: dtype must be RS_BF16 (RS_UNSUPPORTED otherwise);
