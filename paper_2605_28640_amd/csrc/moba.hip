@@ -557,8 +557,7 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     long wg_per_unit = (256 + units - 1) / units;
     if (const char *e = getenv("RATSPARSE_GATE_WGS")) wg_per_unit = (atol(e) + units - 1) / units;
     if (wg_per_unit < 1) wg_per_unit = 1;
-    const char *enw = getenv("RATSPARSE_GATE_NWV");
-    const int nwv = (enw && atoi(enw) == 4) ? 4 : 6;
+    constexpr int nwv = 6;
     if (wg_per_unit > (n_tiles + nwv - 1) / nwv) wg_per_unit = (n_tiles + nwv - 1) / nwv;
     const dim3 g4((unsigned)wg_per_unit, (unsigned)units);
     const char *eso = getenv("RATSPARSE_GATE_SHARED");
@@ -575,11 +574,7 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
         if (s->D == 128) {
             moba_block_means_kernel<bf16, 128><<<g1p, 256, 0, stream>>>((const bf16 *)k_cache, means_out, split, s->Tcap, T, block, Nb);
 #define RS_GATE1(DD, KLL, WW, LDS) moba_gate_mfma_kernel<DD, KLL, WW, 1><<<g3, 64, LDS, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first)
-#define RS_GATE4(DD, KLL)                                                                                                                   \
-    do {                                                                                                                                    \
-        if (nwv == 6) moba_gate_mfma_kernel<DD, KLL, false, 6><<<g4, 384, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first); \
-        else moba_gate_mfma_kernel<DD, KLL, false, 4><<<g4, 256, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first);        \
-    } while (0)
+#define RS_GATE4(DD, KLL) moba_gate_mfma_kernel<DD, KLL, false, 6><<<g4, 384, 0, stream>>>((const bf16 *)q, split, idx_out, s->Hq, s->Hkv, T, block, Nb, K, n_first)
 #define RS_GATE(DD)                                            \
     do {                                                       \
         if (kl == 0) RS_GATE1(DD, 0, true, lds_mfma);          \

@@ -667,18 +667,11 @@ void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache
                             hipStream_t stream)
 {
     const dim3 grid((unsigned)splits, (unsigned)(B * Hq));
-    const char *e = std::getenv("RATSPARSE_ATTEND_THREADS");
-    const int nt = e ? std::atoi(e) : 512;
-#define RS_LAUNCH1(ST, DD, NT)                                                                              \
-    decode_attend_kernel<ST, DD, NT><<<grid, NT, 0, stream>>>(                                              \
+    constexpr int kAttThreads = 512;  // about one such workgroup per CU (see the split rule of the caller)
+#define RS_LAUNCH(ST, DD)                                                                                   \
+    decode_attend_kernel<ST, DD, kAttThreads><<<grid, kAttThreads, 0, stream>>>(                            \
         (const ST *)q, (const ST *)k_cache, (const ST *)v_cache, idx, (ST *)out, lse_out, partial, Hq, Hkv, \
         Tcap, P, T_valid, K, scale, splits, unit_ctr, err, tag, spin_limit, idx_per_kv)
-#define RS_LAUNCH(ST, DD)                          \
-    do {                                           \
-        if (nt == 1024) RS_LAUNCH1(ST, DD, 1024);  \
-        else if (nt == 512) RS_LAUNCH1(ST, DD, 512); \
-        else RS_LAUNCH1(ST, DD, 256);              \
-    } while (0)
     if (dtype == RS_BF16) {
         if (D == 128) RS_LAUNCH(bf16, 128);
         else RS_LAUNCH(bf16, 64);
@@ -686,7 +679,6 @@ void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache
         if (D == 128) RS_LAUNCH(float, 128);
         else RS_LAUNCH(float, 64);
     }
-#undef RS_LAUNCH1
 #undef RS_LAUNCH
 }
 
