@@ -164,7 +164,7 @@ static DecodeLayout decode_layout(const rs_shape *s, long T_valid, int K)
 // T_valid tokens laid out by L; returns the grid
 static long fused_setup(FusedParams &prm, const rs_shape *s, const DecodeLayout &L, char *w, const void *q,
                         const void *meta, const void *k_cache, const void *v_cache, void *out, float *lse_out,
-                        int32_t *idx_out, long T_valid, int K, int n_first, int n_local, float scale, int *threads_out)
+                        int32_t *idx_out, long T_valid, int K, int n_first, int n_local, float scale)
 {
     const long units = (long)s->B * s->Hq;
     uint32_t *ctr_score = (uint32_t *)w + kCtrlUnit0;
@@ -199,8 +199,6 @@ static long fused_setup(FusedParams &prm, const rs_shape *s, const DecodeLayout 
     prm.trace = env_int("RATSPARSE_TRACE", 0) ? (uint64_t *)(w + L.off_trace) : nullptr;
     prm.state = nullptr; prm.T_max = 0;
     const long items = units * (prm.S_score + prm.S_att) + (long)prm.units_fine * (prm.S_att_fine - prm.S_att);
-    // two 512-thread workgroups per CU: one streams while the other selects or merges
-    *threads_out = env_int("RATSPARSE_FUSED_THREADS", 512) == 256 ? 256 : 512;
     long grid = env_int("RATSPARSE_FUSED_GRID", 2 * num_cus());
     if (grid > items) grid = items;
     return grid;
@@ -464,11 +462,10 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     if (fused && !group && !two_launch) {
         // one persistent launch: score -> select -> attend, handed over through tagged words
         FusedParams prm;
-        int threads = 512;
         const long grid = fused_setup(prm, s, L, w, q, meta, k_cache, v_cache, out, lse_out, idx_out, T_valid, K, n_first,
-                                      n_local, scale, &threads);
+                                      n_local, scale);
         prm.tag = tag;
-        st = decode_fused_dispatch(s->dtype, s->D, prm, L.Np, (int)grid, threads, (hipStream_t)stream);
+        st = decode_fused_dispatch(s->dtype, s->D, prm, L.Np, (int)grid, (hipStream_t)stream);
         if (st != RS_OK) return st;
         return launch_status();
     }
@@ -575,13 +572,12 @@ int32_t rat_decode_step(const rs_shape *s, const void *k, const void *v, const f
         return launch_status();
     }
     FusedParams prm;
-    int threads = 512;
     const long grid = fused_setup(prm, s, L, w, q, meta, k_cache, v_cache, out, lse_out, idx_out, T_max, K, n_first,
-                                  n_local, scale, &threads);
+                                  n_local, scale);
     prm.reverse = env_int("RATSPARSE_FUSED_PINGPONG", 1);  // the kernel takes the parity of the length it reads
     prm.state = (uint32_t *)w;
     prm.T_max = T_max;
-    st = decode_fused_dispatch(s->dtype, s->D, prm, L.Np, (int)grid, threads, (hipStream_t)stream);
+    st = decode_fused_dispatch(s->dtype, s->D, prm, L.Np, (int)grid, (hipStream_t)stream);
     if (st != RS_OK) return st;
     return launch_status();
 }

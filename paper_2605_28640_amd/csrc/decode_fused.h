@@ -34,6 +34,6 @@ struct FusedParams {
 };
 
 // np_lds: page keys the dynamic LDS must hold (Np, or its largest value over the replays)
-int decode_fused_dispatch(int dtype, int D, const FusedParams &prm, int np_lds, int grid, int threads, hipStream_t stream);
+int decode_fused_dispatch(int dtype, int D, const FusedParams &prm, int np_lds, int grid, hipStream_t stream);
 
 }  // namespace rs

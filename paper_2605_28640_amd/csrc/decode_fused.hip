@@ -362,14 +362,11 @@ static int launch_fused(const FusedParams &prm, int np_lds, int grid, hipStream_
     return RS_OK;
 }
 
-int decode_fused_dispatch(int dtype, int D, const FusedParams &prm, int np_lds, int grid, int threads, hipStream_t stream)
+int decode_fused_dispatch(int dtype, int D, const FusedParams &prm, int np_lds, int grid, hipStream_t stream)
 {
-    if (threads == 512) {
-        if (dtype == RS_BF16) return D == 128 ? launch_fused<bf16, 128, 512>(prm, np_lds, grid, stream) : launch_fused<bf16, 64, 512>(prm, np_lds, grid, stream);
-        return D == 128 ? launch_fused<float, 128, 512>(prm, np_lds, grid, stream) : launch_fused<float, 64, 512>(prm, np_lds, grid, stream);
-    }
-    if (dtype == RS_BF16) return D == 128 ? launch_fused<bf16, 128, 256>(prm, np_lds, grid, stream) : launch_fused<bf16, 64, 256>(prm, np_lds, grid, stream);
-    return D == 128 ? launch_fused<float, 128, 256>(prm, np_lds, grid, stream) : launch_fused<float, 64, 256>(prm, np_lds, grid, stream);
+    // two 512-thread workgroups per CU: one streams while the other selects or merges
+    if (dtype == RS_BF16) return D == 128 ? launch_fused<bf16, 128, 512>(prm, np_lds, grid, stream) : launch_fused<bf16, 64, 512>(prm, np_lds, grid, stream);
+    return D == 128 ? launch_fused<float, 128, 512>(prm, np_lds, grid, stream) : launch_fused<float, 64, 512>(prm, np_lds, grid, stream);
 }
 
 }  // namespace rs
