@@ -9,6 +9,7 @@
 namespace rs {
 // scan.hip
 int scan_chunk_tokens(int dtype, int D);
+bool scan_writes_meta(int dtype, int D, int P, int BH, long T_new, long t0);
 bool scan_uses_step_kernel(long T_new);
 void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
                    float *state_v, void *k_cache, void *v_cache, void *meta, int P, int BH, long T_new, long t0,
@@ -317,10 +318,12 @@ int32_t rat_scan(const rs_shape *s, const void *k, const void *v, const float *g
         ctrl = (uint32_t *)ws;
         rec = (uint64_t *)((char *)ws + RS_WS_CTRL_BYTES);
     }
-    const bool step = scan_uses_step_kernel(T_new);
-    scan_dispatch(s->dtype, s->D, k, v, g, state_k, state_v, k_cache, v_cache, step ? meta : nullptr, s->P, (int)BH,
+    // the page bounds leave with the states where the kernel can do that (one token: always; long
+    // runs: bfloat16, 128 channels, 16-token pages, chunk-aligned start); else a pass over the touched pages
+    const bool in_scan = meta && scan_writes_meta(s->dtype, s->D, s->P, (int)BH, T_new, t0);
+    scan_dispatch(s->dtype, s->D, k, v, g, state_k, state_v, k_cache, v_cache, in_scan ? meta : nullptr, s->P, (int)BH,
                   T_new, t0, s->Tcap, ctrl, rec, next_tag(), g_spin_limit.load(), (hipStream_t)stream);
-    if (meta && !step) {  // long runs: the pages the new rows touch are recomputed after the scan
+    if (meta && !in_scan) {  // the pages the new rows touch are recomputed after the scan
         const int p_begin = (int)(t0 / s->P);
         const int p_end = (int)((t0 + T_new + s->P - 1) / s->P);
         page_meta_dispatch(s->dtype, s->D, k_cache, meta, (int)BH, s->Tcap, s->P, p_begin, p_end - p_begin, t0 + T_new,

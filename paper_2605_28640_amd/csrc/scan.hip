@@ -27,13 +27,18 @@
 
 namespace rs {
 
-template <typename ST, int D, int DS, int NT, int NW>
+// META (bfloat16, full 128-channel rows, 16-token pages, a run that starts on a chunk boundary):
+// a wave's 16 tokens are exactly one page, so the page's channelwise min / max of the stored keys
+// (App. A.1, Quest) leave with the states -- in-lane over the lane's four tokens, two shuffles
+// over the wave's row groups -- and the keys need no second pass.
+template <typename ST, int D, int DS, int NT, int NW, bool META>
 __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
     const ST *__restrict__ k, const ST *__restrict__ v, const float *__restrict__ g,
     float *__restrict__ state_k, float *__restrict__ state_v, ST *__restrict__ k_cache,
     ST *__restrict__ v_cache, int BH, long T_new, long t0, long Tcap, int n_chunks,
-    uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit)
+    uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit, ST *__restrict__ meta)
 {
+    static_assert(!META || (sizeof(ST) == 2 && DS == D && D == 128 && NT == 4), "page = the 16 tokens of a wave");
     constexpr int LPR = DS / 8;      // lanes per row (of the slab)
     constexpr int RPW = 64 / LPR;    // row groups per wave
     constexpr int CHUNK = NW * RPW * NT;
@@ -216,6 +221,12 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         sv[c] = fmaf(a[c], s_carry[wave][1][c0 + c], bv[c]);
     }
     const long out_row0 = (long)bh * Tcap + t0;
+    float plo[8], phi[8];  // META: bounds of the stored (rounded) keys of this lane's tokens
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        plo[c] = INFINITY;
+        phi[c] = -INFINITY;
+    }
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
         const long t = tbase + i;
@@ -233,6 +244,35 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
             const long off = (out_row0 + t) * D + ch0 + c0;
             R::store(k_cache + off, sk);
             R::store(v_cache + off, sv);
+            if constexpr (META) {
+                const uint32_t w[4] = {pack_bf16x2(sk[0], sk[1]), pack_bf16x2(sk[2], sk[3]), pack_bf16x2(sk[4], sk[5]),
+                                       pack_bf16x2(sk[6], sk[7])};  // the bits just stored
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float x0 = __uint_as_float(w[c] << 16), x1 = __uint_as_float(w[c] & 0xffff0000u);
+                    plo[2 * c] = fminf(plo[2 * c], x0);
+                    phi[2 * c] = fmaxf(phi[2 * c], x0);
+                    plo[2 * c + 1] = fminf(plo[2 * c + 1], x1);
+                    phi[2 * c + 1] = fmaxf(phi[2 * c + 1], x1);
+                }
+            }
+        }
+    }
+    if constexpr (META) {
+        // the wave's tokens j CHUNK + 16 wave .. + 15 are page (t0 + that) / 16: fold the four row groups
+#pragma unroll
+        for (int msk = LPR; msk < 64; msk <<= 1)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                plo[c] = fminf(plo[c], shfl_xor_f(plo[c], msk));
+                phi[c] = fmaxf(phi[c], shfl_xor_f(phi[c], msk));
+            }
+        const long tw = (long)j * CHUNK + (long)wave * (RPW * NT);  // the wave's first token
+        if (tw < T_new) {
+            const long page = (t0 + tw) / 16;
+            ST *mrow = meta + (((long)bh * (Tcap / 16) + page) * 2) * D + c0;
+            if (rg == 0) R::store(mrow, plo);
+            if (rg == 1) R::store(mrow + D, phi);
         }
     }
 
@@ -291,11 +331,11 @@ __global__ __launch_bounds__(256) void rat_step_kernel(
     state_v[e] = sv;
 }
 
-template <typename ST, int D, int DS>
+template <typename ST, int D, int DS, bool META>
 static int launch_scan(const void *k, const void *v, const float *g, float *state_k,
                        float *state_v, void *k_cache, void *v_cache, int BH, long T_new, long t0,
                        long Tcap, uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit,
-                       hipStream_t stream)
+                       void *meta, hipStream_t stream)
 {
     constexpr int NT = sizeof(ST) == 2 ? 4 : 2;
     constexpr int NW = 8;
@@ -307,7 +347,7 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
         if (per_cu == 0) {
             int dev = 0, n = 0;
             (void)hipGetDevice(&dev);
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, rat_scan_chunk_kernel<ST, D, DS, NT, NW>, NW * 64, 0) != hipSuccess || n < 1) n = 1;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, rat_scan_chunk_kernel<ST, D, DS, NT, NW, META>, NW * 64, 0) != hipSuccess || n < 1) n = 1;
             per_cu = n;
             if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         }
@@ -315,9 +355,9 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
         const long want = e ? std::atol(e) : (long)per_cu * cus;
         if (grid > want) grid = want;
     }
-    rat_scan_chunk_kernel<ST, D, DS, NT, NW><<<dim3((unsigned)grid), dim3(NW * 64), 0, stream>>>(
+    rat_scan_chunk_kernel<ST, D, DS, NT, NW, META><<<dim3((unsigned)grid), dim3(NW * 64), 0, stream>>>(
         (const ST *)k, (const ST *)v, g, state_k, state_v, (ST *)k_cache, (ST *)v_cache, BH, T_new,
-        t0, Tcap, n_chunks, ctrl, rec, tag, spin_limit);
+        t0, Tcap, n_chunks, ctrl, rec, tag, spin_limit, (ST *)meta);
     return 0;
 }
 
@@ -329,6 +369,24 @@ int scan_chunk_tokens(int dtype, int D)
 
 // host entry used by the C ABI (arguments already validated)
 bool scan_uses_step_kernel(long T_new) { return T_new <= 8; }
+
+static bool scan_uses_slabs(int BH, long T_new)
+{
+    // few (batch, head) pairs and a long run: 32-channel slabs, so that the chunk chains are
+    // shorter and there are more of them
+    const char *es = std::getenv("RATSPARSE_SCAN_SLAB");
+    return es ? std::atoi(es) != 0 : (BH <= 16 && T_new >= 2048);
+}
+
+// whether the chunk kernel leaves the Quest page bounds of the rows it stores (else the caller
+// recomputes the touched pages afterwards)
+bool scan_writes_meta(int dtype, int D, int P, int BH, long T_new, long t0)
+{
+    if (scan_uses_step_kernel(T_new)) return true;  // the step kernel keeps the touched page current
+    const char *e = std::getenv("RATSPARSE_SCAN_META");
+    if (e && std::atoi(e) == 0) return false;
+    return dtype == RS_BF16 && D == 128 && P == 16 && !scan_uses_slabs(BH, T_new) && t0 % scan_chunk_tokens(dtype, D) == 0;
+}
 
 void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
                    float *state_v, void *k_cache, void *v_cache, void *meta, int P, int BH, long T_new, long t0,
@@ -346,17 +404,17 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
                                                               (float *)k_cache, (float *)v_cache, (float *)meta, P, BH, D, T_new, t0, Tcap, nullptr, 0);
         return;
     }
-    // few (batch, head) pairs and a long run: 32-channel slabs, so that the chunk chains are
-    // shorter and there are more of them
-    const char *es = std::getenv("RATSPARSE_SCAN_SLAB");
-    const bool slab = es ? std::atoi(es) != 0 : (BH <= 16 && T_new >= 2048);
-#define RS_SCAN(ST, DD, DSS) launch_scan<ST, DD, DSS>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, stream)
+    const bool slab = scan_uses_slabs(BH, T_new);
+#define RS_SCAN(ST, DD, DSS, MM) launch_scan<ST, DD, DSS, MM>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, meta, stream)
     if (dtype == RS_BF16) {
-        if (D == 128) slab ? RS_SCAN(bf16, 128, 32) : RS_SCAN(bf16, 128, 128);
-        else slab ? RS_SCAN(bf16, 64, 32) : RS_SCAN(bf16, 64, 64);
+        if (D == 128) {
+            if (slab) RS_SCAN(bf16, 128, 32, false);
+            else if (meta && scan_writes_meta(dtype, D, P, BH, T_new, t0)) RS_SCAN(bf16, 128, 128, true);
+            else RS_SCAN(bf16, 128, 128, false);
+        } else slab ? RS_SCAN(bf16, 64, 32, false) : RS_SCAN(bf16, 64, 64, false);
     } else {
-        if (D == 128) slab ? RS_SCAN(float, 128, 32) : RS_SCAN(float, 128, 128);
-        else slab ? RS_SCAN(float, 64, 32) : RS_SCAN(float, 64, 64);
+        if (D == 128) slab ? RS_SCAN(float, 128, 32, false) : RS_SCAN(float, 128, 128, false);
+        else slab ? RS_SCAN(float, 64, 32, false) : RS_SCAN(float, 64, 64, false);
     }
 #undef RS_SCAN
 }

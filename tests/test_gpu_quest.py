@@ -209,6 +209,40 @@ def test_scan_with_meta_equals_separate_page_meta(rs):
         ws.async_status()
 
 
+@pytest.mark.parametrize("in_scan", ["1", "0"])
+def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan):
+    """Long runs with the page metadata: where the scan kernel can (bfloat16, 128 channels,
+    16-token pages, a start on a chunk boundary) the bounds leave with the states, else the
+    touched pages are recomputed afterwards; runs of both kinds back to back, with ragged ends,
+    must leave what one bulk pass over the final cache computes.  The knob switches the first
+    kind off, so both paths see every run."""
+    monkeypatch.setenv("RATSPARSE_SCAN_META", in_scan)
+    B, H, D, P = 2, 20, 128, 16  # 40 (batch, head) pairs: full-row chunks
+    runs = [(0, 256), (256, 777), (1033, 200), (1233, 3000)]  # (t0, T_new): aligned, aligned, unaligned, unaligned
+    T = 4233
+    Tcap = 4240
+    r = np.random.default_rng(17)
+    k = synth.to_bf16_grid(r.standard_normal((B, H, T, D)).astype(np.float32))
+    v = synth.to_bf16_grid(r.standard_normal((B, H, T, D)).astype(np.float32))
+    g = (1 / (1 + np.exp(-(4.2 + 0.5 * r.standard_normal((B, H, T, D)))))).astype(np.float32)
+    dt = torch.bfloat16
+    s = rs.make_shape(B, H, H, D, Tcap, P, dt)
+    kc = torch.zeros(B, H, Tcap, D, dtype=dt, device="cuda")
+    vc = torch.zeros_like(kc)
+    sk = torch.zeros(B, H, D, device="cuda")
+    sv = torch.zeros_like(sk)
+    meta = torch.zeros(B, H, Tcap // P, 2, D, dtype=dt, device="cuda")
+    ws = rs.Workspace(rs.rat_scan_workspace_bytes(s, 3000))
+    for t0, n in runs:
+        rs.rat_scan(s, to_dev(k[:, :, t0:t0 + n], "bf16"), to_dev(v[:, :, t0:t0 + n], "bf16"), to_dev(g[:, :, t0:t0 + n]),
+                    sk, sv, kc, vc, t0, n, ws, meta)
+    want = torch.zeros_like(meta)
+    rs.quest_page_meta(s, kc, want, 0, T)
+    assert torch.equal(meta, want)
+    np.testing.assert_array_equal(to_np(meta), oracle.quest_page_meta(to_np(kc), P, T))
+    ws.async_status()
+
+
 def test_exact_ties_take_the_lowest_index(rs):
     B, H, D, P, Np = 1, 2, 128, 16, 300
     r = np.random.default_rng(3)
