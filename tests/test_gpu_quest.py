@@ -209,18 +209,19 @@ def test_scan_with_meta_equals_separate_page_meta(rs):
         ws.async_status()
 
 
+@pytest.mark.parametrize("P", [16, 32, 64, 128, 256])
 @pytest.mark.parametrize("in_scan", ["1", "0"])
-def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan):
+def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan, P):
     """Long runs with the page metadata: where the scan kernel can (bfloat16, 128 channels,
-    16-token pages, a start on a chunk boundary) the bounds leave with the states, else the
+    pages of 16 to 128 tokens, a start on a chunk boundary) the bounds leave with the states, else the
     touched pages are recomputed afterwards; runs of both kinds back to back, with ragged ends,
     must leave what one bulk pass over the final cache computes.  The knob switches the first
     kind off, so both paths see every run."""
     monkeypatch.setenv("RATSPARSE_SCAN_META", in_scan)
-    B, H, D, P = 2, 20, 128, 16  # 40 (batch, head) pairs: full-row chunks
+    B, H, D = 2, 20, 128  # 40 (batch, head) pairs: full-row chunks
     runs = [(0, 256), (256, 777), (1033, 200), (1233, 3000)]  # (t0, T_new): aligned, aligned, unaligned, unaligned
     T = 4233
-    Tcap = 4240
+    Tcap = 4352  # a multiple of every page size
     r = np.random.default_rng(17)
     k = synth.to_bf16_grid(r.standard_normal((B, H, T, D)).astype(np.float32))
     v = synth.to_bf16_grid(r.standard_normal((B, H, T, D)).astype(np.float32))
