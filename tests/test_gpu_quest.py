@@ -219,7 +219,8 @@ def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan, P):
     kind off, so both paths see every run."""
     monkeypatch.setenv("RATSPARSE_SCAN_META", in_scan)
     B, H, D = 2, 20, 128  # 40 (batch, head) pairs: full-row chunks
-    runs = [(0, 256), (256, 777), (1033, 200), (1233, 3000)]  # (t0, T_new): aligned, aligned, unaligned, unaligned
+    # (t0, T_new): aligned; aligned and a single chunk; unaligned; unaligned; unaligned and long
+    runs = [(0, 256), (256, 100), (356, 677), (1033, 200), (1233, 3000)]
     T = 4233
     Tcap = 4352  # a multiple of every page size
     r = np.random.default_rng(17)
