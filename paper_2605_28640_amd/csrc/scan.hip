@@ -27,21 +27,25 @@
 
 namespace rs {
 
-// PGW > 0 (bfloat16, full 128-channel rows, a run that starts on a chunk boundary, pages of
-// 16 PGW tokens with PGW in {1, 2, 4, 8}): a wave's 16 tokens are a page or an aligned part of
-// one, so the page's channelwise min / max of the stored keys (App. A.1, Quest) leave with the
-// states -- in-lane over the lane's four tokens, two shuffles over the wave's row groups, and
-// for PGW > 1 a fold of PGW waves through LDS -- and the keys need no second pass.
-template <typename ST, int D, int DS, int NT, int NW, int PGW>
+// PAGE > 0 (bfloat16, full rows, a run that starts on a chunk boundary, PAGE a power of two from
+// 16 tokens to the chunk length): a wave's 16 (D = 128) or 32 (D = 64) tokens are whole pages or
+// an aligned part of one, so the page's channelwise min / max of the stored keys (App. A.1,
+// Quest) leave with the states -- in-lane over the lane's four tokens, shuffles over the row
+// groups of a page, and for pages longer than a wave's tokens a fold of the waves' bounds
+// through LDS -- and the keys need no second pass.
+template <typename ST, int D, int DS, int NT, int NW, int PAGE>
 __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
     const ST *__restrict__ k, const ST *__restrict__ v, const float *__restrict__ g,
     float *__restrict__ state_k, float *__restrict__ state_v, ST *__restrict__ k_cache,
     ST *__restrict__ v_cache, int BH, long T_new, long t0, long Tcap, int n_chunks,
     uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit, ST *__restrict__ meta)
 {
-    constexpr bool META = PGW > 0;
-    static_assert(!META || (sizeof(ST) == 2 && DS == D && D == 128 && NT == 4), "a wave's tokens = 16");
-    __shared__ float s_pg[META && PGW > 1 ? NW : 1][2][META && PGW > 1 ? D : 1];
+    constexpr bool META = PAGE > 0;
+    constexpr int TW = (64 / (DS / 8)) * NT;  // tokens of a wave
+    static_assert(!META || (sizeof(ST) == 2 && DS == D && NT == 4 && PAGE >= 16 && (NW * TW) % (PAGE > 0 ? PAGE : 1) == 0),
+                  "pages tile the chunk");
+    constexpr bool PG_LDS = META && PAGE > TW;  // a page spans several waves
+    __shared__ float s_pg[PG_LDS ? NW : 1][2][PG_LDS ? D : 1];
     constexpr int LPR = DS / 8;      // lanes per row (of the slab)
     constexpr int RPW = 64 / LPR;    // row groups per wave
     constexpr int CHUNK = NW * RPW * NT;
@@ -262,25 +266,34 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         }
     }
     if constexpr (META) {
-        // the wave's tokens j CHUNK + 16 wave .. + 15 are page (t0 + that) / 16: fold the four row groups
+        if constexpr (!PG_LDS) {
+            // PAGE / NT row groups make a page: fold them, then the first two lanes groups of a page write it
+            constexpr int RGP = PAGE / NT;
 #pragma unroll
-        for (int msk = LPR; msk < 64; msk <<= 1)
+            for (int msk = LPR; msk < LPR * RGP; msk <<= 1)
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                plo[c] = fminf(plo[c], shfl_xor_f(plo[c], msk));
-                phi[c] = fmaxf(phi[c], shfl_xor_f(phi[c], msk));
-            }
-        constexpr int P = 16 * PGW;
-        if constexpr (PGW == 1) {
-            const long tw = (long)j * CHUNK + (long)wave * (RPW * NT);  // the wave's first token
-            if (tw < T_new) {
-                const long page = (t0 + tw) / P;
-                ST *mrow = meta + (((long)bh * (Tcap / P) + page) * 2) * D + c0;
-                if (rg == 0) R::store(mrow, plo);
-                if (rg == 1) R::store(mrow + D, phi);
+                for (int c = 0; c < 8; ++c) {
+                    plo[c] = fminf(plo[c], shfl_xor_f(plo[c], msk));
+                    phi[c] = fmaxf(phi[c], shfl_xor_f(phi[c], msk));
+                }
+            const long tp = (long)j * CHUNK + (long)wave * TW + (long)(rg / RGP) * PAGE;  // the page's first token
+            if (tp < T_new && rg % RGP < 2) {
+                const long page = (t0 + tp) / PAGE;
+                ST *mrow = meta + (((long)bh * (Tcap / PAGE) + page) * 2) * D + c0;
+                if (rg % RGP == 0) R::store(mrow, plo);
+                else R::store(mrow + D, phi);
             }
         } else {
-            // a page spans PGW waves: their bounds meet in LDS, wave w < NW / PGW writes page w of the chunk
+            // a page spans WPP waves: each folds all its row groups, their bounds meet in LDS, and
+            // wave w < NW / WPP writes page w of the chunk
+            constexpr int WPP = PAGE / TW;
+#pragma unroll
+            for (int msk = LPR; msk < 64; msk <<= 1)
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    plo[c] = fminf(plo[c], shfl_xor_f(plo[c], msk));
+                    phi[c] = fmaxf(phi[c], shfl_xor_f(phi[c], msk));
+                }
             if (rg == 0) {
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
@@ -289,20 +302,20 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
                 }
             }
             __syncthreads();
-            const long tp = (long)j * CHUNK + (long)wave * P;  // first token of page `wave` of this chunk
-            if (wave < NW / PGW && rg < 2 && tp < T_new) {
+            const long tp = (long)j * CHUNK + (long)wave * PAGE;  // first token of page `wave` of this chunk
+            if (wave < NW / WPP && rg < 2 && tp < T_new) {
                 float x[8];
 #pragma unroll
-                for (int c = 0; c < 8; ++c) x[c] = s_pg[wave * PGW][rg][c0 + c];
+                for (int c = 0; c < 8; ++c) x[c] = s_pg[wave * WPP][rg][c0 + c];
 #pragma unroll
-                for (int w2 = 1; w2 < PGW; ++w2)
+                for (int w2 = 1; w2 < WPP; ++w2)
 #pragma unroll
                     for (int c = 0; c < 8; ++c) {
-                        const float y = s_pg[wave * PGW + w2][rg][c0 + c];
+                        const float y = s_pg[wave * WPP + w2][rg][c0 + c];
                         x[c] = rg == 0 ? fminf(x[c], y) : fmaxf(x[c], y);
                     }
-                const long page = (t0 + tp) / P;
-                R::store(meta + (((long)bh * (Tcap / P) + page) * 2 + rg) * D + c0, x);
+                const long page = (t0 + tp) / PAGE;
+                R::store(meta + (((long)bh * (Tcap / PAGE) + page) * 2 + rg) * D + c0, x);
             }
         }
     }
@@ -362,7 +375,7 @@ __global__ __launch_bounds__(256) void rat_step_kernel(
     state_v[e] = sv;
 }
 
-template <typename ST, int D, int DS, int PGW>
+template <typename ST, int D, int DS, int PAGE>
 static int launch_scan(const void *k, const void *v, const float *g, float *state_k,
                        float *state_v, void *k_cache, void *v_cache, int BH, long T_new, long t0,
                        long Tcap, uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit,
@@ -378,7 +391,7 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
         if (per_cu == 0) {
             int dev = 0, n = 0;
             (void)hipGetDevice(&dev);
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, rat_scan_chunk_kernel<ST, D, DS, NT, NW, PGW>, NW * 64, 0) != hipSuccess || n < 1) n = 1;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, rat_scan_chunk_kernel<ST, D, DS, NT, NW, PAGE>, NW * 64, 0) != hipSuccess || n < 1) n = 1;
             per_cu = n;
             if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         }
@@ -386,7 +399,7 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
         const long want = e ? std::atol(e) : (long)per_cu * cus;
         if (grid > want) grid = want;
     }
-    rat_scan_chunk_kernel<ST, D, DS, NT, NW, PGW><<<dim3((unsigned)grid), dim3(NW * 64), 0, stream>>>(
+    rat_scan_chunk_kernel<ST, D, DS, NT, NW, PAGE><<<dim3((unsigned)grid), dim3(NW * 64), 0, stream>>>(
         (const ST *)k, (const ST *)v, g, state_k, state_v, (ST *)k_cache, (ST *)v_cache, BH, T_new,
         t0, Tcap, n_chunks, ctrl, rec, tag, spin_limit, (ST *)meta);
     return 0;
@@ -416,8 +429,8 @@ bool scan_writes_meta(int dtype, int D, int P, int BH, long T_new, long t0)
     if (scan_uses_step_kernel(T_new)) return true;  // the step kernel keeps the touched page current
     const char *e = std::getenv("RATSPARSE_SCAN_META");
     if (e && std::atoi(e) == 0) return false;
-    return dtype == RS_BF16 && D == 128 && (P == 16 || P == 32 || P == 64 || P == 128) && !scan_uses_slabs(BH, T_new) &&
-           t0 % scan_chunk_tokens(dtype, D) == 0;
+    const long chunk = scan_chunk_tokens(dtype, D);  // 128 tokens at D = 128, 256 at D = 64
+    return dtype == RS_BF16 && P >= 16 && P <= chunk && (P & (P - 1)) == 0 && !scan_uses_slabs(BH, T_new) && t0 % chunk == 0;
 }
 
 void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
@@ -438,16 +451,24 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
     }
     const bool slab = scan_uses_slabs(BH, T_new);
 #define RS_SCAN(ST, DD, DSS, MM) launch_scan<ST, DD, DSS, MM>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, meta, stream)
+    const bool in_scan = !slab && meta && scan_writes_meta(dtype, D, P, BH, T_new, t0);
     if (dtype == RS_BF16) {
         if (D == 128) {
             if (slab) RS_SCAN(bf16, 128, 32, 0);
-            else if (meta && scan_writes_meta(dtype, D, P, BH, T_new, t0)) {
-                if (P == 16) RS_SCAN(bf16, 128, 128, 1);
-                else if (P == 32) RS_SCAN(bf16, 128, 128, 2);
-                else if (P == 64) RS_SCAN(bf16, 128, 128, 4);
-                else RS_SCAN(bf16, 128, 128, 8);
-            } else RS_SCAN(bf16, 128, 128, 0);
-        } else slab ? RS_SCAN(bf16, 64, 32, 0) : RS_SCAN(bf16, 64, 64, 0);
+            else if (!in_scan) RS_SCAN(bf16, 128, 128, 0);
+            else if (P == 16) RS_SCAN(bf16, 128, 128, 16);
+            else if (P == 32) RS_SCAN(bf16, 128, 128, 32);
+            else if (P == 64) RS_SCAN(bf16, 128, 128, 64);
+            else RS_SCAN(bf16, 128, 128, 128);
+        } else {
+            if (slab) RS_SCAN(bf16, 64, 32, 0);
+            else if (!in_scan) RS_SCAN(bf16, 64, 64, 0);
+            else if (P == 16) RS_SCAN(bf16, 64, 64, 16);
+            else if (P == 32) RS_SCAN(bf16, 64, 64, 32);
+            else if (P == 64) RS_SCAN(bf16, 64, 64, 64);
+            else if (P == 128) RS_SCAN(bf16, 64, 64, 128);
+            else RS_SCAN(bf16, 64, 64, 256);
+        }
     } else {
         if (D == 128) slab ? RS_SCAN(float, 128, 32, 0) : RS_SCAN(float, 128, 128, 0);
         else slab ? RS_SCAN(float, 64, 32, 0) : RS_SCAN(float, 64, 64, 0);
