@@ -319,7 +319,7 @@ int32_t rat_scan(const rs_shape *s, const void *k, const void *v, const float *g
         rec = (uint64_t *)((char *)ws + RS_WS_CTRL_BYTES);
     }
     // the page bounds leave with the states where the kernel can do that (one token: always; long
-    // runs: bfloat16, a page size that tiles the chunk, chunk-aligned start); else a pass over the touched pages
+    // runs: full-row form, a page size that tiles the chunk, chunk-aligned start); else a pass over the touched pages
     const bool in_scan = meta && scan_writes_meta(s->dtype, s->D, s->P, (int)BH, T_new, t0);
     scan_dispatch(s->dtype, s->D, k, v, g, state_k, state_v, k_cache, v_cache, in_scan ? meta : nullptr, s->P, (int)BH,
                   T_new, t0, s->Tcap, ctrl, rec, next_tag(), g_spin_limit.load(), (hipStream_t)stream);

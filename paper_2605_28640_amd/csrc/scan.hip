@@ -27,9 +27,9 @@
 
 namespace rs {
 
-// PAGE > 0 (bfloat16, full rows, a run that starts on a chunk boundary, PAGE a power of two from
-// 16 tokens to the chunk length): a wave's 16 (D = 128) or 32 (D = 64) tokens are whole pages or
-// an aligned part of one, so the page's channelwise min / max of the stored keys (App. A.1,
+// PAGE > 0 (full rows, a run that starts on a chunk boundary, PAGE a power of two from 16 tokens
+// to the chunk length): a wave's tokens (16 or 32 in bfloat16, 8 or 16 in float32, at 128 or 64
+// channels) are whole pages or an aligned part of one, so the page's channelwise min / max of the stored keys (App. A.1,
 // Quest) leave with the states -- in-lane over the lane's four tokens, shuffles over the row
 // groups of a page, and for pages longer than a wave's tokens a fold of the waves' bounds
 // through LDS -- and the keys need no second pass.
@@ -42,8 +42,7 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
 {
     constexpr bool META = PAGE > 0;
     constexpr int TW = (64 / (DS / 8)) * NT;  // tokens of a wave
-    static_assert(!META || (sizeof(ST) == 2 && DS == D && NT == 4 && PAGE >= 16 && (NW * TW) % (PAGE > 0 ? PAGE : 1) == 0),
-                  "pages tile the chunk");
+    static_assert(!META || (DS == D && PAGE >= 16 && (NW * TW) % (PAGE > 0 ? PAGE : 1) == 0), "pages tile the chunk");
     constexpr bool PG_LDS = META && PAGE > TW;  // a page spans several waves
     __shared__ float s_pg[PG_LDS ? NW : 1][2][PG_LDS ? D : 1];
     constexpr int LPR = DS / 8;      // lanes per row (of the slab)
@@ -252,15 +251,23 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
             R::store(k_cache + off, sk);
             R::store(v_cache + off, sv);
             if constexpr (META) {
-                const uint32_t w[4] = {pack_bf16x2(sk[0], sk[1]), pack_bf16x2(sk[2], sk[3]), pack_bf16x2(sk[4], sk[5]),
-                                       pack_bf16x2(sk[6], sk[7])};  // the bits just stored
+                float xs[8];  // the values just stored
+                if constexpr (sizeof(ST) == 2) {
+                    const uint32_t w[4] = {pack_bf16x2(sk[0], sk[1]), pack_bf16x2(sk[2], sk[3]), pack_bf16x2(sk[4], sk[5]),
+                                           pack_bf16x2(sk[6], sk[7])};
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const float x0 = __uint_as_float(w[c] << 16), x1 = __uint_as_float(w[c] & 0xffff0000u);
-                    plo[2 * c] = fminf(plo[2 * c], x0);
-                    phi[2 * c] = fmaxf(phi[2 * c], x0);
-                    plo[2 * c + 1] = fminf(plo[2 * c + 1], x1);
-                    phi[2 * c + 1] = fmaxf(phi[2 * c + 1], x1);
+                    for (int c = 0; c < 4; ++c) {
+                        xs[2 * c] = __uint_as_float(w[c] << 16);
+                        xs[2 * c + 1] = __uint_as_float(w[c] & 0xffff0000u);
+                    }
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) xs[c] = sk[c];
+                }
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    plo[c] = fminf(plo[c], xs[c]);
+                    phi[c] = fmaxf(phi[c], xs[c]);
                 }
             }
         }
@@ -429,8 +436,8 @@ bool scan_writes_meta(int dtype, int D, int P, int BH, long T_new, long t0)
     if (scan_uses_step_kernel(T_new)) return true;  // the step kernel keeps the touched page current
     const char *e = std::getenv("RATSPARSE_SCAN_META");
     if (e && std::atoi(e) == 0) return false;
-    const long chunk = scan_chunk_tokens(dtype, D);  // 128 tokens at D = 128, 256 at D = 64
-    return dtype == RS_BF16 && P >= 16 && P <= chunk && (P & (P - 1)) == 0 && !scan_uses_slabs(BH, T_new) && t0 % chunk == 0;
+    const long chunk = scan_chunk_tokens(dtype, D);  // bfloat16: 128 tokens at D = 128, 256 at D = 64; float32: half
+    return P >= 16 && P <= chunk && (P & (P - 1)) == 0 && !scan_uses_slabs(BH, T_new) && t0 % chunk == 0;
 }
 
 void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
@@ -470,8 +477,20 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
             else RS_SCAN(bf16, 64, 64, 256);
         }
     } else {
-        if (D == 128) slab ? RS_SCAN(float, 128, 32, 0) : RS_SCAN(float, 128, 128, 0);
-        else slab ? RS_SCAN(float, 64, 32, 0) : RS_SCAN(float, 64, 64, 0);
+        if (D == 128) {
+            if (slab) RS_SCAN(float, 128, 32, 0);
+            else if (!in_scan) RS_SCAN(float, 128, 128, 0);
+            else if (P == 16) RS_SCAN(float, 128, 128, 16);
+            else if (P == 32) RS_SCAN(float, 128, 128, 32);
+            else RS_SCAN(float, 128, 128, 64);
+        } else {
+            if (slab) RS_SCAN(float, 64, 32, 0);
+            else if (!in_scan) RS_SCAN(float, 64, 64, 0);
+            else if (P == 16) RS_SCAN(float, 64, 64, 16);
+            else if (P == 32) RS_SCAN(float, 64, 64, 32);
+            else if (P == 64) RS_SCAN(float, 64, 64, 64);
+            else RS_SCAN(float, 64, 64, 128);
+        }
     }
 #undef RS_SCAN
 }

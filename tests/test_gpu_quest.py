@@ -209,12 +209,13 @@ def test_scan_with_meta_equals_separate_page_meta(rs):
         ws.async_status()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("D", [128, 64])
 @pytest.mark.parametrize("P", [16, 32, 64, 128, 256])
 @pytest.mark.parametrize("in_scan", ["1", "0"])
-def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan, P, D):
-    """Long runs with the page metadata: where the scan kernel can (bfloat16, pages of 16
-    tokens up to the chunk length, a start on a chunk boundary) the bounds leave with the states, else the
+def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan, P, D, dtype):
+    """Long runs with the page metadata: where the scan kernel can (pages of 16 tokens up
+    to the chunk length, a start on a chunk boundary) the bounds leave with the states, else the
     touched pages are recomputed afterwards; runs of both kinds back to back, with ragged ends,
     must leave what one bulk pass over the final cache computes.  The knob switches the first
     kind off, so both paths see every run."""
@@ -228,7 +229,7 @@ def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan, P, D):
     k = synth.to_bf16_grid(r.standard_normal((B, H, T, D)).astype(np.float32))
     v = synth.to_bf16_grid(r.standard_normal((B, H, T, D)).astype(np.float32))
     g = (1 / (1 + np.exp(-(4.2 + 0.5 * r.standard_normal((B, H, T, D)))))).astype(np.float32)
-    dt = torch.bfloat16
+    dt = tdtype(dtype)
     s = rs.make_shape(B, H, H, D, Tcap, P, dt)
     kc = torch.zeros(B, H, Tcap, D, dtype=dt, device="cuda")
     vc = torch.zeros_like(kc)
@@ -237,7 +238,7 @@ def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan, P, D):
     meta = torch.zeros(B, H, Tcap // P, 2, D, dtype=dt, device="cuda")
     ws = rs.Workspace(rs.rat_scan_workspace_bytes(s, 3000))
     for t0, n in runs:
-        rs.rat_scan(s, to_dev(k[:, :, t0:t0 + n], "bf16"), to_dev(v[:, :, t0:t0 + n], "bf16"), to_dev(g[:, :, t0:t0 + n]),
+        rs.rat_scan(s, to_dev(k[:, :, t0:t0 + n], dtype), to_dev(v[:, :, t0:t0 + n], dtype), to_dev(g[:, :, t0:t0 + n]),
                     sk, sv, kc, vc, t0, n, ws, meta)
     want = torch.zeros_like(meta)
     rs.quest_page_meta(s, kc, want, 0, T)
