@@ -27,7 +27,7 @@
 
 namespace rs {
 
-// PAGE > 0 (full rows, a run that starts on a chunk boundary, PAGE a power of two from 16 tokens
+// PAGE > 0 (a run that starts on a chunk boundary, PAGE a power of two from 16 tokens
 // to the chunk length): a wave's tokens (16 or 32 in bfloat16, 8 or 16 in float32, at 128 or 64
 // channels) are whole pages or an aligned part of one, so the page's channelwise min / max of the stored keys (App. A.1,
 // Quest) leave with the states -- in-lane over the lane's four tokens, shuffles over the row
@@ -42,9 +42,9 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
 {
     constexpr bool META = PAGE > 0;
     constexpr int TW = (64 / (DS / 8)) * NT;  // tokens of a wave
-    static_assert(!META || (DS == D && PAGE >= 16 && (NW * TW) % (PAGE > 0 ? PAGE : 1) == 0), "pages tile the chunk");
+    static_assert(!META || (PAGE >= 16 && (NW * TW) % (PAGE > 0 ? PAGE : 1) == 0), "pages tile the chunk");
     constexpr bool PG_LDS = META && PAGE > TW;  // a page spans several waves
-    __shared__ float s_pg[PG_LDS ? NW : 1][2][PG_LDS ? D : 1];
+    __shared__ float s_pg[PG_LDS ? NW : 1][2][PG_LDS ? DS : 1];
     constexpr int LPR = DS / 8;      // lanes per row (of the slab)
     constexpr int RPW = 64 / LPR;    // row groups per wave
     constexpr int CHUNK = NW * RPW * NT;
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
             const long tp = (long)j * CHUNK + (long)wave * TW + (long)(rg / RGP) * PAGE;  // the page's first token
             if (tp < T_new && rg % RGP < 2) {
                 const long page = (t0 + tp) / PAGE;
-                ST *mrow = meta + (((long)bh * (Tcap / PAGE) + page) * 2) * D + c0;
+                ST *mrow = meta + (((long)bh * (Tcap / PAGE) + page) * 2) * D + ch0 + c0;
                 if (rg % RGP == 0) R::store(mrow, plo);
                 else R::store(mrow + D, phi);
             }
@@ -322,7 +322,7 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
                         x[c] = rg == 0 ? fminf(x[c], y) : fmaxf(x[c], y);
                     }
                 const long page = (t0 + tp) / PAGE;
-                R::store(meta + (((long)bh * (Tcap / PAGE) + page) * 2 + rg) * D + c0, x);
+                R::store(meta + (((long)bh * (Tcap / PAGE) + page) * 2 + rg) * D + ch0 + c0, x);
             }
         }
     }
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(256) void rat_step_kernel(
     state_v[e] = sv;
 }
 
-template <typename ST, int D, int DS, int PAGE>
+template <typename ST, int D, int DS, int PAGE_ARG>
 static int launch_scan(const void *k, const void *v, const float *g, float *state_k,
                        float *state_v, void *k_cache, void *v_cache, int BH, long T_new, long t0,
                        long Tcap, uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit,
@@ -391,6 +391,7 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
     constexpr int NT = sizeof(ST) == 2 ? 4 : 2;
     constexpr int NW = 8;
     constexpr int CHUNK = NW * (64 / (DS / 8)) * NT;
+    constexpr int PAGE = (PAGE_ARG <= CHUNK) ? PAGE_ARG : 0;  // larger pages never get here with the bounds asked for
     const int n_chunks = (int)((T_new + CHUNK - 1) / CHUNK);
     long grid = (long)BH * (D / DS) * n_chunks;
     if (n_chunks > 1) {
@@ -436,8 +437,9 @@ bool scan_writes_meta(int dtype, int D, int P, int BH, long T_new, long t0)
     if (scan_uses_step_kernel(T_new)) return true;  // the step kernel keeps the touched page current
     const char *e = std::getenv("RATSPARSE_SCAN_META");
     if (e && std::atoi(e) == 0) return false;
-    const long chunk = scan_chunk_tokens(dtype, D);  // bfloat16: 128 tokens at D = 128, 256 at D = 64; float32: half
-    return P >= 16 && P <= chunk && (P & (P - 1)) == 0 && !scan_uses_slabs(BH, T_new) && t0 % chunk == 0;
+    // chunk of the form in use: bfloat16 128 tokens at D = 128, 256 at D = 64 (float32: half); 32-channel slabs: D / 32 times that
+    const long chunk = (long)scan_chunk_tokens(dtype, D) * (scan_uses_slabs(BH, T_new) ? D / 32 : 1);
+    return P >= 16 && P <= chunk && (P & (P - 1)) == 0 && t0 % chunk == 0;
 }
 
 void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
@@ -458,40 +460,36 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
     }
     const bool slab = scan_uses_slabs(BH, T_new);
 #define RS_SCAN(ST, DD, DSS, MM) launch_scan<ST, DD, DSS, MM>(k, v, g, state_k, state_v, k_cache, v_cache, BH, T_new, t0, Tcap, ctrl, rec, tag, spin_limit, meta, stream)
-    const bool in_scan = !slab && meta && scan_writes_meta(dtype, D, P, BH, T_new, t0);
+    const bool in_scan = meta && scan_writes_meta(dtype, D, P, BH, T_new, t0);
+    // page sizes up to 512 tokens have their own instantiation where they tile the form's chunk
+#define RS_SCAN_P(ST, DD, DSS)                           \
+    do {                                                 \
+        if (!in_scan) RS_SCAN(ST, DD, DSS, 0);           \
+        else if (P == 16) RS_SCAN(ST, DD, DSS, 16);      \
+        else if (P == 32) RS_SCAN(ST, DD, DSS, 32);      \
+        else if (P == 64) RS_SCAN(ST, DD, DSS, 64);      \
+        else if (P == 128) RS_SCAN(ST, DD, DSS, 128);    \
+        else if (P == 256) RS_SCAN(ST, DD, DSS, 256);    \
+        else RS_SCAN(ST, DD, DSS, 512);                  \
+    } while (0)
     if (dtype == RS_BF16) {
         if (D == 128) {
-            if (slab) RS_SCAN(bf16, 128, 32, 0);
-            else if (!in_scan) RS_SCAN(bf16, 128, 128, 0);
-            else if (P == 16) RS_SCAN(bf16, 128, 128, 16);
-            else if (P == 32) RS_SCAN(bf16, 128, 128, 32);
-            else if (P == 64) RS_SCAN(bf16, 128, 128, 64);
-            else RS_SCAN(bf16, 128, 128, 128);
+            if (slab) RS_SCAN_P(bf16, 128, 32);
+            else RS_SCAN_P(bf16, 128, 128);
         } else {
-            if (slab) RS_SCAN(bf16, 64, 32, 0);
-            else if (!in_scan) RS_SCAN(bf16, 64, 64, 0);
-            else if (P == 16) RS_SCAN(bf16, 64, 64, 16);
-            else if (P == 32) RS_SCAN(bf16, 64, 64, 32);
-            else if (P == 64) RS_SCAN(bf16, 64, 64, 64);
-            else if (P == 128) RS_SCAN(bf16, 64, 64, 128);
-            else RS_SCAN(bf16, 64, 64, 256);
+            if (slab) RS_SCAN_P(bf16, 64, 32);
+            else RS_SCAN_P(bf16, 64, 64);
         }
     } else {
         if (D == 128) {
-            if (slab) RS_SCAN(float, 128, 32, 0);
-            else if (!in_scan) RS_SCAN(float, 128, 128, 0);
-            else if (P == 16) RS_SCAN(float, 128, 128, 16);
-            else if (P == 32) RS_SCAN(float, 128, 128, 32);
-            else RS_SCAN(float, 128, 128, 64);
+            if (slab) RS_SCAN_P(float, 128, 32);
+            else RS_SCAN_P(float, 128, 128);
         } else {
-            if (slab) RS_SCAN(float, 64, 32, 0);
-            else if (!in_scan) RS_SCAN(float, 64, 64, 0);
-            else if (P == 16) RS_SCAN(float, 64, 64, 16);
-            else if (P == 32) RS_SCAN(float, 64, 64, 32);
-            else if (P == 64) RS_SCAN(float, 64, 64, 64);
-            else RS_SCAN(float, 64, 64, 128);
+            if (slab) RS_SCAN_P(float, 64, 32);
+            else RS_SCAN_P(float, 64, 64);
         }
     }
+#undef RS_SCAN_P
 #undef RS_SCAN
 }
 

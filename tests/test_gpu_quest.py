@@ -209,22 +209,24 @@ def test_scan_with_meta_equals_separate_page_meta(rs):
         ws.async_status()
 
 
+@pytest.mark.parametrize("slab", ["0", "1"])  # full rows, or 32-channel slabs (chunks four / two times as long)
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("D", [128, 64])
-@pytest.mark.parametrize("P", [16, 32, 64, 128, 256])
+@pytest.mark.parametrize("P", [16, 32, 64, 128, 256, 512])
 @pytest.mark.parametrize("in_scan", ["1", "0"])
-def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan, P, D, dtype):
+def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan, P, D, dtype, slab):
     """Long runs with the page metadata: where the scan kernel can (pages of 16 tokens up
     to the chunk length, a start on a chunk boundary) the bounds leave with the states, else the
     touched pages are recomputed afterwards; runs of both kinds back to back, with ragged ends,
     must leave what one bulk pass over the final cache computes.  The knob switches the first
     kind off, so both paths see every run."""
     monkeypatch.setenv("RATSPARSE_SCAN_META", in_scan)
+    monkeypatch.setenv("RATSPARSE_SCAN_SLAB", slab)
     B, H = 2, 20  # 40 (batch, head) pairs: full-row chunks (128 tokens at 128 channels, 256 at 64)
     # (t0, T_new): aligned; aligned and a single chunk; unaligned; unaligned; unaligned and long
-    runs = [(0, 256), (256, 100), (356, 677), (1033, 200), (1233, 3000)]
+    runs = [(0, 256), (256, 100), (356, 156), (512, 521), (1033, 200), (1233, 3000)]  # 512: aligned for every form
     T = 4233
-    Tcap = 4352  # a multiple of every page size
+    Tcap = 4608  # a multiple of every page size
     r = np.random.default_rng(17)
     k = synth.to_bf16_grid(r.standard_normal((B, H, T, D)).astype(np.float32))
     v = synth.to_bf16_grid(r.standard_normal((B, H, T, D)).astype(np.float32))
