@@ -255,6 +255,19 @@ int32_t snapkv_compress(const rs_shape *s, const void *q_win, const void *k_cach
                         int64_t Tcap_out, int32_t *idx_out, float *votes_out, void *ws,
                         size_t ws_bytes, void *stream);
 
+/* The same with the window rows' log-sum-exp handed in (an option, not in the paper): the
+ * votes need each window row's softmax normaliser over all the keys it sees, which
+ * snapkv_compress gets from a first sweep over the keys.  A caller that has just run the
+ * prefill attention of those rows already holds it (lse_out of sparse_attn_prefill, rows
+ * T-W .. T-1, same queries and scale); with it the keys are swept once instead of twice.
+ *   lse_win [B, Hq, W] float32: log sum_{i <= T-W+w} exp(scale * q_w . k_i), natural log
+ * Everything else as snapkv_compress, same workspace size. */
+int32_t snapkv_compress_lse(const rs_shape *s, const void *q_win, const void *k_cache,
+                            const void *v_cache, int64_t T, int32_t W, int32_t K_keep,
+                            int32_t pool_kernel, float scale, const float *lse_win, void *kc_out,
+                            void *vc_out, int64_t Tcap_out, int32_t *idx_out, float *votes_out,
+                            void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

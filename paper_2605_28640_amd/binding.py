@@ -62,6 +62,8 @@ SIGNATURES = {
     "snapkv_compress_workspace_bytes": (_sz, [_shp, _i64, _i32]),
     "snapkv_compress": (_i32, [_shp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _f32, _vp, _vp, _i64,
                                _vp, _vp, _vp, _sz, _vp]),
+    "snapkv_compress_lse": (_i32, [_shp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _i64,
+                                   _vp, _vp, _vp, _sz, _vp]),
 }
 
 
@@ -230,3 +232,10 @@ def snapkv_compress(s, q_win, k_cache, v_cache, T, W, K_keep, pool_kernel, scale
     _check(load().snapkv_compress(ctypes.byref(s), _ptr(q_win), _ptr(k_cache), _ptr(v_cache), T, W,
                                   K_keep, pool_kernel, scale, _ptr(kc_out), _ptr(vc_out), Tcap_out,
                                   _ptr(idx_out), _ptr(votes_out), ws.ptr, ws.nbytes, _stream()))
+
+
+def snapkv_compress_lse(s, q_win, k_cache, v_cache, T, W, K_keep, pool_kernel, scale, lse_win, kc_out, vc_out,
+                        Tcap_out, idx_out, votes_out, ws):
+    _check(load().snapkv_compress_lse(ctypes.byref(s), _ptr(q_win), _ptr(k_cache), _ptr(v_cache), T, W,
+                                      K_keep, pool_kernel, scale, _ptr(lse_win), _ptr(kc_out), _ptr(vc_out),
+                                      Tcap_out, _ptr(idx_out), _ptr(votes_out), ws.ptr, ws.nbytes, _stream()))

@@ -43,7 +43,7 @@ int prefill_dispatch(const rs_shape *s, const void *q, const void *k_cache, cons
 size_t snapkv_ws_bytes(const rs_shape *s, long T, int W);
 int snapkv_dispatch(const rs_shape *s, const void *q_win, const void *k_cache, const void *v_cache, long T,
                     int W, int K_keep, int pool_kernel, float scale, void *kc_out, void *vc_out, long Tcap_out,
-                    int32_t *idx_out, float *votes_out, char *ws, hipStream_t stream);
+                    int32_t *idx_out, float *votes_out, const float *lse_in, char *ws, hipStream_t stream);
 
 __global__ void fill_zero_kernel(uint32_t *p, long n)
 {
@@ -635,14 +635,15 @@ size_t snapkv_compress_workspace_bytes(const rs_shape *s, int64_t T, int32_t W)
     return snapkv_ws_bytes(s, T, W);
 }
 
-int32_t snapkv_compress(const rs_shape *s, const void *q_win, const void *k_cache, const void *v_cache, int64_t T,
-                        int32_t W, int32_t K_keep, int32_t pool_kernel, float scale, void *kc_out, void *vc_out,
-                        int64_t Tcap_out, int32_t *idx_out, float *votes_out, void *ws, size_t ws_bytes,
-                        void *stream)
+static int32_t snapkv_impl(const rs_shape *s, const void *q_win, const void *k_cache, const void *v_cache, int64_t T,
+                           int32_t W, int32_t K_keep, int32_t pool_kernel, float scale, const float *lse_win,
+                           bool need_lse, void *kc_out, void *vc_out, int64_t Tcap_out, int32_t *idx_out,
+                           float *votes_out, void *ws, size_t ws_bytes, void *stream)
 {
     int st = check_shape(s, false);
     if (st != RS_OK) return st;
     if (!q_win || !k_cache || !v_cache || !kc_out || !vc_out || !idx_out) return RS_INVALID_ARG;
+    if (need_lse && (!lse_win || !aligned16(lse_win))) return RS_INVALID_ARG;
     if (!aligned16(q_win) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(kc_out) ||
         !aligned16(vc_out) || !aligned16(idx_out) || (votes_out && !aligned16(votes_out)))
         return RS_INVALID_ARG;
@@ -651,7 +652,25 @@ int32_t snapkv_compress(const rs_shape *s, const void *q_win, const void *k_cach
     if (pool_kernel < 1 || pool_kernel % 2 == 0 || pool_kernel > 63) return RS_INVALID_ARG;
     if (!ws || !aligned16(ws) || ws_bytes < snapkv_ws_bytes(s, T, W)) return RS_WORKSPACE_TOO_SMALL;
     return snapkv_dispatch(s, q_win, k_cache, v_cache, T, W, K_keep, pool_kernel, scale, kc_out, vc_out, Tcap_out,
-                           idx_out, votes_out, (char *)ws, (hipStream_t)stream);
+                           idx_out, votes_out, lse_win, (char *)ws, (hipStream_t)stream);
+}
+
+int32_t snapkv_compress(const rs_shape *s, const void *q_win, const void *k_cache, const void *v_cache, int64_t T,
+                        int32_t W, int32_t K_keep, int32_t pool_kernel, float scale, void *kc_out, void *vc_out,
+                        int64_t Tcap_out, int32_t *idx_out, float *votes_out, void *ws, size_t ws_bytes,
+                        void *stream)
+{
+    return snapkv_impl(s, q_win, k_cache, v_cache, T, W, K_keep, pool_kernel, scale, nullptr, false, kc_out, vc_out,
+                       Tcap_out, idx_out, votes_out, ws, ws_bytes, stream);
+}
+
+int32_t snapkv_compress_lse(const rs_shape *s, const void *q_win, const void *k_cache, const void *v_cache, int64_t T,
+                            int32_t W, int32_t K_keep, int32_t pool_kernel, float scale, const float *lse_win,
+                            void *kc_out, void *vc_out, int64_t Tcap_out, int32_t *idx_out, float *votes_out,
+                            void *ws, size_t ws_bytes, void *stream)
+{
+    return snapkv_impl(s, q_win, k_cache, v_cache, T, W, K_keep, pool_kernel, scale, lse_win, true, kc_out, vc_out,
+                       Tcap_out, idx_out, votes_out, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

@@ -648,7 +648,7 @@ size_t snapkv_ws_bytes(const rs_shape *s, long T, int W) { return (T > W) ? snap
 
 int snapkv_dispatch(const rs_shape *s, const void *q_win, const void *k_cache, const void *v_cache, long T, int W,
                     int K_keep, int pool_kernel, float scale, void *kc_out, void *vc_out, long Tcap_out,
-                    int32_t *idx_out, float *votes_out, char *ws, hipStream_t stream)
+                    int32_t *idx_out, float *votes_out, const float *lse_in, char *ws, hipStream_t stream)
 {
     if (s->dtype != RS_BF16) return RS_UNSUPPORTED;  // the matrix-core path takes bf16 operands
     const SnapLayout Ly = snap_layout(s, T, W);
@@ -659,12 +659,18 @@ int snapkv_dispatch(const rs_shape *s, const void *q_win, const void *k_cache, c
     float *pooled = votes_out ? votes_out : (float *)(ws + Ly.off_pooled);
     const dim3 grid((unsigned)Ly.n_chunks, (unsigned)BK);
     const bf16 *qw = (const bf16 *)q_win, *kc = (const bf16 *)k_cache;
-    if (s->D == 128)
-        snapkv_stats_kernel<128><<<grid, 256, 0, stream>>>(qw, kc, stats, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale, Ly.keys_per_wg);
-    else
-        snapkv_stats_kernel<64><<<grid, 256, 0, stream>>>(qw, kc, stats, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale, Ly.keys_per_wg);
-    const long rows_total = BK * Ly.R;
-    snapkv_lse_kernel<<<(unsigned)((rows_total + 3) / 4), 256, 0, stream>>>(stats, lse, Ly.R, Ly.n_chunks, rows_total);
+    // the rows' log-sum-exp over all visible keys: handed in by the caller (the prefill attention of
+    // the window rows has it), or from a first sweep over the keys
+    if (lse_in) {
+        lse = const_cast<float *>(lse_in);  // [B, Hq, W] is [B * Hkv][G * W]: only read
+    } else {
+        if (s->D == 128)
+            snapkv_stats_kernel<128><<<grid, 256, 0, stream>>>(qw, kc, stats, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale, Ly.keys_per_wg);
+        else
+            snapkv_stats_kernel<64><<<grid, 256, 0, stream>>>(qw, kc, stats, s->Hq, s->Hkv, T, s->Tcap, W, Ly.n_chunks, scale, Ly.keys_per_wg);
+        const long rows_total = BK * Ly.R;
+        snapkv_lse_kernel<<<(unsigned)((rows_total + 3) / 4), 256, 0, stream>>>(stats, lse, Ly.R, Ly.n_chunks, rows_total);
+    }
     // votes exist for prefix keys only: chunks that start past the prefix are not needed
     const dim3 grid2((unsigned)((L + Ly.keys_per_wg - 1) / Ly.keys_per_wg), (unsigned)BK);
     if (s->D == 128)

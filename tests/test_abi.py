@@ -110,6 +110,12 @@ def test_every_entry_point_rejects_bad_arguments_before_touching_the_gpu():
     assert lib.snapkv_compress(sp, A, A, A, 256, 32, 64, 7, 0.1, A, A, 64, A, None, A, big, None) == 1    # output too short
     assert lib.snapkv_compress(sp, A, A, A, 256, 32, 64, 7, 0.1, A, A, 128, A, None, A, 16, None) == 3
 
+    # snapkv_compress_lse(..., scale, lse_win, kc_out, ...): the log-sum-exp is required
+    assert lib.snapkv_compress_lse(sp, A, A, A, 256, 32, 64, 7, 0.1, None, A, A, 128, A, None, A, big, None) == 1
+    assert lib.snapkv_compress_lse(sp, A, A, A, 256, 32, 64, 7, 0.1, A + 4, A, A, 128, A, None, A, big, None) == 1
+    assert lib.snapkv_compress_lse(sp, A, A, A, 256, 32, 64, 4, 0.1, A, A, A, 128, A, None, A, big, None) == 1
+    assert lib.snapkv_compress_lse(sp, A, A, A, 256, 32, 64, 7, 0.1, A, A, A, 128, A, None, A, 16, None) == 3
+
     # more pages than the selection's LDS keys hold
     huge = binding.make_shape(1, 1, 1, 64, 15361 * 16, 16, binding.RS_BF16)
     hp = ctypes.byref(huge)

@@ -100,6 +100,32 @@ def test_snapkv_compress_then_decode(rs, monkeypatch, case):
     assert torch.equal(idx2, idx) and torch.equal(votes2, votes)
     assert torch.equal(kco2, kco) and torch.equal(vco2, vco)
 
+    # the same with the window rows' log-sum-exp handed in (one sweep over the keys instead of two):
+    # from the oracle's causal attention of those rows, and from the GPU's own dense prefill
+    q_full = np.zeros((w.B, w.Hq, T, w.D), dtype=np.float32)
+    q_full[:, :, L:] = qw
+    _, olse = oracle.sparse_attn_prefill(q_full, kc, vc, T, 16, scale, None, t_begin=L, t_end=T)
+    glse = torch.zeros(w.B, w.Hq, T, device="cuda")
+    gout = torch.zeros(w.B, w.Hq, T, w.D, dtype=torch.bfloat16, device="cuda")
+    wsp = rs.Workspace(rs.sparse_attn_prefill_workspace_bytes(s, T, 16, 0))
+    rs.sparse_attn_prefill(s, to_dev(q_full, "bf16"), to_dev(kc, "bf16"), to_dev(vc, "bf16"), T, 16, scale, None, 0,
+                           gout, glse, wsp)
+    for name, lse_win, band in (("oracle", to_dev(olse.astype(np.float32)), 1e-4),
+                                ("prefill", glse[:, :, L:].contiguous(), 2e-3)):
+        kco3, vco3 = torch.zeros_like(kco), torch.zeros_like(vco)
+        idx3, votes3 = torch.full_like(idx, -5), torch.zeros_like(votes)
+        rs.snapkv_compress_lse(s, to_dev(qw, "bf16"), to_dev(kc, "bf16"), to_dev(vc, "bf16"), T, W, K_keep, pool, scale,
+                               lse_win, kco3, vco3, Tco, idx3, votes3, ws)
+        np.testing.assert_allclose(to_np(votes3), opooled, rtol=2e-4 if name == "oracle" else 5e-3, atol=1e-9)
+        g3 = to_np(idx3)
+        for b in range(w.B):
+            for h in range(w.Hkv):
+                ok, why = topk_set_ok(opooled[b, h], np.zeros(L, bool), K_keep, g3[b, h], band=band)
+                assert ok, (name, b, h, why)
+                rows = np.concatenate([g3[b, h], np.arange(L, T)])
+                np.testing.assert_array_equal(to_np(kco3)[b, h, :K_keep + W], kc[b, h, rows])
+    wsp.async_status()
+
     # a decode step over the compressed cache: append through rat_scan, then dense attention
     sc = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tco, 16, torch.bfloat16)
     kd, vd, gd, qd = synth.decode_step(w, 0)
