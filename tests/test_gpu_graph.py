@@ -60,7 +60,8 @@ def test_prefill_path_replays_from_a_captured_graph(rs, monkeypatch, form):
     ws.async_status()
 
 
-def test_snapkv_compress_replays_from_a_captured_graph(rs):
+@pytest.mark.parametrize("with_lse", [False, True])  # snapkv_compress / snapkv_compress_lse
+def test_snapkv_compress_replays_from_a_captured_graph(rs, with_lse):
     B, Hq, Hkv, D, T, W, keep = 1, 8, 2, 128, 3000, 32, 400
     dt = torch.bfloat16
     Tcap = 3008
@@ -76,8 +77,14 @@ def test_snapkv_compress_replays_from_a_captured_graph(rs):
     ws = rs.Workspace(rs.snapkv_compress_workspace_bytes(s, T, W))
     scale = 1.0 / np.sqrt(D)
 
+    # For the replay check any finite normaliser will do: the votes only have to come out the same.
+    lse = torch.randn(B, Hq, W, device="cuda", generator=gen) + 8.0
+
     def run():
-        rs.snapkv_compress(s, qw, kc, vc, T, W, keep, 7, scale, kco, vco, Tco, idx, None, ws)
+        if with_lse:
+            rs.snapkv_compress_lse(s, qw, kc, vc, T, W, keep, 7, scale, lse, kco, vco, Tco, idx, None, ws)
+        else:
+            rs.snapkv_compress(s, qw, kc, vc, T, W, keep, 7, scale, kco, vco, Tco, idx, None, ws)
 
     run()
     torch.cuda.synchronize()
