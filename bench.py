@@ -407,6 +407,13 @@ def main():
         paper["snapkv_W64_keep512_us"] = round(1e3 * timed(
             lambda: rs.snapkv_compress(sp, qwp, kcp, vcp, Tp, 64, keepp, 7, scp, kcop, vcop, keepp + 128, idxs, None,
                                        wsp), reps=10), 2)
+        # the same with the window rows' log-sum-exp taken from the dense prefill (one key sweep)
+        lsep = torch.zeros(Bp, Hp, Tp, device=dev)
+        rs.sparse_attn_prefill(sp, qp, kcp, vcp, Tp, 64, scp, None, 0, outpp, lsep, wsp)
+        lsew = lsep[:, :, -64:].contiguous()
+        paper["snapkv_W64_keep512_with_prefill_lse_us"] = round(1e3 * timed(
+            lambda: rs.snapkv_compress_lse(sp, qwp, kcp, vcp, Tp, 64, keepp, 7, scp, lsew, kcop, vcop, keepp + 128,
+                                           idxs, None, wsp), reps=10), 2)
         wsp.async_status()
         extra["paper_settings_T4096"] = paper
         del kcp, vcp, qp, outpp, idxp, kcop, vcop, wsp

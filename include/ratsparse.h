@@ -261,7 +261,10 @@ int32_t snapkv_compress(const rs_shape *s, const void *q_win, const void *k_cach
  * prefill attention of those rows already holds it (lse_out of sparse_attn_prefill, rows
  * T-W .. T-1, same queries and scale); with it the keys are swept once instead of twice.
  *   lse_win [B, Hq, W] float32: log sum_{i <= T-W+w} exp(scale * q_w . k_i), natural log
- * Everything else as snapkv_compress, same workspace size. */
+ * The values are taken on trust (device memory cannot be checked at the call): it has to
+ * be the dense causal normaliser over this very k_cache, so the lse_out of a routed prefill
+ * (listed blocks only) does not qualify, and a wrong or non-finite entry gives wrong votes
+ * for that row, no error.  Everything else as snapkv_compress, same workspace size. */
 int32_t snapkv_compress_lse(const rs_shape *s, const void *q_win, const void *k_cache,
                             const void *v_cache, int64_t T, int32_t W, int32_t K_keep,
                             int32_t pool_kernel, float scale, const float *lse_win, void *kc_out,
