@@ -188,6 +188,25 @@ def test_c5_snapkv_128k(rs):
     rows = np.concatenate([got, np.arange(T - W, T)])
     np.testing.assert_array_equal(to_np(kco[0, kvh, :K_keep + W]), hk[0, 0, rows])
     np.testing.assert_array_equal(to_np(vco[0, kvh, :K_keep + W]), hv[0, 0, rows])
+    # the one-sweep form: the window rows' log-sum-exp handed in (here from float32 torch ops on
+    # the same cache; a prefill would supply it), against the same oracle votes
+    qd_ = to_dev(qw, "bf16").float().view(w.B, w.Hkv, G * W, w.D)
+    logits = torch.matmul(qd_, kc[:, :, :T].float().transpose(2, 3)).view(w.B, w.Hq, W, T) * scale
+    future = torch.arange(T, device="cuda")[None, :] > (T - W + torch.arange(W, device="cuda"))[:, None]
+    lse = torch.logsumexp(logits.masked_fill(future, float("-inf")), dim=-1).contiguous()
+    del logits
+    kco2, vco2, idx2, votes2 = torch.zeros_like(kco), torch.zeros_like(vco), torch.zeros_like(idx), torch.zeros_like(votes)
+    rs.snapkv_compress_lse(s, to_dev(qw, "bf16"), kc, vc, T, W, K_keep, w.pool, scale, lse, kco2, vco2, Tco, idx2,
+                           votes2, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(to_np(votes2[0, kvh]), op[0, 0], rtol=3e-4, atol=1e-10)
+    got2 = to_np(idx2[0, kvh])
+    ok, why = topk_set_ok(op[0, 0], np.zeros(T - W, bool), K_keep, got2)
+    assert ok, why
+    rows2 = np.concatenate([got2, np.arange(T - W, T)])
+    np.testing.assert_array_equal(to_np(kco2[0, kvh, :K_keep + W]), hk[0, 0, rows2])
+    np.testing.assert_array_equal(to_np(vco2[0, kvh, :K_keep + W]), hv[0, 0, rows2])
+    del kco2, vco2
     # dense decode over the compressed cache, a few steps
     sc = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tco, 16, torch.bfloat16)
     sk2 = sk.clone()
