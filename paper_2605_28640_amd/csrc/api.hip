@@ -192,7 +192,9 @@ static long fused_setup(FusedParams &prm, const rs_shape *s, const DecodeLayout 
     if (fine > kMaxAttSplits) fine = kMaxAttSplits;
     if (fine > K) fine = K;
     prm.S_att_fine = fine < prm.S_att ? prm.S_att : fine;
-    prm.units_fine = (int)(units * env_int("RATSPARSE_FUSED_FINE_PCT", 6) / 100);
+    int fine_pct = env_int("RATSPARSE_FUSED_FINE_PCT", 6);
+    fine_pct = fine_pct < 0 ? 0 : fine_pct > 100 ? 100 : fine_pct;
+    prm.units_fine = (int)(units * fine_pct / 100);
     prm.S_max = kMaxAttSplits;
     prm.reverse = env_int("RATSPARSE_FUSED_PINGPONG", 1) ? (int)(T_valid & 1) : 0;
     prm.nt_kv = env_int("RATSPARSE_FUSED_NT", 1);  // bit 0: K/V pages, bit 1: page metadata
@@ -202,6 +204,7 @@ static long fused_setup(FusedParams &prm, const rs_shape *s, const DecodeLayout 
     const long items = units * (prm.S_score + prm.S_att) + (long)prm.units_fine * (prm.S_att_fine - prm.S_att);
     long grid = env_int("RATSPARSE_FUSED_GRID", 2 * num_cus());
     if (grid > items) grid = items;
+    if (grid < 1) grid = 1;
     return grid;
 }
 

@@ -404,7 +404,9 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
             if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         }
         const char *e = std::getenv("RATSPARSE_SCAN_GRID");
-        const long want = e ? std::atol(e) : (long)per_cu * cus;
+        long want = e ? std::atol(e) : (long)per_cu * cus;
+        if (want < 1) want = 1;
+        if (want > (long)per_cu * cus) want = (long)per_cu * cus;  // the knob only narrows: every workgroup stays resident
         if (grid > want) grid = want;
     }
     rat_scan_chunk_kernel<ST, D, DS, NT, NW, PAGE><<<dim3((unsigned)grid), dim3(NW * 64), 0, stream>>>(
