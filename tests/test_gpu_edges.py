@@ -172,3 +172,48 @@ def test_snapkv_edges(rs, case):
             np.testing.assert_array_equal(to_np(vco)[b, h, :K_keep + W], vc[b, h, src])
     torch.cuda.synchronize()
     ws.async_status()
+
+
+def test_out_of_range_knob_values_are_clamped(rs, monkeypatch):
+    """The tuning knobs are read at dispatch; values outside their range are clamped to it, so the
+    work split changes at most: the scan (whose arithmetic does not depend on the grid) stays bit-equal,
+    the persistent decode launch picks the same pages and agrees to the rounding of a different merge order."""
+    B, H, D, T, P, K = 2, 4, 128, 2048, 16, 16
+    dt = torch.bfloat16
+    gen = torch.Generator(device="cuda").manual_seed(23)
+    k = torch.randn(B, H, T, D, device="cuda", generator=gen).to(dt)
+    v = torch.randn(B, H, T, D, device="cuda", generator=gen).to(dt)
+    g = torch.sigmoid(4.2 + 0.5 * torch.randn(B, H, T, D, device="cuda", generator=gen))
+    q = torch.randn(B, H, D, device="cuda", generator=gen).to(dt)
+    s = rs.make_shape(B, H, H, D, T, P, dt)
+    monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0")  # the persistent launch, where the decode knobs apply
+    monkeypatch.setenv("RATSPARSE_FUSED_ONE_WG", "0")
+
+    def run():
+        kc = torch.zeros(B, H, T, D, dtype=dt, device="cuda")
+        vc = torch.zeros_like(kc)
+        sk = torch.zeros(B, H, D, device="cuda")
+        sv = torch.zeros_like(sk)
+        meta = torch.zeros(B, H, T // P, 2, D, dtype=dt, device="cuda")
+        ws = rs.Workspace(max(rs.rat_scan_workspace_bytes(s, T), rs.sparse_attn_decode_workspace_bytes(s, T, K)))
+        rs.rat_scan(s, k, v, g, sk, sv, kc, vc, 0, T, ws, meta)
+        out = torch.zeros(B, H, D, dtype=dt, device="cuda")
+        idx = torch.zeros(B, H, K, dtype=torch.int32, device="cuda")
+        rs.sparse_attn_decode(s, q, kc, vc, T, 1.0 / np.sqrt(D), None, K, meta, 1, 1, out, None, idx, ws)
+        torch.cuda.synchronize()
+        ws.async_status()
+        return kc, vc, sk, sv, meta, idx, out
+
+    want = run()
+    for knobs in ({"RATSPARSE_SCAN_GRID": "-1", "RATSPARSE_FUSED_GRID": "-3", "RATSPARSE_FUSED_FINE_PCT": "500"},
+                  {"RATSPARSE_SCAN_GRID": "1000000000", "RATSPARSE_FUSED_GRID": "0", "RATSPARSE_FUSED_FINE_PCT": "-7",
+                   "RATSPARSE_META_SPW": "1000000"}):
+        say("knobs", knobs)
+        for name, value in knobs.items():
+            monkeypatch.setenv(name, value)
+        got = run()
+        for a, b in zip(got[:6], want[:6]):
+            assert torch.equal(a, b)
+        assert torch.allclose(got[6].float(), want[6].float(), rtol=2e-2, atol=2e-2)
+        for name in knobs:
+            monkeypatch.delenv(name)
