@@ -28,7 +28,18 @@
  *   - Return value: RS_OK or an error code below.  Nothing is printed or thrown.
  *     A kernel-side failure of a bounded wait is recorded in the workspace and
  *     reported by ratsparse_async_status().
- *   - Outputs must not alias inputs.
+ *   - Outputs must not alias inputs, with one exception: rat_scan may run in place
+ *     (k_cache == k and v_cache == v) when the two layouts coincide, i.e. t0 == 0 and
+ *     T_new == Tcap; every row is read before it is overwritten.
+ *   - Tuning knobs: a handful of RATSPARSE_* environment variables (work splits, grid sizes,
+ *     forced kernel forms) are read once per process, under std::call_once, on the first
+ *     call that needs one; after that no entry point touches the environment, and calls
+ *     from several host threads see one consistent table.  Unset = the measured defaults.
+ *     Changing the environment later has no effect (ratsparse_debug_reload_knobs is the
+ *     test hook that re-reads it; do not call it while other threads are inside the library).
+ *   - Threads: entry points may be called from several host threads as long as each call
+ *     has its own workspace and stream; the only process-wide host state is the call-tag
+ *     counter and the spin limit (both atomics) and the knob table above.
  *   - Stream capture: quest_page_meta, moba_select_prefill, sparse_attn_prefill and
  *     snapkv_compress keep no per-call state on the host and may be captured into a
  *     HIP graph and replayed.  rat_scan, quest_select_decode and sparse_attn_decode (and
@@ -89,6 +100,9 @@ int32_t ratsparse_probe_read(const void *src, size_t bytes, void *sink, void *st
  * default is 1 << 22).  With 0 a kernel that would have to wait gives up at once, exits
  * normally and records RS_ASYNC_TIMEOUT: the error path can be tested without a hang. */
 void ratsparse_debug_set_spin_limit(int32_t polls);
+
+/* Test hook: read the RATSPARSE_* tuning variables again (they are read once per process). */
+void ratsparse_debug_reload_knobs(void);
 
 /* ---- Exponentially decaying memory: Sec. 2.1, Eq. 1 --------------------------------
  * For every (batch, KV head, channel):  s_t = g_t * s_{t-1} + (1 - g_t) * x_t  for the
@@ -155,7 +169,7 @@ int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache
                            void *ws, size_t ws_bytes, void *stream);
 
 /* ---- Group-shared Quest selection (an option for grouped-query attention) --------------
- * Not in the paper, which selects per query head (Sec. 3 defines the selected set per head);
+ * Not in the paper, which selects per query head (Sec. 2.2 and 2.3 define the selected set per head);
  * offered for Hq / Hkv in {2, 4, 8} so that the query heads of a KV head share one page set:
  * Eq. 3 with the score of a page summed over the group,
  *   score_p = sum_{h in group} sum_c max(q_{h,c} * min_{p,c}, q_{h,c} * max_{p,c}),
@@ -178,7 +192,7 @@ int32_t sparse_attn_decode_group(const rs_shape *s, const void *q, const void *k
                                  int32_t *idx_out, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- One decode step whose length lives on the device (replayable) --------------------
- * The decode loop of Sec. 3 with Quest (App. A.1): append token T of the gated cache
+ * The decode loop with Quest (Sec. 2.2; App. A.1): append token T of the gated cache
  * (Eq. 1 step, as rat_scan with T_new = 1 and meta), then select K pages (Eq. 3) and
  * attend them (Eq. 4) over the T + 1 stored tokens, as sparse_attn_decode's fused mode.
  * T is not an argument: it is a 64-bit word of the workspace's control block, read by the
@@ -192,8 +206,11 @@ int32_t sparse_attn_decode_group(const rs_shape *s, const void *q, const void *k
  *   (<= Tcap).  Per query head; select-then-attend as one launch (the persistent form, or one
  *   workgroup per (batch, head) for short contexts: chosen by shape at T_max).
  * A step that would pass T_max, or that finds fewer than K pages, changes nothing (neither
- * caches nor count) except that it sets the asynchronous error word
- * (ratsparse_async_status -> RS_ASYNC_TIMEOUT).  n_first + n_local <= K is required. */
+ * carries, caches, page bounds nor count: the append kernel applies the same test as the
+ * attention kernel) except that it sets the asynchronous error word
+ * (ratsparse_async_status -> RS_ASYNC_TIMEOUT).  n_first + n_local <= K is required.
+ * rat_decode_state_set must have run on the workspace before the first step (it also
+ * draws the first tag; a workspace that was only zeroed starts at T = 0 with a fixed tag). */
 size_t rat_decode_step_workspace_bytes(const rs_shape *s, int64_t T_max, int32_t K);
 int32_t rat_decode_state_set(void *ws, size_t ws_bytes, int64_t T, void *stream);
 int32_t rat_decode_state_get(void *ws, int64_t *T, void *stream);
@@ -202,6 +219,18 @@ int32_t rat_decode_step(const rs_shape *s, const void *k, const void *v, const f
                         void *meta, const void *q, float scale, int32_t K, int32_t n_first,
                         int32_t n_local, int64_t T_max, void *out, float *lse_out,
                         int32_t *idx_out, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- Strict head-level hit rate: Sec. 2.3 (H1) -----------------------------------------
+ * Hit_h = 1 only if, at every decoding step, the candidates head h selected hold the golden
+ * answer position of that step.  One call folds one step in:
+ *   hit[b, h] := 0 if gold[b, h] >= 0 and gold[b, h] / unit is not in idx[b, h, :]
+ *   idx  [B, H, K] int32: the lists written by quest_select_decode / sparse_attn_decode
+ *        (H = Hq, unit = P: a page holds the position) or by snapkv_compress (H = Hkv, unit = 1)
+ *   gold [B, H] int32: the golden token position of this step; negative = none for that head
+ *   hit  [B, H] uint8, in/out; set it to 1 before the first step.  Pointers 4-byte aligned.
+ * The mean of hit over heads after the last step is the hit rate. */
+int32_t selection_hit_update(const int32_t *idx, int32_t B, int32_t H, int32_t K, const int32_t *gold,
+                             int32_t unit, uint8_t *hit, void *stream);
 
 /* ---- MoBA routing at prefill: Sec. 2.2, Eq. 3; App. A.1, MoBA paragraph ----------------
  * Block representative = mean of the stored keys of a block of `block` tokens (the

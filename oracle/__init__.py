@@ -235,3 +235,21 @@ def snapkv_compress(q_win, k_cache, v_cache, T, K_keep, pool_kernel, scale, Tcap
     pooled = maxpool1d(votes, pool_kernel)
     idx, kc, vc = snapkv_select_gather(pooled, k_cache, v_cache, T, W, K_keep, Tcap_out)
     return dict(votes=votes, pooled=pooled, idx=idx, kc=kc, vc=vc)
+
+
+def head_hit(idx_steps, gold_steps, unit=1):
+    """Strict head-level hit (Sec. 2.3, H1): Hit_h = 1 only if at every step t the golden position
+    g_t is among the candidates head h selected at that step.  idx_steps: per step an int array
+    [B, H, K] of selected candidates (pages or tokens); gold_steps: per step an int array [B, H] of
+    golden token positions (negative: none at that step for that head); unit: tokens per candidate
+    (page size for page lists, 1 for token lists).  Returns a bool array [B, H]."""
+    hit = None
+    for idx, gold in zip(idx_steps, gold_steps):
+        idx, gold = np.asarray(idx), np.asarray(gold)
+        if hit is None:
+            hit = np.ones(gold.shape, dtype=bool)
+        for b in range(gold.shape[0]):
+            for h in range(gold.shape[1]):
+                if gold[b, h] >= 0 and (gold[b, h] // unit) not in set(int(x) for x in idx[b, h]):
+                    hit[b, h] = False
+    return hit

@@ -38,6 +38,7 @@ SIGNATURES = {
     "ratsparse_async_status": (_i32, [_vp, _vp]),
     "ratsparse_probe_read": (_i32, [_vp, _sz, _vp, _vp]),
     "ratsparse_debug_set_spin_limit": (None, [_i32]),
+    "ratsparse_debug_reload_knobs": (None, []),
     "rat_scan_workspace_bytes": (_sz, [_shp, _i64]),
     "rat_scan": (_i32, [_shp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _sz, _vp]),
     "quest_page_meta": (_i32, [_shp, _vp, _vp, _i64, _i64, _vp]),
@@ -54,6 +55,7 @@ SIGNATURES = {
     "rat_decode_state_get": (_i32, [_vp, ctypes.POINTER(ctypes.c_int64), _vp]),
     "rat_decode_step": (_i32, [_shp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _i32, _i32, _i32, _i64,
                                _vp, _vp, _vp, _vp, _sz, _vp]),
+    "selection_hit_update": (_i32, [_vp, _i32, _i32, _i32, _vp, _i32, _vp, _vp]),
     "moba_select_prefill_workspace_bytes": (_sz, [_shp, _i64, _i32]),
     "moba_select_prefill": (_i32, [_shp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "sparse_attn_prefill_workspace_bytes": (_sz, [_shp, _i64, _i32, _i32]),
@@ -191,6 +193,12 @@ def rat_decode_step(s, k, v, g, state_k, state_v, k_cache, v_cache, meta, q, sca
     _check(load().rat_decode_step(ctypes.byref(s), _ptr(k), _ptr(v), _ptr(g), _ptr(state_k), _ptr(state_v),
                                   _ptr(k_cache), _ptr(v_cache), _ptr(meta), _ptr(q), scale, K, n_first, n_local,
                                   T_max, _ptr(out), _ptr(lse_out), _ptr(idx_out), ws.ptr, ws.nbytes, _stream()))
+
+
+def selection_hit_update(idx, gold, unit, hit):
+    B, H, K = idx.shape
+    assert gold.shape == (B, H) and hit.shape == (B, H) and hit.dtype == torch.uint8
+    _check(load().selection_hit_update(_ptr(idx), B, H, K, _ptr(gold), unit, _ptr(hit), _stream()))
 
 
 def sparse_attn_decode_workspace_bytes(s, T_valid, K):

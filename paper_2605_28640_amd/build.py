@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libratsparse.so")
-SOURCES = ["api.hip", "scan.hip", "quest.hip", "decode_fused.hip", "moba.hip", "prefill.hip", "snapkv.hip"]
+SOURCES = ["api.hip", "scan.hip", "quest.hip", "decode_fused.hip", "moba.hip", "prefill.hip", "snapkv.hip", "analysis.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -3,8 +3,11 @@
 #include <chrono>
 #include <cstdlib>
 
+#include <mutex>
+
 #include "common.h"
 #include "decode_fused.h"
+#include "knobs.h"
 
 namespace rs {
 // scan.hip
@@ -19,7 +22,7 @@ void page_meta_dispatch(int dtype, int D, const void *k_cache, void *meta, int B
                         int p_begin, int n_pages, long t_end, hipStream_t stream);
 void step_at_state_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
                             float *state_v, void *k_cache, void *v_cache, void *meta, int P, int BH, long Tcap,
-                            const uint32_t *pos_state, long T_max, hipStream_t stream);
+                            const uint32_t *pos_state, long T_max, int K, hipStream_t stream);
 void unit_decode_dispatch(int dtype, int D, const void *q, const void *meta, const void *k_cache, const void *v_cache,
                           void *out, float *lse_out, int32_t *idx_out, int B, int Hq, int Hkv, long Tcap, int P,
                           long T_valid, int Np, int K, int n_first, int n_local, float scale, uint32_t *state,
@@ -123,10 +126,51 @@ static int num_cus()
     return n;
 }
 
-static int env_int(const char *name, int dflt)
+static int env_or_unset(const char *name)
 {
     const char *e = std::getenv(name);
-    return e ? std::atoi(e) : dflt;
+    return e ? std::atoi(e) : kKnobUnset;
+}
+
+static Knobs g_knobs;
+static std::once_flag g_knobs_once;
+
+static void knobs_read()
+{
+    Knobs &k = g_knobs;
+    k.score_wgs = env_or_unset("RATSPARSE_SCORE_WGS");
+    k.attend_wgs = env_or_unset("RATSPARSE_ATTEND_WGS");
+    k.fused_grid = env_or_unset("RATSPARSE_FUSED_GRID");
+    k.fused_sscore = env_or_unset("RATSPARSE_FUSED_SSCORE");
+    k.fused_satt = env_or_unset("RATSPARSE_FUSED_SATT");
+    k.fused_fine = env_or_unset("RATSPARSE_FUSED_FINE");
+    k.fused_fine_pct = env_or_unset("RATSPARSE_FUSED_FINE_PCT");
+    k.fused_nt = env_or_unset("RATSPARSE_FUSED_NT");
+    k.fused_pingpong = env_or_unset("RATSPARSE_FUSED_PINGPONG");
+    k.fused_two_launch = env_or_unset("RATSPARSE_FUSED_TWO_LAUNCH");
+    k.fused_one_wg = env_or_unset("RATSPARSE_FUSED_ONE_WG");
+    k.scan_grid = env_or_unset("RATSPARSE_SCAN_GRID");
+    k.scan_slab = env_or_unset("RATSPARSE_SCAN_SLAB");
+    k.scan_meta = env_or_unset("RATSPARSE_SCAN_META");
+    k.meta_spw = env_or_unset("RATSPARSE_META_SPW");
+    k.gate_waves = env_or_unset("RATSPARSE_GATE_WAVES");
+    k.gate_wgs = env_or_unset("RATSPARSE_GATE_WGS");
+    k.gate_shared = env_or_unset("RATSPARSE_GATE_SHARED");
+    k.prefill_masked = env_or_unset("RATSPARSE_PREFILL_MASKED");
+    k.prefill_grid = env_or_unset("RATSPARSE_PREFILL_GRID");
+    k.snap_one_wg = env_or_unset("RATSPARSE_SNAP_ONE_WG");
+}
+
+const Knobs &knobs()
+{
+    std::call_once(g_knobs_once, knobs_read);
+    return g_knobs;
+}
+
+void knobs_reload()
+{
+    (void)knobs();
+    knobs_read();
 }
 
 constexpr int kMaxAttSplits = 64;
@@ -142,9 +186,9 @@ static DecodeLayout decode_layout(const rs_shape *s, long T_valid, int K)
     const long units = (long)s->B * s->Hq;
     L.Np = (int)((T_valid + s->P - 1) / s->P);
     // 512-thread workgroups, about one per CU (128 pages per workgroup step)
-    L.splits_score = pick_splits(units, L.Np, 128, env_int("RATSPARSE_SCORE_WGS", 256));
+    L.splits_score = pick_splits(units, L.Np, 128, knob_or(knobs().score_wgs, 256));
     const long dense_tiles = (T_valid + 15) / 16;
-    L.splits_att_max = pick_splits(units, dense_tiles, 8, env_int("RATSPARSE_ATTEND_WGS", 512));
+    L.splits_att_max = pick_splits(units, dense_tiles, 8, knob_or(knobs().attend_wgs, 512));
     if (L.splits_att_max < kMaxAttSplits) L.splits_att_max = kMaxAttSplits;
     size_t off = RS_WS_CTRL_BYTES;
     L.off_scores = off;
@@ -156,7 +200,9 @@ static DecodeLayout decode_layout(const rs_shape *s, long T_valid, int K)
     L.off_partial = off;
     off += align256((size_t)units * L.splits_att_max * (s->D + 2) * 8);
     L.off_trace = off;
-    if (env_int("RATSPARSE_TRACE", 0)) off += (size_t)4096 * 64 * 8;
+#ifdef RS_FUSED_TRACE
+    off += (size_t)4096 * 64 * 8;
+#endif
     L.total = off;
     return L;
 }
@@ -181,28 +227,33 @@ static long fused_setup(FusedParams &prm, const rs_shape *s, const DecodeLayout 
     prm.Hq = s->Hq; prm.Hkv = s->Hkv; prm.units = (int)units;
     prm.Tcap = s->Tcap; prm.Np_cap = s->Tcap / s->P; prm.T_valid = T_valid;
     prm.P = s->P; prm.Np = L.Np; prm.K = K; prm.n_first = n_first; prm.n_local = n_local;
-    int ss = env_int("RATSPARSE_FUSED_SSCORE", 0), sa = env_int("RATSPARSE_FUSED_SATT", 0);
+    const Knobs &kn = knobs();
+    int ss = knob_or(kn.fused_sscore, 0), sa = knob_or(kn.fused_satt, 0);
     if (ss <= 0) ss = (L.Np + 511) / 512;                      // ~512 pages (256 KiB of bf16 metadata) per item
     if (sa <= 0) sa = (int)(((long)K * (s->P / 16) + 31) / 32);  // ~32 tiles (256 KiB of bf16 K+V) per item
     if (ss > L.Np) ss = L.Np;
     if (sa > kMaxAttSplits) sa = kMaxAttSplits;
     if (sa > K) sa = K;
     prm.S_score = ss < 1 ? 1 : ss; prm.S_att = sa < 1 ? 1 : sa;
-    int fine = env_int("RATSPARSE_FUSED_FINE", 2) * prm.S_att;
+    int fine = knob_or(kn.fused_fine, 2) * prm.S_att;
     if (fine > kMaxAttSplits) fine = kMaxAttSplits;
     if (fine > K) fine = K;
     prm.S_att_fine = fine < prm.S_att ? prm.S_att : fine;
-    int fine_pct = env_int("RATSPARSE_FUSED_FINE_PCT", 6);
+    int fine_pct = knob_or(kn.fused_fine_pct, 6);
     fine_pct = fine_pct < 0 ? 0 : fine_pct > 100 ? 100 : fine_pct;
     prm.units_fine = (int)(units * fine_pct / 100);
     prm.S_max = kMaxAttSplits;
-    prm.reverse = env_int("RATSPARSE_FUSED_PINGPONG", 1) ? (int)(T_valid & 1) : 0;
-    prm.nt_kv = env_int("RATSPARSE_FUSED_NT", 1);  // bit 0: K/V pages, bit 1: page metadata
+    prm.reverse = knob_or(kn.fused_pingpong, 1) ? (int)(T_valid & 1) : 0;
+    prm.nt_kv = knob_or(kn.fused_nt, 1);  // bit 0: K/V pages, bit 1: page metadata
     prm.scale = scale; prm.tag = 0; prm.spin_limit = g_spin_limit.load();
-    prm.trace = env_int("RATSPARSE_TRACE", 0) ? (uint64_t *)(w + L.off_trace) : nullptr;
+#ifdef RS_FUSED_TRACE
+    prm.trace = (uint64_t *)(w + L.off_trace);
+#else
+    prm.trace = nullptr;
+#endif
     prm.state = nullptr; prm.T_max = 0;
     const long items = units * (prm.S_score + prm.S_att) + (long)prm.units_fine * (prm.S_att_fine - prm.S_att);
-    long grid = env_int("RATSPARSE_FUSED_GRID", 2 * num_cus());
+    long grid = knob_or(kn.fused_grid, 2 * num_cus());
     if (grid > items) grid = items;
     if (grid < 1) grid = 1;
     return grid;
@@ -266,6 +317,9 @@ int32_t ratsparse_probe_read(const void *src, size_t bytes, void *sink, void *st
 
 // test hook: bound of the scan's in-kernel wait, in polls
 void ratsparse_debug_set_spin_limit(int32_t polls) { g_spin_limit.store(polls < 0 ? 0 : polls); }
+
+// test hook: read the RATSPARSE_* tuning variables again (they are otherwise read once per process)
+void ratsparse_debug_reload_knobs(void) { knobs_reload(); }
 
 int32_t ratsparse_workspace_init(void *ws, size_t ws_bytes, void *stream)
 {
@@ -449,7 +503,7 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     // 32 query over 8 KV heads at 32K, batch 1, 29 against 33 us.  Long ones the other way: batch 4
     // at 64K (538 MB) 95 against 143 us, batch 32 at 8K 98 against 112 us.
     const double step_bytes = ((double)s->B * s->Hkv * Np * 2 + (double)units * K * s->P * 2) * s->D * esize(s->dtype);
-    const int two_launch = env_int("RATSPARSE_FUSED_TWO_LAUNCH", (step_bytes >= 450e6 && Np >= 512) ? 0 : 1);
+    const int two_launch = knob_or(knobs().fused_two_launch, (step_bytes >= 450e6 && Np >= 512) ? 0 : 1);
     // Short contexts (the paper's 4096 tokens): the whole step of a (batch, query head) inside one
     // workgroup, one launch, nothing handed between workgroups.  Taken when a unit's metadata and
     // picked pages are small (at most 1.5 MB, and at most 512 KB unless there are 128 units or
@@ -459,7 +513,7 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     // 28 / 32 / 44 and 47 / 52 / 59; the other way at 32K, batch 2: 51 / 34 / 47.
     const double unit_bytes = ((double)Np * 2 + (double)K * s->P * 2) * s->D * esize(s->dtype);
     const bool unit_rule = two_launch && unit_bytes <= 1.5e6 && (units >= 128 || unit_bytes <= 512e3);
-    const int one_wg = env_int("RATSPARSE_FUSED_ONE_WG", unit_rule ? 1 : 0);
+    const int one_wg = knob_or(knobs().fused_one_wg, unit_rule ? 1 : 0);
     if (fused && !group && one_wg && Np <= 4096 && K <= 1024) {
         unit_decode_dispatch(s->dtype, s->D, q, meta, k_cache, v_cache, out, lse_out, idx_out, s->B, s->Hq, s->Hkv,
                              s->Tcap, s->P, T_valid, (int)Np, K, n_first, n_local, scale, nullptr, (hipStream_t)stream);
@@ -490,7 +544,7 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     // partials to merge than many small ones (32 query / 8 KV heads, batch 1: dense over 16.5K rows
     // 29 -> 25 us, over 32K rows 45 -> 41 us, 128 listed pages 13.7 -> 10.1 us against 256 threads
     // and 512 workgroups).  A wave takes two tiles per step: past 16 steps per wave, twice the splits.
-    int target = env_int("RATSPARSE_ATTEND_WGS", 0);
+    int target = knob_or(knobs().attend_wgs, 0);
     if (target <= 0) {
         target = 256;
         if (tiles > (long)pick_splits(units, tiles, 8, 256) * 8 * 2 * 16) target = 512;
@@ -566,13 +620,13 @@ int32_t rat_decode_step(const rs_shape *s, const void *k, const void *v, const f
     if (!ws || !aligned16(ws) || ws_bytes < L.total) return RS_WORKSPACE_TOO_SMALL;
     char *w = (char *)ws;
     step_at_state_dispatch(s->dtype, s->D, k, v, g, state_k, state_v, k_cache, v_cache, meta, s->P, s->B * s->Hkv,
-                           s->Tcap, (const uint32_t *)w, T_max, (hipStream_t)stream);
+                           s->Tcap, (const uint32_t *)w, T_max, K, (hipStream_t)stream);
     if (launch_status() != RS_OK) return RS_LAUNCH_FAILED;
     // short contexts: one workgroup per (batch, query head), as in sparse_attn_decode (sized at T_max)
     const long units = (long)s->B * s->Hq;
     const double unit_bytes = ((double)L.Np * 2 + (double)K * s->P * 2) * s->D * esize(s->dtype);
     const bool unit_rule = unit_bytes <= 1.5e6 && (units >= 128 || unit_bytes <= 512e3);
-    if (env_int("RATSPARSE_FUSED_ONE_WG", unit_rule ? 1 : 0) && L.Np <= 4096 && K <= 1024) {
+    if (knob_or(knobs().fused_one_wg, unit_rule ? 1 : 0) && L.Np <= 4096 && K <= 1024) {
         unit_decode_dispatch(s->dtype, s->D, q, meta, k_cache, v_cache, out, lse_out, idx_out, s->B, s->Hq, s->Hkv,
                              s->Tcap, s->P, T_max, L.Np, K, n_first, n_local, scale, (uint32_t *)w, (hipStream_t)stream);
         return launch_status();
@@ -580,7 +634,7 @@ int32_t rat_decode_step(const rs_shape *s, const void *k, const void *v, const f
     FusedParams prm;
     const long grid = fused_setup(prm, s, L, w, q, meta, k_cache, v_cache, out, lse_out, idx_out, T_max, K, n_first,
                                   n_local, scale);
-    prm.reverse = env_int("RATSPARSE_FUSED_PINGPONG", 1);  // the kernel takes the parity of the length it reads
+    prm.reverse = knob_or(knobs().fused_pingpong, 1);  // the kernel takes the parity of the length it reads
     prm.state = (uint32_t *)w;
     prm.T_max = T_max;
     st = decode_fused_dispatch(s->dtype, s->D, prm, L.Np, (int)grid, (hipStream_t)stream);
@@ -604,7 +658,7 @@ int32_t moba_select_prefill(const rs_shape *s, const void *q, const void *k_cach
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(means_out) || !aligned16(idx_out)) return RS_INVALID_ARG;
     if (T <= 0 || T > s->Tcap || block <= 0 || block % 16 != 0) return RS_INVALID_ARG;
     const long Nb = (T + block - 1) / block;
-    if (Nb > 1024) return RS_UNSUPPORTED;
+    if (Nb > 256) return RS_UNSUPPORTED;  // one LDS score column per thread in the gate kernel
     if (n_first < 0 || K < 1 + n_first || K > 32) return RS_INVALID_ARG;
     if (!ws || !aligned16(ws) || ws_bytes < moba_select_ws_bytes(s, T, block)) return RS_WORKSPACE_TOO_SMALL;
     return moba_select_dispatch(s, q, k_cache, T, block, K, n_first, means_out, idx_out, (char *)ws,

@@ -229,10 +229,12 @@ __device__ __forceinline__ uint64_t load_u64_agent(const uint64_t *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// order-preserving map float32 -> uint32 (larger float <=> larger key)
+// order-preserving map float32 -> uint32 (larger float <=> larger key); -0.0 and +0.0 are
+// equal numbers and get the same key, so that a tie between them goes to the lower index
 __device__ __forceinline__ uint32_t float_to_key(float f)
 {
-    const uint32_t u = __float_as_uint(f);
+    uint32_t u = __float_as_uint(f);
+    if (u == 0x80000000u) u = 0u;
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 

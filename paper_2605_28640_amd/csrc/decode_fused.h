@@ -26,7 +26,7 @@ struct FusedParams {
     float scale;
     uint32_t tag;
     int spin_limit;
-    uint64_t *trace;  // optional timeline for tuning: [workgroup][64] of (time << 20 | item << 4 | phase)
+    uint64_t *trace;  // builds with -DRS_FUSED_TRACE only: timeline [workgroup][64] of (time << 24 | item << 4 | phase); else NULL
     // replayable step: T_valid, Np and tag are read from the workspace's state words (T_valid =
     // tokens in the cache + 1: the step's append has run) and the last workgroup out advances them
     uint32_t *state;  // control words of the workspace, or NULL: T_valid, Np, tag above are used

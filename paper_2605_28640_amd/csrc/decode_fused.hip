@@ -39,6 +39,9 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
     if constexpr (STATE) {
         T_valid_ = *reinterpret_cast<const long *>(a.state + kCtrlStateT) + 1;
         tag_ = a.state[kCtrlStateTag];
+        // a workspace that has only been zeroed holds tag 0, which zero-filled score, list and
+        // partial words would already "carry": never hand off under tag 0
+        if (tag_ == 0u) tag_ = 0x5bd1e995u;
         Np_ = (int)((T_valid_ + a.P - 1) / a.P);
         score_stride = (a.T_max + a.P - 1) / a.P;
         reverse_ = a.reverse ? (int)(T_valid_ & 1) : 0;
@@ -66,11 +69,16 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
     const int n_total = n_score + n_att_coarse + a.units_fine * a.S_att_fine;
     const int G = a.Hq / a.Hkv;
 
+    // per-workgroup timeline for tuning: compiled in only with -DRS_FUSED_TRACE (never in the shipped library)
+#ifdef RS_FUSED_TRACE
     int n_ev = 0;
     auto mark = [&](int item_, int phase) {
         if (a.trace && tid == 0 && n_ev < 64)
             a.trace[(long)blockIdx.x * 64 + n_ev++] = (wall_clock64() << 24) | ((uint64_t)(item_ & 0xfffff) << 4) | (uint64_t)phase;
     };
+#else
+    auto mark = [](int, int) {};
+#endif
     if (tid == 0) s_next = (int)atomicAdd(a.ticket, 1u);
     __syncthreads();
     int item = s_next;

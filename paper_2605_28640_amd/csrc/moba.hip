@@ -2,6 +2,7 @@
 // representatives, per-query gate scores against the blocks before the query's own, and
 // the top-K blocks per query token (own block and the first n_first always kept).
 #include "common.h"
+#include "knobs.h"
 
 namespace rs {
 
@@ -550,20 +551,20 @@ int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, 
     const size_t lds_mfma = in_registers ? 0 : lds_wave;
     const long n_tiles = (T + 63) / 64, units = (long)s->B * s->Hq;
     long per_unit = (2048 + units - 1) / units;
-    if (const char *e = getenv("RATSPARSE_GATE_WAVES")) per_unit = (atol(e) + units - 1) / units;
+    if (knobs().gate_waves != kKnobUnset) per_unit = ((long)knobs().gate_waves + units - 1) / units;
     if (per_unit < 1) per_unit = 1;
     const dim3 g3((unsigned)(n_tiles < per_unit ? n_tiles : per_unit), (unsigned)units);
     // six-wave workgroups with the operands in LDS (48 KB + 6 x 16 KB of query rows): one per CU
     long wg_per_unit = (256 + units - 1) / units;
-    if (const char *e = getenv("RATSPARSE_GATE_WGS")) wg_per_unit = (atol(e) + units - 1) / units;
+    if (knobs().gate_wgs != kKnobUnset) wg_per_unit = ((long)knobs().gate_wgs + units - 1) / units;
     if (wg_per_unit < 1) wg_per_unit = 1;
     constexpr int nwv = 6;
     if (wg_per_unit > (n_tiles + nwv - 1) / nwv) wg_per_unit = (n_tiles + nwv - 1) / nwv;
     const dim3 g4((unsigned)wg_per_unit, (unsigned)units);
-    const char *eso = getenv("RATSPARSE_GATE_SHARED");
+    const int eso = knobs().gate_shared;
     // worth its set-up from about 8192 tiles on (C4 0.148 -> 0.138 ms; 8 x 32 heads x 4096 tokens, blocks of 64,
     // top-8: 0.184 -> 0.150 ms; 32 heads x 4096 tokens: 0.026 against 0.031 ms the other way)
-    const bool shared_ops = in_registers && (eso ? atoi(eso) != 0 : units * n_tiles >= 8192);
+    const bool shared_ops = in_registers && (eso != kKnobUnset ? eso != 0 : units * n_tiles >= 8192);
 #define RS_LAUNCH(ST, DD)                                                                                          \
     do {                                                                                                           \
         moba_block_means_kernel<ST, DD><<<g1, 256, 0, stream>>>((const ST *)k_cache, means_out, nullptr, s->Tcap, T, block, Nb); \

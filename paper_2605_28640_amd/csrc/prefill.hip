@@ -25,6 +25,7 @@
 #include <cstdlib>
 
 #include "common.h"
+#include "knobs.h"
 
 #include <type_traits>
 
@@ -714,12 +715,6 @@ static PrefillLayout prefill_layout(const rs_shape *s, long T, int block, int K)
     return L;
 }
 
-static int env_int_pf(const char *name, int dflt)
-{
-    const char *e = std::getenv(name);
-    return e ? std::atoi(e) : dflt;
-}
-
 size_t prefill_ws_bytes(const rs_shape *s, long T, int block, int K) { return prefill_layout(s, T, block, K).total; }
 
 int prefill_dispatch(const rs_shape *s, const void *q, const void *k_cache, const void *v_cache, long T, int block,
@@ -763,7 +758,7 @@ int prefill_dispatch(const rs_shape *s, const void *q, const void *k_cache, cons
     // blocks of 128: top-8 1.72 / 1.19, top-4 0.98 / 1.15; 8192 tokens, 128, top-8: 0.92 / 1.03.
     const bool can_mask = idx && Nb <= 64 && block % kKT == 0;
     const double by_sets = 0.85 * (p.n_diag + 4.0), regrouped = (K - 1) * (4.3 + block / 64.0) + 9.0;
-    const int masked = can_mask ? env_int_pf("RATSPARSE_PREFILL_MASKED", by_sets < regrouped ? 1 : 0) : 0;
+    const int masked = can_mask ? knob_or(knobs().prefill_masked, by_sets < regrouped ? 1 : 0) : 0;
     if (masked) {
         const dim3 grid((unsigned)p.n_diag, (unsigned)units);
         if (s->D == 128) prefill_attn_kernel<128, true><<<grid, 256, 0, stream>>>(p);

@@ -7,6 +7,7 @@
 // instruction and every global access is a run of full 128/256-byte rows.
 #include <cstdlib>
 #include "common.h"
+#include "knobs.h"
 #include "select.h"
 
 namespace rs {
@@ -105,7 +106,7 @@ void page_meta_dispatch(int dtype, int D, const void *k_cache, void *meta, int B
     const int spp = P / 16;
     const long segs = (long)n_pages * spp;
     int spw = 4;
-    if (const char *e = std::getenv("RATSPARSE_META_SPW")) spw = std::atoi(e) > 0 ? std::atoi(e) : spw;
+    if (knobs().meta_spw != kKnobUnset && knobs().meta_spw > 0) spw = knobs().meta_spw;
     while (spw > 1 && (segs * BH) / spw < 8192) spw >>= 1;
     if (spw < spp) spw = spp;
     spw = (spw / spp) * spp;

@@ -24,6 +24,7 @@
 #include <cstdlib>
 
 #include "common.h"
+#include "knobs.h"
 
 namespace rs {
 
@@ -344,13 +345,16 @@ __global__ __launch_bounds__(256) void rat_step_kernel(
     const ST *__restrict__ k, const ST *__restrict__ v, const float *__restrict__ g,
     float *__restrict__ state_k, float *__restrict__ state_v, ST *__restrict__ k_cache,
     ST *__restrict__ v_cache, ST *__restrict__ meta, int P, int BH, int D, long T_new, long t0, long Tcap,
-    const uint32_t *__restrict__ pos_state, long T_max)
+    const uint32_t *__restrict__ pos_state, long T_max, int K_min_pages)
 {
     const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (long)BH * D) return;
     if (pos_state) {  // replayable step: the write position is the workspace's token count
         t0 = *reinterpret_cast<const long *>(pos_state + kCtrlStateT);
-        if (t0 + T_new > T_max) return;  // the step's attention kernel reports it
+        // a step the attention kernel of the same call will refuse (past T_max, or fewer pages than
+        // it must select) appends nothing either: the refused step leaves carries, caches and page
+        // bounds as they were, and the attention kernel reports it
+        if (t0 + T_new > T_max || (t0 + T_new + P - 1) / P < (long)K_min_pages) return;
     }
     const long bh = e / D;
     const int c = (int)(e % D);
@@ -403,8 +407,7 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
             per_cu = n;
             if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         }
-        const char *e = std::getenv("RATSPARSE_SCAN_GRID");
-        long want = e ? std::atol(e) : (long)per_cu * cus;
+        long want = knob_or(knobs().scan_grid, per_cu * cus);
         if (want < 1) want = 1;
         if (want > (long)per_cu * cus) want = (long)per_cu * cus;  // the knob only narrows: every workgroup stays resident
         if (grid > want) grid = want;
@@ -428,8 +431,8 @@ static bool scan_uses_slabs(int BH, long T_new)
 {
     // few (batch, head) pairs and a long run: 32-channel slabs, so that the chunk chains are
     // shorter and there are more of them
-    const char *es = std::getenv("RATSPARSE_SCAN_SLAB");
-    return es ? std::atoi(es) != 0 : (BH <= 16 && T_new >= 2048);
+    const int forced = knobs().scan_slab;
+    return forced != kKnobUnset ? forced != 0 : (BH <= 16 && T_new >= 2048);
 }
 
 // whether the chunk kernel leaves the Quest page bounds of the rows it stores (else the caller
@@ -437,8 +440,7 @@ static bool scan_uses_slabs(int BH, long T_new)
 bool scan_writes_meta(int dtype, int D, int P, int BH, long T_new, long t0)
 {
     if (scan_uses_step_kernel(T_new)) return true;  // the step kernel keeps the touched page current
-    const char *e = std::getenv("RATSPARSE_SCAN_META");
-    if (e && std::atoi(e) == 0) return false;
+    if (knobs().scan_meta == 0) return false;
     // chunk of the form in use: bfloat16 128 tokens at D = 128, 256 at D = 64 (float32: half); 32-channel slabs: D / 32 times that
     const long chunk = (long)scan_chunk_tokens(dtype, D) * (scan_uses_slabs(BH, T_new) ? D / 32 : 1);
     return P >= 16 && P <= chunk && (P & (P - 1)) == 0 && t0 % chunk == 0;
@@ -454,10 +456,10 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
         const unsigned blocks = (unsigned)((n + 255) / 256);
         if (dtype == RS_BF16)
             rat_step_kernel<bf16><<<blocks, 256, 0, stream>>>((const bf16 *)k, (const bf16 *)v, g, state_k, state_v,
-                                                             (bf16 *)k_cache, (bf16 *)v_cache, (bf16 *)meta, P, BH, D, T_new, t0, Tcap, nullptr, 0);
+                                                             (bf16 *)k_cache, (bf16 *)v_cache, (bf16 *)meta, P, BH, D, T_new, t0, Tcap, nullptr, 0, 0);
         else
             rat_step_kernel<float><<<blocks, 256, 0, stream>>>((const float *)k, (const float *)v, g, state_k, state_v,
-                                                              (float *)k_cache, (float *)v_cache, (float *)meta, P, BH, D, T_new, t0, Tcap, nullptr, 0);
+                                                              (float *)k_cache, (float *)v_cache, (float *)meta, P, BH, D, T_new, t0, Tcap, nullptr, 0, 0);
         return;
     }
     const bool slab = scan_uses_slabs(BH, T_new);
@@ -498,16 +500,16 @@ void scan_dispatch(int dtype, int D, const void *k, const void *v, const float *
 // the decode-time append of one token at the position the workspace's state words hold
 void step_at_state_dispatch(int dtype, int D, const void *k, const void *v, const float *g, float *state_k,
                             float *state_v, void *k_cache, void *v_cache, void *meta, int P, int BH, long Tcap,
-                            const uint32_t *pos_state, long T_max, hipStream_t stream)
+                            const uint32_t *pos_state, long T_max, int K, hipStream_t stream)
 {
     const long n = (long)BH * D;
     const unsigned blocks = (unsigned)((n + 255) / 256);
     if (dtype == RS_BF16)
         rat_step_kernel<bf16><<<blocks, 256, 0, stream>>>((const bf16 *)k, (const bf16 *)v, g, state_k, state_v,
-                                                         (bf16 *)k_cache, (bf16 *)v_cache, (bf16 *)meta, P, BH, D, 1, 0, Tcap, pos_state, T_max);
+                                                         (bf16 *)k_cache, (bf16 *)v_cache, (bf16 *)meta, P, BH, D, 1, 0, Tcap, pos_state, T_max, K);
     else
         rat_step_kernel<float><<<blocks, 256, 0, stream>>>((const float *)k, (const float *)v, g, state_k, state_v,
-                                                          (float *)k_cache, (float *)v_cache, (float *)meta, P, BH, D, 1, 0, Tcap, pos_state, T_max);
+                                                          (float *)k_cache, (float *)v_cache, (float *)meta, P, BH, D, 1, 0, Tcap, pos_state, T_max, K);
 }
 
 }  // namespace rs

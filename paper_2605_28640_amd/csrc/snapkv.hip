@@ -9,6 +9,7 @@
 // a lane owns one query row and gets its softmax max / sum cheaply; sweep 2 forms S = Q K^T
 // so that a lane owns one key column and its vote is an in-lane sum over the query rows.
 #include "common.h"
+#include "knobs.h"
 #include "select.h"
 
 #include <type_traits>
@@ -678,8 +679,8 @@ int snapkv_dispatch(const rs_shape *s, const void *q_win, const void *k_cache, c
     else
         snapkv_votes_kernel<64><<<grid2, 256, 0, stream>>>(qw, kc, lse, votes, s->Hq, s->Hkv, T, s->Tcap, W, scale, Ly.keys_per_wg);
     const long tot = BK * L;
-    const char *e1 = std::getenv("RATSPARSE_SNAP_ONE_WG");  // 0: the spread-out selection at any length
-    if (L <= kSnapOneWgKeys && !(e1 && std::atoi(e1) == 0)) {
+    // knob 0: the spread-out selection at any length
+    if (L <= kSnapOneWgKeys && knobs().snap_one_wg != 0) {
         snapkv_pool_select_kernel<<<(unsigned)BK, kSnapOneWgThreads, (size_t)L * 4, stream>>>(
             votes, votes_out, idx_out, (int)L, pool_kernel, K_keep);
     } else {

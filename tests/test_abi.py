@@ -87,6 +87,12 @@ def test_every_entry_point_rejects_bad_arguments_before_touching_the_gpu():
     assert lib.rat_decode_state_get(None, None, None) == 1
     assert lib.rat_decode_step_workspace_bytes(sp, 257, 4) == 0
 
+    # selection_hit_update(idx, B, H, K, gold, unit, hit, stream)
+    assert lib.selection_hit_update(None, 1, 2, 4, A, 16, A, None) == 1
+    assert lib.selection_hit_update(A, 1, 2, 4, A, 0, A, None) == 1      # unit must be positive
+    assert lib.selection_hit_update(A, 0, 2, 4, A, 16, A, None) == 1
+    assert lib.selection_hit_update(A + 2, 1, 2, 4, A, 16, A, None) == 1  # misaligned list
+
     # moba_select_prefill(s, q, k_cache, T, block, K, n_first, means_out, idx_out, ws, ws_bytes, stream)
     assert lib.moba_select_prefill(sp, A, A, 256, 24, 3, 0, A, A, A, big, None) == 1     # block not a multiple of 16
     assert lib.moba_select_prefill(sp, A, A, 256, 64, 33, 0, A, A, A, big, None) == 1    # K > 32

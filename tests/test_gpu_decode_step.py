@@ -59,11 +59,11 @@ def _step_inputs(w, step):
     return to_dev(k, w.dtype), to_dev(v, w.dtype), to_dev(g), to_dev(q, w.dtype), (k, v, g, q)
 
 
-def _force_form(monkeypatch, form):
+def _force_form(knobs, form):
     """Both sides run the same form of select-then-attend: the persistent launch, or one workgroup
     per (batch, head) (the step takes one of these two by shape; the knobs force either)."""
-    monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0" if form == "persistent" else "1")
-    monkeypatch.setenv("RATSPARSE_FUSED_ONE_WG", "0" if form == "persistent" else "1")
+    knobs.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0" if form == "persistent" else "1")
+    knobs.setenv("RATSPARSE_FUSED_ONE_WG", "0" if form == "persistent" else "1")
 
 
 FORMS = ["persistent", "one_wg"]
@@ -71,8 +71,8 @@ FORMS = ["persistent", "one_wg"]
 
 @pytest.mark.parametrize("form", FORMS)
 @pytest.mark.parametrize("case", range(len(CASES)))
-def test_step_equals_scan_then_fused_decode(rs, monkeypatch, case, form):
-    _force_form(monkeypatch, form)
+def test_step_equals_scan_then_fused_decode(rs, knobs, case, form):
+    _force_form(knobs, form)
     _, T0, steps, Tcap, P, K, n_first, n_local = CASES[case]
     say("decode step case", case, T0, steps, Tcap, P, K)
     w, s, pre, a, b = _setup(rs, case)
@@ -132,8 +132,8 @@ def test_step_equals_scan_then_fused_decode(rs, monkeypatch, case, form):
 
 
 @pytest.mark.parametrize("form", FORMS)
-def test_step_past_the_sized_length_changes_nothing_and_reports(rs, monkeypatch, form):
-    _force_form(monkeypatch, form)
+def test_step_past_the_sized_length_changes_nothing_and_reports(rs, knobs, form):
+    _force_form(knobs, form)
     w, T0, steps, Tcap, P, K, n_first, n_local = CASES[0]
     w, s, pre, a, b = _setup(rs, 0)
     dt = tdtype(w.dtype)
@@ -161,8 +161,46 @@ def test_step_past_the_sized_length_changes_nothing_and_reports(rs, monkeypatch,
 
 
 @pytest.mark.parametrize("form", FORMS)
-def test_step_replays_from_a_captured_graph(rs, monkeypatch, form):
-    _force_form(monkeypatch, form)
+def test_step_with_fewer_pages_than_K_changes_nothing_and_reports(rs, knobs, form):
+    """A step taken while the sequence still has fewer pages than K must select (right after
+    rat_decode_state_set with a short T) is refused by the attention kernel; the append of the same
+    call must then leave the carries, the caches and the page bounds alone too, or a later replay
+    would apply the gate to the carry a second time."""
+    _force_form(knobs, form)
+    w, T0, steps, Tcap, P, K, n_first, n_local = CASES[0]
+    w, s, pre, a, b = _setup(rs, 0)
+    dt = tdtype(w.dtype)
+    scale = 1.0 / np.sqrt(w.D)
+    T_max = Tcap
+    T_short = 3 * P  # 3 pages, 4 after the append: fewer than K = 8
+    assert (T_short + 1 + P - 1) // P < K
+    ws = rs.Workspace(rs.rat_decode_step_workspace_bytes(s, T_max, K))
+    rs.rat_decode_state_set(ws, T_short)
+    out = torch.full((w.B, w.Hq, w.D), 7.0, dtype=dt, device="cuda")
+    idx = torch.full((w.B, w.Hq, K), -3, dtype=torch.int32, device="cuda")
+    tk, tv, tg, tq, _ = _step_inputs(w, 0)
+    keep = [t.clone() for t in (a.sk, a.sv, a.kc, a.vc, a.meta, out, idx)]
+    for _ in range(2):  # the second call sees exactly what the first saw
+        rs.rat_decode_step(s, tk, tv, tg, a.sk, a.sv, a.kc, a.vc, a.meta, tq, scale, K, n_first, n_local, T_max, out,
+                           None, idx, ws)
+        with pytest.raises(rs.RatsparseError):
+            ws.async_status()
+        assert rs.rat_decode_state_get(ws) == T_short
+        for was, now in zip(keep, (a.sk, a.sv, a.kc, a.vc, a.meta, out, idx)):
+            assert torch.equal(was, now)
+    # the first length at which K pages exist goes through, from the same workspace
+    T_ok = (K - 1) * P
+    rs.rat_decode_state_set(ws, T_ok)
+    rs.rat_decode_step(s, tk, tv, tg, a.sk, a.sv, a.kc, a.vc, a.meta, tq, scale, K, n_first, n_local, T_max, out,
+                       None, idx, ws)
+    ws.async_status()
+    assert rs.rat_decode_state_get(ws) == T_ok + 1
+    np.testing.assert_array_equal(to_np(idx), np.broadcast_to(np.arange(K, dtype=np.int32), (w.B, w.Hq, K)))
+
+
+@pytest.mark.parametrize("form", FORMS)
+def test_step_replays_from_a_captured_graph(rs, knobs, form):
+    _force_form(knobs, form)
     _, T0, steps, Tcap, P, K, n_first, n_local = CASES[0]
     w, s, pre, a, b = _setup(rs, 0)
     dt = tdtype(w.dtype)
@@ -210,10 +248,10 @@ def test_step_replays_from_a_captured_graph(rs, monkeypatch, form):
     ws_a.async_status()
 
 
-def test_step_at_the_measured_size_equals_the_two_calls(rs, monkeypatch):
+def test_step_at_the_measured_size_equals_the_two_calls(rs, knobs):
     """The measured configuration (batch 4, 32 heads, 64K context, 256 of 4096+ pages): several
     score and attention slices per unit, page count growing under the fixed work split."""
-    _force_form(monkeypatch, "persistent")
+    _force_form(knobs, "persistent")
     B, H, D, P, K = 4, 32, 128, 16, 256
     T0, steps = 65536 - 6, 14  # crosses the edge of page 4096
     Tcap = 65536 + 64

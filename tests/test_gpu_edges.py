@@ -7,7 +7,7 @@ import torch
 
 import oracle
 from gpu_util import say, tdtype, to_dev, to_np
-from helpers import attn_close
+from helpers import attn_close, topk_set_ok
 from paper_2605_28640_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -39,7 +39,7 @@ DECODE = [
 
 
 @pytest.mark.parametrize("case", range(len(DECODE)))
-def test_decode_edges(rs, monkeypatch, case):
+def test_decode_edges(rs, knobs, case):
     w, T, Tcap, P, K, n_first, n_local = DECODE[case]
     say("decode edge", case, w.name, T, Tcap, P, K, n_first, n_local)
     w, kc, vc = _cache(w, T, Tcap)
@@ -61,17 +61,27 @@ def test_decode_edges(rs, monkeypatch, case):
     rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out, lse, idx, ws)
     gidx = to_np(idx)
     for two_launch in ("0", "1"):  # the one persistent launch and the two-launch form agree
-        monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", two_launch)
+        knobs.setenv("RATSPARSE_FUSED_TWO_LAUNCH", two_launch)
         out_m, idx_m = torch.zeros_like(out), torch.full_like(idx, -7)
         rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out_m, None, idx_m, ws)
         np.testing.assert_array_equal(to_np(idx_m), gidx)
         assert attn_close(to_np(out_m), to_np(out).astype(np.float64), tol)[0]
-    monkeypatch.delenv("RATSPARSE_FUSED_TWO_LAUNCH")
+    knobs.delenv("RATSPARSE_FUSED_TWO_LAUNCH")
+    osc = oracle.quest_scores(q, ometa, Np)
+    forced = np.zeros(Np, bool)
+    forced[:n_first] = True
+    forced[Np - n_local:] = True
+    oidx = oracle.quest_select(osc, K, n_first, n_local)
+    identical = 0
     for b in range(w.B):
         for h in range(w.Hq):
             row = gidx[b, h]
             assert np.all(np.diff(row) > 0) and row[0] >= 0 and row[-1] < Np, row
             assert set(range(n_first)) <= set(row) and set(range(Np - n_local, Np)) <= set(row), row
+            ok, why = topk_set_ok(osc[b, h], forced, K, row)  # the selection against the oracle's scores (Eq. 3)
+            assert ok, (b, h, why)
+            identical += np.array_equal(row, oidx[b, h])
+    say("  selections identical to the oracle's: %d of %d" % (identical, w.B * w.Hq))
     want, wlse = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, gidx)
     ok, worst = attn_close(to_np(out), want, tol)
     assert ok, worst
@@ -174,7 +184,7 @@ def test_snapkv_edges(rs, case):
     ws.async_status()
 
 
-def test_out_of_range_knob_values_are_clamped(rs, monkeypatch):
+def test_out_of_range_knob_values_are_clamped(rs, knobs):
     """The tuning knobs are read at dispatch; values outside their range are clamped to it, so the
     work split changes at most: the scan (whose arithmetic does not depend on the grid) stays bit-equal,
     the persistent decode launch picks the same pages and agrees to the rounding of a different merge order."""
@@ -186,8 +196,8 @@ def test_out_of_range_knob_values_are_clamped(rs, monkeypatch):
     g = torch.sigmoid(4.2 + 0.5 * torch.randn(B, H, T, D, device="cuda", generator=gen))
     q = torch.randn(B, H, D, device="cuda", generator=gen).to(dt)
     s = rs.make_shape(B, H, H, D, T, P, dt)
-    monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0")  # the persistent launch, where the decode knobs apply
-    monkeypatch.setenv("RATSPARSE_FUSED_ONE_WG", "0")
+    knobs.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0")  # the persistent launch, where the decode knobs apply
+    knobs.setenv("RATSPARSE_FUSED_ONE_WG", "0")
 
     def run():
         kc = torch.zeros(B, H, T, D, dtype=dt, device="cuda")
@@ -210,10 +220,10 @@ def test_out_of_range_knob_values_are_clamped(rs, monkeypatch):
                    "RATSPARSE_META_SPW": "1000000"}):
         say("knobs", knobs)
         for name, value in knobs.items():
-            monkeypatch.setenv(name, value)
+            knobs.setenv(name, value)
         got = run()
         for a, b in zip(got[:6], want[:6]):
             assert torch.equal(a, b)
         assert torch.allclose(got[6].float(), want[6].float(), rtol=2e-2, atol=2e-2)
         for name in knobs:
-            monkeypatch.delenv(name)
+            knobs.delenv(name)

@@ -42,72 +42,130 @@ def _check_scan_units(units, inputs, kc, vc, sk, sv, T):
     return states
 
 
-def _decode_run(rs, w, units, check_steps, budget):
-    """Full-size Quest decode: prefill scan, bulk page metadata, then w.steps decode steps of
-    append + page-meta update + fused select/attend, checked on sampled units and steps."""
+def _decode_run(rs, w, units, runs, dtype="bf16", dense_check=False):
+    """Full-size Quest decode: prefill scan and bulk page metadata once, then for each
+    (budget, steps, check_steps) of `runs` the decode steps of append + page-meta update + fused
+    select/attend from the state after the prefill, checked on sampled units and steps against the
+    oracle (every run rewrites the same appended rows, so it starts from the same cache)."""
     P = w.P
-    Tcap = w.T + ((w.steps + 16 + P - 1) // P) * P
-    s, inputs, kc, vc, sk, sv = _prefill_on_gpu(rs, w, Tcap, P)
-    states = _check_scan_units([(b, kvh) for (b, kvh, _) in units], inputs, kc, vc, sk, sv, w.T)
+    bf = dtype == "bf16"
+    tdt = torch.bfloat16 if bf else torch.float32
+    max_steps = max(st for _, st, _ in runs)
+    Tcap = w.T + ((max_steps + 16 + P - 1) // P) * P
+    if bf:
+        s, inputs, kc, vc, sk, sv = _prefill_on_gpu(rs, w, Tcap, P)
+        states0 = _check_scan_units(sorted(set((b, kvh) for (b, kvh, _) in units)), inputs, kc, vc, sk, sv, w.T)
+    else:
+        k, v, g = synth.prefill(w)
+        s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tcap, P, tdt)
+        kc = torch.zeros(w.B, w.Hkv, Tcap, w.D, device="cuda")
+        vc = torch.zeros_like(kc)
+        sk = torch.zeros(w.B, w.Hkv, w.D, device="cuda")
+        sv = torch.zeros_like(sk)
+        wsp = rs.Workspace(rs.rat_scan_workspace_bytes(s, w.T))
+        rs.rat_scan(s, to_dev(k), to_dev(v), to_dev(g), sk, sv, kc, vc, 0, w.T, wsp)
+        torch.cuda.synchronize()
+        wsp.async_status()
+        states0 = {}
+        for (b, kvh) in sorted(set((b, kvh) for (b, kvh, _) in units)):
+            ko, vo, osk, osv = oracle.rat_scan(k[b:b + 1, kvh:kvh + 1], v[b:b + 1, kvh:kvh + 1], g[b:b + 1, kvh:kvh + 1])
+            assert scan_close(to_np(kc[b, kvh, :w.T]), ko[0, 0])[0] and scan_close(to_np(vc[b, kvh, :w.T]), vo[0, 0])[0]
+            assert scan_close(to_np(sk[b, kvh]), osk[0, 0])[0] and scan_close(to_np(sv[b, kvh]), osv[0, 0])[0]
+            states0[(b, kvh)] = (osk, osv)
+        inputs = None
     del inputs
-    meta = torch.zeros(w.B, w.Hkv, Tcap // P, 2, w.D, dtype=torch.bfloat16, device="cuda")
+    stored_ok = bf16_store_ok if bf else (lambda x, y: scan_close(x, y)[0])
+    tol = 2e-2 if bf else 1e-4
+    meta = torch.zeros(w.B, w.Hkv, Tcap // P, 2, w.D, dtype=tdt, device="cuda")
     rs.quest_page_meta(s, kc, meta, 0, w.T)
-    K = int(round(budget * (w.T // P)))
+    sk0, sv0 = sk.clone(), sv.clone()
     scale = 1.0 / np.sqrt(w.D)
-    out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.bfloat16, device="cuda")
-    idx = torch.zeros(w.B, w.Hq, K, dtype=torch.int32, device="cuda")
-    ws = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, Tcap, K))
-    identical = 0
-    for i in range(w.steps):
-        kd, vd, gd, qd = synth.decode_step(w, i)
-        t = w.T + i
-        rs.rat_scan(s, to_dev(kd, "bf16"), to_dev(vd, "bf16"), to_dev(gd), sk, sv, kc, vc, t, 1, None, meta)
-        rs.sparse_attn_decode(s, to_dev(qd, "bf16"), kc, vc, t + 1, scale, None, K, meta, 1, 1, out, None, idx, ws)
-        for (b, kvh) in states:  # the oracle follows every append of its units
-            osk, osv = states[(b, kvh)]
-            ko, vo, osk, osv = oracle.rat_scan(kd[b:b + 1, kvh:kvh + 1], vd[b:b + 1, kvh:kvh + 1],
-                                               gd[b:b + 1, kvh:kvh + 1], osk, osv)
-            states[(b, kvh)] = (osk, osv)
-            if i in check_steps:
-                assert bf16_store_ok(to_np(kc[b, kvh, t]), ko[0, 0, 0]) and bf16_store_ok(to_np(vc[b, kvh, t]), vo[0, 0, 0])
-        if i not in check_steps:
-            continue
-        Tv = t + 1
-        Np = -(-Tv // P)
-        forced = np.zeros(Np, bool)
-        forced[0] = forced[-1] = True
-        for (b, kvh, h) in units:
-            hk = to_np(kc[b:b + 1, kvh:kvh + 1])  # the rows the GPU stored
-            hv = to_np(vc[b:b + 1, kvh:kvh + 1])
-            ometa = oracle.quest_page_meta(hk, P, Tv)
-            np.testing.assert_array_equal(to_np(meta[b, kvh, :Np]), ometa[0, 0, :Np])
-            osc = oracle.quest_scores(qd[b:b + 1, h:h + 1], ometa, Np)
-            got = to_np(idx[b, h])
-            ok, why = topk_set_ok(osc[0, 0], forced, K, got)
-            assert ok, (i, b, h, why)
-            identical += np.array_equal(got, oracle.quest_select(osc, K, 1, 1)[0, 0])
-            want, _ = oracle.sparse_attn_decode(qd[b:b + 1, h:h + 1], hk, hv, P, Tv, scale, got[None, None])
-            ok, worst = attn_close(to_np(out[b, h]), want[0, 0])
-            assert ok, (i, b, h, worst)
-    torch.cuda.synchronize()
-    ws.async_status()
-    say("  selections identical to the oracle's: %d of %d" % (identical, len(check_steps & set(range(w.steps))) * len(units)))
+    out = torch.zeros(w.B, w.Hq, w.D, dtype=tdt, device="cuda")
+    for budget, steps, check_steps in runs:
+        K = int(round(budget * (w.T // P)))
+        say("  budget", budget, "K", K, "steps", steps)
+        sk.copy_(sk0)
+        sv.copy_(sv0)
+        states = dict(states0)
+        idx = torch.zeros(w.B, w.Hq, K, dtype=torch.int32, device="cuda")
+        ws = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, Tcap, K))
+        identical = checked = 0
+        for i in range(steps):
+            kd, vd, gd, qd = synth.decode_step(w, i)
+            t = w.T + i
+            rs.rat_scan(s, to_dev(kd, dtype), to_dev(vd, dtype), to_dev(gd), sk, sv, kc, vc, t, 1, None, meta)
+            rs.sparse_attn_decode(s, to_dev(qd, dtype), kc, vc, t + 1, scale, None, K, meta, 1, 1, out, None, idx, ws)
+            for (b, kvh) in states:  # the oracle follows every append of its units
+                osk, osv = states[(b, kvh)]
+                ko, vo, osk, osv = oracle.rat_scan(kd[b:b + 1, kvh:kvh + 1], vd[b:b + 1, kvh:kvh + 1],
+                                                   gd[b:b + 1, kvh:kvh + 1], osk, osv)
+                states[(b, kvh)] = (osk, osv)
+                if i in check_steps:
+                    assert stored_ok(to_np(kc[b, kvh, t]), ko[0, 0, 0]) and stored_ok(to_np(vc[b, kvh, t]), vo[0, 0, 0])
+            if i not in check_steps:
+                continue
+            Tv = t + 1
+            Np = -(-Tv // P)
+            forced = np.zeros(Np, bool)
+            forced[0] = forced[-1] = True
+            for (b, kvh, h) in units:
+                hk = to_np(kc[b:b + 1, kvh:kvh + 1])  # the rows the GPU stored
+                hv = to_np(vc[b:b + 1, kvh:kvh + 1])
+                ometa = oracle.quest_page_meta(hk, P, Tv)
+                np.testing.assert_array_equal(to_np(meta[b, kvh, :Np]), ometa[0, 0, :Np])
+                osc = oracle.quest_scores(qd[b:b + 1, h:h + 1], ometa, Np)
+                got = to_np(idx[b, h])
+                ok, why = topk_set_ok(osc[0, 0], forced, K, got)
+                assert ok, (budget, i, b, h, why)
+                identical += np.array_equal(got, oracle.quest_select(osc, K, 1, 1)[0, 0])
+                checked += 1
+                want, _ = oracle.sparse_attn_decode(qd[b:b + 1, h:h + 1], hk, hv, P, Tv, scale, got[None, None])
+                ok, worst = attn_close(to_np(out[b, h]), want[0, 0], tol)
+                assert ok, (budget, i, b, h, worst)
+                if dense_check:  # full budget: every page selected equals the dense path, and both the oracle's dense result
+                    outd = torch.zeros_like(out)
+                    idxd = torch.zeros(w.B, w.Hq, Np, dtype=torch.int32, device="cuda")
+                    wsd = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, Tcap, Np))
+                    rs.sparse_attn_decode(s, to_dev(qd, dtype), kc, vc, Tv, scale, None, Np, meta, 1, 1, outd, None, idxd, wsd)
+                    np.testing.assert_array_equal(to_np(idxd[b, h]), np.arange(Np))
+                    wantd, _ = oracle.sparse_attn_decode(qd[b:b + 1, h:h + 1], hk, hv, P, Tv, scale)
+                    assert attn_close(to_np(outd[b, h]), wantd[0, 0], tol)[0]
+                    rs.sparse_attn_decode(s, to_dev(qd, dtype), kc, vc, Tv, scale, None, 0, None, 0, 0, outd, None, None, wsd)
+                    assert attn_close(to_np(outd[b, h]), wantd[0, 0], tol)[0]
+                    wsd.async_status()
+        torch.cuda.synchronize()
+        ws.async_status()
+        say("  selections identical to the oracle's: %d of %d" % (identical, checked))
 
 
-def test_c3_olmo_decode_64k_budget_1_16(rs):
+def test_c1_tiny_fp32_decode_chain(rs):
+    """configs[0] as a chain: prefill scan, then all 16 decode steps (append + page bounds + select +
+    attend) with 16-token pages at budget 1/8 (K = 16 of 128 pages), float32, every unit and every step
+    against the oracle, and at every step the full-budget selection and the dense path against the
+    oracle's dense attention (Eq. 1, 3, 4; App. A.1, Quest)."""
+    w = synth.C1
+    say("full size", w.name)
+    units = [(b, h, h) for b in range(w.B) for h in range(w.Hq)]
+    _decode_run(rs, w, units, [(1 / 8, w.steps, set(range(w.steps)))], dtype="f32", dense_check=True)
+
+
+def test_c3_olmo_decode_64k(rs):
+    """configs[2] at both of its budgets: 1/16 (K = 256, the headline launch) over all 512 steps and
+    1/4 (K = 1024: other slice counts in the persistent launch) over 96 steps."""
     w = synth.C3
     say("full size", w.name)
     checks = {0, 1, 2, 255, 511} | set(range(31, 512, 32))
-    _decode_run(rs, w, units=[(0, 0, 0), (3, 17, 17)], check_steps=checks, budget=1 / 16)
+    _decode_run(rs, w, units=[(0, 0, 0), (3, 17, 17)],
+                runs=[(1 / 16, w.steps, checks), (1 / 4, 96, {0, 1, 2, 15, 16, 47, 95})])
 
 
 def test_c2_gqa_decode_32k(rs):
+    """configs[1] at its three budgets (1/4, 1/8, 1/16), grouped-query heads."""
     w = synth.C2
     say("full size", w.name)
     checks = {0, 1, 2, 127, 255} | set(range(15, 256, 16))
-    for budget in (1 / 4, 1 / 16):
-        _decode_run(rs, w.scaled(steps=64 if budget > 0.1 else 256), units=[(0, 0, 1), (0, 5, 22)],
-                    check_steps=checks, budget=budget)
+    _decode_run(rs, w, units=[(0, 0, 1), (0, 5, 22)],
+                runs=[(1 / 4, 64, checks), (1 / 8, 64, checks), (1 / 16, w.steps, checks)])
 
 
 def test_c4_moba_prefill_32k(rs):

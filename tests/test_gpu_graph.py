@@ -13,8 +13,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("form", ["0", "1"])  # routed attention regrouped by block / by bit sets
-def test_prefill_path_replays_from_a_captured_graph(rs, monkeypatch, form):
-    monkeypatch.setenv("RATSPARSE_PREFILL_MASKED", form)
+def test_prefill_path_replays_from_a_captured_graph(rs, knobs, form):
+    knobs.setenv("RATSPARSE_PREFILL_MASKED", form)
     B, H, D, T, block, K = 1, 8, 128, 1024, 128, 3
     dt = torch.bfloat16
     s = rs.make_shape(B, H, H, D, T, 16, dt)

@@ -63,7 +63,7 @@ CASES += _random_cases(20260528, 8)
 
 
 @pytest.mark.parametrize("case", range(len(CASES)))
-def test_moba_select_and_sparse_prefill(rs, monkeypatch, case):
+def test_moba_select_and_sparse_prefill(rs, knobs, case):
     w, T, Tcap, block, K, n_first = CASES[case]
     say("moba case", case, T, Tcap, block, K, n_first)
     w, q, kc, vc = _setup(w, T, Tcap)
@@ -99,11 +99,11 @@ def test_moba_select_and_sparse_prefill(rs, monkeypatch, case):
     # the gate's other form (block-mean operands shared through LDS by six-wave workgroups, or
     # fetched by each one-wave workgroup; the library picks by size): the same routing bit for bit
     for form in ("0", "1"):
-        monkeypatch.setenv("RATSPARSE_GATE_SHARED", form)
+        knobs.setenv("RATSPARSE_GATE_SHARED", form)
         idx2 = torch.full_like(idx, -9)
         rs.moba_select_prefill(s, tq, tkc, T, block, K, n_first, means, idx2, ws)
         assert torch.equal(idx2, idx), form
-    monkeypatch.delenv("RATSPARSE_GATE_SHARED")
+    knobs.delenv("RATSPARSE_GATE_SHARED")
 
     # block-sparse attention over the GPU's own routing
     out = torch.zeros(w.B, w.Hq, T, w.D, dtype=torch.bfloat16, device="cuda")
@@ -113,14 +113,14 @@ def test_moba_select_and_sparse_prefill(rs, monkeypatch, case):
     # regrouped by block, and - for up to 64 blocks of a multiple of 64 tokens - causal tiles
     # with a bit set of listed blocks per row
     for form in ("0", "1"):
-        monkeypatch.setenv("RATSPARSE_PREFILL_MASKED", form)
+        knobs.setenv("RATSPARSE_PREFILL_MASKED", form)
         out.zero_(), lse.zero_()
         rs.sparse_attn_prefill(s, tq, tkc, tvc, T, block, scale, idx, K, out, lse, ws)
         ok, worst = attn_close(to_np(out), oout)
         assert ok, (form, worst)
         np.testing.assert_allclose(to_np(lse), olse, rtol=2e-3, atol=2e-3)
         say("  sparse prefill, form", form, "worst relative row error", worst)
-    monkeypatch.delenv("RATSPARSE_PREFILL_MASKED")
+    knobs.delenv("RATSPARSE_PREFILL_MASKED")
     rs.sparse_attn_prefill(s, tq, tkc, tvc, T, block, scale, idx, K, out, lse, ws)  # the library's own choice
     assert attn_close(to_np(out), oout)[0]
 
@@ -177,11 +177,11 @@ def test_moba_exact_ties_pick_lowest_blocks(rs, K, n_first, block):
 
 
 @pytest.mark.parametrize("form", ["0", "1"])
-def test_lists_are_taken_as_given(rs, monkeypatch, form):
+def test_lists_are_taken_as_given(rs, knobs, form):
     """The attention follows the lists it is handed, whatever wrote them: rows whose own block is
     not listed do not attend it, rows with an empty list give zeros and a log-sum-exp of -inf,
     entries may come in any order.  Both forms of the routed kernel."""
-    monkeypatch.setenv("RATSPARSE_PREFILL_MASKED", form)
+    knobs.setenv("RATSPARSE_PREFILL_MASKED", form)
     w = synth.C4.scaled(B=1, Hq=4, Hkv=2, T=1536)
     T, block, K = 1536, 128, 4
     w, q, kc, vc = _setup(w, T, T)

@@ -82,7 +82,7 @@ CASES += _random_cases(20260528, 12)
 
 
 @pytest.mark.parametrize("case", range(len(CASES)))
-def test_meta_select_attend(rs, monkeypatch, case):
+def test_meta_select_attend(rs, knobs, case):
     w, T, Tcap, P, K, n_first, n_local = CASES[case]
     say("quest case", case, w.name, T, Tcap, P, K, n_first, n_local)
     w, kc, vc = _cache_from_oracle(w, T, Tcap)
@@ -131,8 +131,8 @@ def test_meta_select_attend(rs, monkeypatch, case):
     # picks by shape; the knobs force each)
     oout2, _ = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, gidx)
     for two_launch, one_wg in (("0", "0"), ("1", "0"), ("1", "1")):
-        monkeypatch.setenv("RATSPARSE_FUSED_TWO_LAUNCH", two_launch)
-        monkeypatch.setenv("RATSPARSE_FUSED_ONE_WG", one_wg)
+        knobs.setenv("RATSPARSE_FUSED_TWO_LAUNCH", two_launch)
+        knobs.setenv("RATSPARSE_FUSED_ONE_WG", one_wg)
         out2 = torch.zeros_like(out)
         idx2 = torch.full_like(idx, -7)
         rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out2, None, idx2, ws)
@@ -144,8 +144,8 @@ def test_meta_select_attend(rs, monkeypatch, case):
         assert torch.equal(out3, out2)  # same result when the selection is not emitted
         _, olse2 = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, gidx)
         np.testing.assert_allclose(to_np(lse3), olse2, rtol=1e-4, atol=1e-4)
-    monkeypatch.delenv("RATSPARSE_FUSED_TWO_LAUNCH")
-    monkeypatch.delenv("RATSPARSE_FUSED_ONE_WG")
+    knobs.delenv("RATSPARSE_FUSED_TWO_LAUNCH")
+    knobs.delenv("RATSPARSE_FUSED_ONE_WG")
     out4 = torch.zeros_like(out)
     rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, n_first, n_local, out4, None, None, ws)  # own choice
     assert attn_close(to_np(out4), oout2, 2e-2 if w.dtype == "bf16" else 1e-4)[0]
@@ -214,14 +214,14 @@ def test_scan_with_meta_equals_separate_page_meta(rs):
 @pytest.mark.parametrize("D", [128, 64])
 @pytest.mark.parametrize("P", [16, 32, 64, 128, 256, 512])
 @pytest.mark.parametrize("in_scan", ["1", "0"])
-def test_scan_runs_leave_the_page_bounds(rs, monkeypatch, in_scan, P, D, dtype, slab):
+def test_scan_runs_leave_the_page_bounds(rs, knobs, in_scan, P, D, dtype, slab):
     """Long runs with the page metadata: where the scan kernel can (pages of 16 tokens up
     to the chunk length, a start on a chunk boundary) the bounds leave with the states, else the
     touched pages are recomputed afterwards; runs of both kinds back to back, with ragged ends,
     must leave what one bulk pass over the final cache computes.  The knob switches the first
     kind off, so both paths see every run."""
-    monkeypatch.setenv("RATSPARSE_SCAN_META", in_scan)
-    monkeypatch.setenv("RATSPARSE_SCAN_SLAB", slab)
+    knobs.setenv("RATSPARSE_SCAN_META", in_scan)
+    knobs.setenv("RATSPARSE_SCAN_SLAB", slab)
     B, H = 2, 20  # 40 (batch, head) pairs: full-row chunks (128 tokens at 128 channels, 256 at 64)
     # (t0, T_new): aligned; aligned and a single chunk; unaligned; unaligned; unaligned and long
     runs = [(0, 256), (256, 100), (356, 156), (512, 521), (1033, 200), (1233, 3000)]  # 512: aligned for every form
@@ -298,7 +298,7 @@ def test_argument_errors_are_reported(rs):
 
 
 def test_random_selector_five_seeds(rs):
-    """The random selector of the paper's H2 analysis (Sec. 3): uniform K-subsets of the pages
+    """The random selector of the paper's H2 analysis (Sec. 2.3): uniform K-subsets of the pages
     drawn on the host, five seeds, evaluated through the listed-pages mode (Eq. 4 unchanged).
     Unsorted lists and a list that misses the newest page are legal inputs."""
     w, kc, vc = _cache_from_oracle(synth.C2.scaled(Hq=8, Hkv=2), 4096 + 5, 4096 + 64)

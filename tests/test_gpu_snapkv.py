@@ -59,7 +59,7 @@ CASES += _random_cases(20260528, 8)
 
 
 @pytest.mark.parametrize("case", range(len(CASES)))
-def test_snapkv_compress_then_decode(rs, monkeypatch, case):
+def test_snapkv_compress_then_decode(rs, knobs, case):
     w, T, Tcap, K_keep, pool = CASES[case]
     say("snapkv case", case, T, Tcap, K_keep, pool, "W", w.W)
     w, qw, kc, vc = _setup(w, T, Tcap)
@@ -92,11 +92,11 @@ def test_snapkv_compress_then_decode(rs, monkeypatch, case):
     assert torch.all(kco[:, :, K_keep + W:] == 0)
     # the other form of the selection (pooling + top-K in one workgroup per head for short
     # prefixes, or spread over workgroups; the library picks by length): the same bits
-    monkeypatch.setenv("RATSPARSE_SNAP_ONE_WG", "0")
+    knobs.setenv("RATSPARSE_SNAP_ONE_WG", "0")
     kco2, vco2, idx2, votes2 = torch.zeros_like(kco), torch.zeros_like(vco), torch.full_like(idx, -5), torch.zeros_like(votes)
     rs.snapkv_compress(s, to_dev(qw, "bf16"), to_dev(kc, "bf16"), to_dev(vc, "bf16"), T, W, K_keep, pool, scale,
                        kco2, vco2, Tco, idx2, votes2, ws)
-    monkeypatch.delenv("RATSPARSE_SNAP_ONE_WG")
+    knobs.delenv("RATSPARSE_SNAP_ONE_WG")
     assert torch.equal(idx2, idx) and torch.equal(votes2, votes)
     assert torch.equal(kco2, kco) and torch.equal(vco2, vco)
 

@@ -153,3 +153,34 @@ def test_group_score_bounds_the_groups_summed_logit_and_reduces_to_per_head():
         for kvh in range(Hkv):
             qsum = q[b, kvh * G:(kvh + 1) * G].astype(np.float64).sum(axis=0)
             np.testing.assert_allclose(s1[b, kvh], kc[b, kvh].astype(np.float64) @ qsum, rtol=1e-12, atol=1e-12)
+
+
+def test_head_hit_rate_definition():
+    """Sec. 2.3 (H1): a head scores 1 only if its selection holds the golden position at EVERY step.
+    Hand-made lists with known answers: a head that always holds it, one that misses once, one
+    without a golden position at some step, pages (unit 16) and tokens (unit 1)."""
+    # 1 sequence, 3 heads, 3 steps, pages of 16 tokens, 4 selected pages per head
+    idx = [np.array([[[0, 2, 5, 9], [0, 2, 5, 9], [1, 3, 4, 8]]]),
+           np.array([[[0, 2, 6, 9], [0, 3, 6, 9], [1, 3, 4, 8]]]),
+           np.array([[[0, 2, 6, 9], [0, 2, 6, 9], [1, 3, 4, 8]]])]
+    gold = [np.array([[5 * 16 + 3, 5 * 16 + 3, 4 * 16]]),        # page 5, 5, 4: all present
+            np.array([[2 * 16 + 15, 2 * 16 + 15, -1]]),          # page 2: head 1 misses it; head 2 has none
+            np.array([[9 * 16, 9 * 16, 8 * 16 + 1]])]            # page 9, 9, 8: all present
+    hit = oracle.head_hit(idx, gold, unit=16)
+    assert hit.tolist() == [[True, False, True]]
+    # the same lists read as token lists (unit 1): only exact positions count
+    hit1 = oracle.head_hit(idx, [np.array([[5, 5, 4]]), np.array([[2, 2, -1]]), np.array([[9, 9, 7]])], unit=1)
+    assert hit1.tolist() == [[True, False, False]]
+    # one step: the hit is plain membership; against a brute-force check on random lists
+    r = np.random.default_rng(3)
+    for _ in range(20):
+        M, K, B, H = 40, 7, 2, 3
+        lists = np.stack([[np.sort(r.choice(M, K, replace=False)) for _ in range(H)] for _ in range(B)])
+        g = r.integers(0, M * 4, (B, H))
+        want = np.array([[(g[b, h] // 4) in lists[b, h].tolist() for h in range(H)] for b in range(B)])
+        assert np.array_equal(oracle.head_hit([lists], [g], unit=4), want)
+    # a uniformly random selector holds a given candidate with probability K / M per step
+    M, K, n = 64, 16, 4000
+    lists = np.stack([np.sort(r.choice(M, K, replace=False)) for _ in range(n)])[None]
+    rate = oracle.head_hit([lists], [np.full((1, n), 37)], unit=1).mean()
+    assert abs(rate - K / M) < 0.03
