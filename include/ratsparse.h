@@ -63,13 +63,18 @@ enum {
     RS_UNSUPPORTED = 2,         /* D not in {64,128}, page / block size not supported, dtype unknown */
     RS_WORKSPACE_TOO_SMALL = 3, /* ws == NULL or ws_bytes below <entry>_workspace_bytes() */
     RS_LAUNCH_FAILED = 4,       /* hipGetLastError() after a launch */
-    RS_ASYNC_TIMEOUT = 5        /* reported by ratsparse_async_status(): a bounded in-kernel wait expired */
+    RS_ASYNC_TIMEOUT = 5,       /* reported by ratsparse_async_status(): a bounded in-kernel wait expired */
+    RS_SCRATCH_LIMIT = 6        /* sparse_attn_decode_static: the shape needs more than RS_STATIC_SCRATCH_BYTES */
 };
 
 enum { RS_F32 = 0, RS_BF16 = 1 };
 
 /* bytes at the start of every workspace reserved for control words */
 #define RS_WS_CTRL_BYTES 65536
+
+/* size of the library's own scratch array, used by sparse_attn_decode_static only (16 MiB of
+ * device memory on every GPU the library runs on, held until the process ends) */
+#define RS_STATIC_SCRATCH_BYTES (16u << 20)
 
 typedef struct rs_shape {
     int32_t B;     /* batch */
@@ -167,6 +172,31 @@ int32_t sparse_attn_decode(const rs_shape *s, const void *q, const void *k_cache
                            const int32_t *idx, int32_t K, const void *meta, int32_t n_first,
                            int32_t n_local, void *out, float *lse_out, int32_t *idx_out,
                            void *ws, size_t ws_bytes, void *stream);
+
+/* ---- sparse_attn_decode without a workspace and without any allocation ------------------
+ * For callers that cannot allocate or size device memory at the call: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same three modes, same
+ * kernels and same results as sparse_attn_decode; the scratch (control words, tagged scores,
+ * tagged page lists, split partials) is a device array of RS_STATIC_SCRATCH_BYTES inside the
+ * library instead of the caller's workspace.  The call itself allocates and frees nothing
+ * (no hipMalloc, no hipFree, no library routine that allocates); the first call on a
+ * device looks up that device's copy of the array.
+ *   async_err  device uint32, caller-owned, required: set to 1 by a kernel whose bounded wait
+ *              expired (outputs then undefined); the caller zeroes it and reads it after
+ *              synchronising.  It stands in for ratsparse_async_status(), which needs a workspace.
+ * Limit: sparse_attn_decode_workspace_bytes(s, T_valid, K) (K = 0 in the dense mode) must not
+ * exceed RS_STATIC_SCRATCH_BYTES, else RS_SCRATCH_LIMIT and nothing is enqueued.  B = 4 with
+ * 32 heads at 64K tokens, 16-token pages, K = 1024 needs 14.2 MiB.
+ * Every call on a GPU uses that GPU's one array: calls that can overlap on one GPU (two
+ * streams, two host threads) race and must be serialised by the caller.  The array keeps
+ * the previous call's contents; each call first clears the control words with a small
+ * kernel (not a memset node), so a call that gave up a wait does not poison the next.
+ * Like sparse_attn_decode it draws a fresh tag per call: call it, do not replay it. */
+int32_t sparse_attn_decode_static(const rs_shape *s, const void *q, const void *k_cache,
+                                  const void *v_cache, int64_t T_valid, float scale,
+                                  const int32_t *idx, int32_t K, const void *meta, int32_t n_first,
+                                  int32_t n_local, void *out, float *lse_out, int32_t *idx_out,
+                                  uint32_t *async_err, void *stream);
 
 /* ---- Group-shared Quest selection (an option for grouped-query attention) --------------
  * Not in the paper, which selects per query head (Sec. 2.2 and 2.3 define the selected set per head);

@@ -12,6 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libratsparse.so")
 
 RS_F32, RS_BF16 = 0, 1
 RS_WS_CTRL_BYTES = 65536
+RS_STATIC_SCRATCH_BYTES = 16 << 20
 
 _lib = None
 
@@ -50,6 +51,8 @@ SIGNATURES = {
     "sparse_attn_decode_workspace_bytes": (_sz, [_shp, _i64, _i32]),
     "sparse_attn_decode": (_i32, [_shp, _vp, _vp, _vp, _i64, _f32, _vp, _i32, _vp, _i32, _i32, _vp,
                                   _vp, _vp, _vp, _sz, _vp]),
+    "sparse_attn_decode_static": (_i32, [_shp, _vp, _vp, _vp, _i64, _f32, _vp, _i32, _vp, _i32, _i32, _vp,
+                                         _vp, _vp, _vp, _vp]),
     "rat_decode_step_workspace_bytes": (_sz, [_shp, _i64, _i32]),
     "rat_decode_state_set": (_i32, [_vp, _sz, _i64, _vp]),
     "rat_decode_state_get": (_i32, [_vp, ctypes.POINTER(ctypes.c_int64), _vp]),
@@ -210,6 +213,13 @@ def sparse_attn_decode(s, q, k_cache, v_cache, T_valid, scale, idx, K, meta, n_f
     _check(load().sparse_attn_decode(ctypes.byref(s), _ptr(q), _ptr(k_cache), _ptr(v_cache), T_valid,
                                      scale, _ptr(idx), K, _ptr(meta), n_first, n_local, _ptr(out),
                                      _ptr(lse_out), _ptr(idx_out), ws.ptr, ws.nbytes, _stream()))
+
+
+def sparse_attn_decode_static(s, q, k_cache, v_cache, T_valid, scale, idx, K, meta, n_first, n_local, out,
+                              lse_out, idx_out, async_err):
+    _check(load().sparse_attn_decode_static(ctypes.byref(s), _ptr(q), _ptr(k_cache), _ptr(v_cache), T_valid,
+                                            scale, _ptr(idx), K, _ptr(meta), n_first, n_local, _ptr(out),
+                                            _ptr(lse_out), _ptr(idx_out), _ptr(async_err), _stream()))
 
 
 def moba_select_prefill_workspace_bytes(s, T, block):

@@ -211,7 +211,8 @@ static DecodeLayout decode_layout(const rs_shape *s, long T_valid, int K)
 // T_valid tokens laid out by L; returns the grid
 static long fused_setup(FusedParams &prm, const rs_shape *s, const DecodeLayout &L, char *w, const void *q,
                         const void *meta, const void *k_cache, const void *v_cache, void *out, float *lse_out,
-                        int32_t *idx_out, long T_valid, int K, int n_first, int n_local, float scale)
+                        int32_t *idx_out, long T_valid, int K, int n_first, int n_local, float scale,
+                        uint32_t *err = nullptr)
 {
     const long units = (long)s->B * s->Hq;
     uint32_t *ctr_score = (uint32_t *)w + kCtrlUnit0;
@@ -223,7 +224,7 @@ static long fused_setup(FusedParams &prm, const rs_shape *s, const DecodeLayout 
     prm.partial = (uint64_t *)(w + L.off_partial);
     prm.ctr_score = ctr_score; prm.ctr_att = ctr_att;
     prm.ticket = (uint32_t *)w + kCtrlTicket; prm.done = (uint32_t *)w + kCtrlDone;
-    prm.err = (uint32_t *)w + kCtrlAsyncErr;
+    prm.err = err ? err : (uint32_t *)w + kCtrlAsyncErr;
     prm.Hq = s->Hq; prm.Hkv = s->Hkv; prm.units = (int)units;
     prm.Tcap = s->Tcap; prm.Np_cap = s->Tcap / s->P; prm.T_valid = T_valid;
     prm.P = s->P; prm.Np = L.Np; prm.K = K; prm.n_first = n_first; prm.n_local = n_local;
@@ -296,6 +297,7 @@ const char *ratsparse_status_string(int32_t status)
         case RS_WORKSPACE_TOO_SMALL: return "workspace too small";
         case RS_LAUNCH_FAILED: return "kernel launch failed";
         case RS_ASYNC_TIMEOUT: return "a bounded in-kernel wait expired";
+        case RS_SCRATCH_LIMIT: return "the shape needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }
@@ -469,7 +471,7 @@ size_t sparse_attn_decode_workspace_bytes(const rs_shape *s, int64_t T_valid, in
 static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, const void *k_cache, const void *v_cache,
                                 int64_t T_valid, float scale, const int32_t *idx, int32_t K, const void *meta,
                                 int32_t n_first, int32_t n_local, void *out, float *lse_out, int32_t *idx_out,
-                                void *ws, size_t ws_bytes, void *stream)
+                                void *ws, size_t ws_bytes, void *stream, uint32_t *err_word = nullptr)
 {
     int st = check_shape(s, true);
     if (st != RS_OK) return st;
@@ -492,6 +494,7 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     char *w = (char *)ws;
     uint32_t *ctr_score = (uint32_t *)w + kCtrlUnit0;
     uint32_t *ctr_att = ctr_score + kMaxUnits;
+    uint32_t *err = err_word ? err_word : (uint32_t *)w + kCtrlAsyncErr;  // where an expired in-kernel wait is recorded
     const long units = (long)s->B * s->Hq;
     const int32_t *use_idx = idx;
     const uint32_t tag = next_tag();
@@ -523,7 +526,7 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
         // one persistent launch: score -> select -> attend, handed over through tagged words
         FusedParams prm;
         const long grid = fused_setup(prm, s, L, w, q, meta, k_cache, v_cache, out, lse_out, idx_out, T_valid, K, n_first,
-                                      n_local, scale);
+                                      n_local, scale, err);
         prm.tag = tag;
         st = decode_fused_dispatch(s->dtype, s->D, prm, L.Np, (int)grid, (hipStream_t)stream);
         if (st != RS_OK) return st;
@@ -533,8 +536,7 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
         int32_t *sel = idx_out ? idx_out : (int32_t *)(w + L.off_idx);
         st = score_select_dispatch(s->dtype, s->D, GQ, q, meta, (uint64_t *)(w + L.off_scores), nullptr, sel, s->B,
                                    s->Hq, s->Hkv, s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score,
-                                   ctr_score, (uint32_t *)w + kCtrlAsyncErr, tag, g_spin_limit.load(),
-                                   (hipStream_t)stream);
+                                   ctr_score, err, tag, g_spin_limit.load(), (hipStream_t)stream);
         if (st != RS_OK) return st;
         if (launch_status() != RS_OK) return RS_LAUNCH_FAILED;
         use_idx = sel;
@@ -553,8 +555,7 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     if (splits > L.splits_att_max) splits = L.splits_att_max;
     decode_attend_dispatch(s->dtype, s->D, q, k_cache, v_cache, use_idx, out, lse_out,
                            (uint64_t *)(w + L.off_partial), s->B, s->Hq, s->Hkv, s->Tcap, s->P, T_valid, K, scale,
-                           splits, ctr_att, (uint32_t *)w + kCtrlAsyncErr, tag, g_spin_limit.load(), group ? 1 : 0,
-                           (hipStream_t)stream);
+                           splits, ctr_att, err, tag, g_spin_limit.load(), group ? 1 : 0, (hipStream_t)stream);
     return launch_status();
 }
 
@@ -574,6 +575,66 @@ int32_t sparse_attn_decode_group(const rs_shape *s, const void *q, const void *k
 {
     return attn_decode_impl(true, s, q, k_cache, v_cache, T_valid, scale, idx, K, meta, n_first, n_local, out,
                             lse_out, idx_out, ws, ws_bytes, stream);
+}
+
+// ---- the entry point that allocates nothing -------------------------------------------------
+// sparse_attn_decode for callers that can neither allocate nor bring a workspace: its scratch
+// (control words, tagged scores, tagged page lists, split partials) is the file-scope device
+// array below.  In host code the array's name is only a stand-in: the device address is taken
+// once per device with hipGetSymbolAddress and kept; kernels, clears and copies use that address.
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char scratch[RS_STATIC_SCRATCH_BYTES];
+
+namespace rs {
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];  // per device: the address of that device's copy of `scratch`
+static std::mutex g_scratch_mutex;
+
+// device address of the current device's scratch array (resolved on the first call per device)
+static int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RS_LAUNCH_FAILED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return RS_LAUNCH_FAILED;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return RS_OK;
+}
+}  // namespace rs
+
+extern "C" {
+
+int32_t sparse_attn_decode_static(const rs_shape *s, const void *q, const void *k_cache, const void *v_cache,
+                                  int64_t T_valid, float scale, const int32_t *idx, int32_t K, const void *meta,
+                                  int32_t n_first, int32_t n_local, void *out, float *lse_out, int32_t *idx_out,
+                                  uint32_t *async_err, void *stream)
+{
+    int st = check_shape(s, true);
+    if (st != RS_OK) return st;
+    if (T_valid <= 0 || T_valid > s->Tcap) return RS_INVALID_ARG;
+    if (!async_err || (reinterpret_cast<uintptr_t>(async_err) & 3u)) return RS_INVALID_ARG;
+    const bool uses_list = idx != nullptr || meta != nullptr;
+    if (uses_list && K < 1) return RS_INVALID_ARG;
+    // the layout sparse_attn_decode would ask a workspace for must fit the static array
+    if (decode_layout(s, T_valid, uses_list ? K : 0).total > (size_t)RS_STATIC_SCRATCH_BYTES) return RS_SCRATCH_LIMIT;
+    void *ptr = nullptr;
+    st = static_scratch(&ptr);
+    if (st != RS_OK) return st;
+    // the array keeps what the last call (or a call that gave up a wait) left: the control words
+    // must start at zero.  A fill kernel, not a memset, so that the call can sit in a captured graph.
+    const long n = RS_WS_CTRL_BYTES / 4;
+    fill_zero_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>((uint32_t *)ptr, n);
+    if (launch_status() != RS_OK) return RS_LAUNCH_FAILED;
+    return attn_decode_impl(false, s, q, k_cache, v_cache, T_valid, scale, idx, K, meta, n_first, n_local, out,
+                            lse_out, idx_out, ptr, (size_t)RS_STATIC_SCRATCH_BYTES, stream, async_err);
 }
 
 size_t rat_decode_step_workspace_bytes(const rs_shape *s, int64_t T_max, int32_t K)

@@ -215,15 +215,15 @@ def test_out_of_range_knob_values_are_clamped(rs, knobs):
         return kc, vc, sk, sv, meta, idx, out
 
     want = run()
-    for knobs in ({"RATSPARSE_SCAN_GRID": "-1", "RATSPARSE_FUSED_GRID": "-3", "RATSPARSE_FUSED_FINE_PCT": "500"},
+    for values in ({"RATSPARSE_SCAN_GRID": "-1", "RATSPARSE_FUSED_GRID": "-3", "RATSPARSE_FUSED_FINE_PCT": "500"},
                   {"RATSPARSE_SCAN_GRID": "1000000000", "RATSPARSE_FUSED_GRID": "0", "RATSPARSE_FUSED_FINE_PCT": "-7",
                    "RATSPARSE_META_SPW": "1000000"}):
-        say("knobs", knobs)
-        for name, value in knobs.items():
+        say("knobs", values)
+        for name, value in values.items():
             knobs.setenv(name, value)
         got = run()
         for a, b in zip(got[:6], want[:6]):
             assert torch.equal(a, b)
         assert torch.allclose(got[6].float(), want[6].float(), rtol=2e-2, atol=2e-2)
-        for name in knobs:
+        for name in values:
             knobs.delenv(name)
