@@ -73,6 +73,15 @@ def test_every_entry_point_rejects_bad_arguments_before_touching_the_gpu():
     assert lib.sparse_attn_decode(sp, A, A, A, 256, 0.1, None, 4, A, 1, 1, None, None, None, A, big, None) == 1
     assert lib.sparse_attn_decode(sp, A, A, A, 256, 0.1, None, 4, A, 1, 1, A, None, None, A, 16, None) == 3
 
+    # sparse_attn_decode_static(s, q, k_cache, v_cache, T_valid, scale, idx, K, meta, n_first, n_local, out,
+    #                           lse_out, idx_out, async_err, stream): validation precedes any GPU call
+    assert lib.sparse_attn_decode_static(sp, A, A, A, 256, 0.1, None, 4, A, 1, 1, A, None, None, None, None) == 1
+    assert lib.sparse_attn_decode_static(sp, A, A, A, 257, 0.1, None, 4, A, 1, 1, A, None, None, A, None) == 1
+    assert lib.sparse_attn_decode_static(sp, A, A, A, 256, 0.1, None, 0, A, 1, 1, A, None, None, A, None) == 1
+    huge = binding.make_shape(16, 32, 32, 128, 66048, 16, binding.RS_BF16)
+    assert lib.sparse_attn_decode_static(ctypes.byref(huge), A, A, A, 66048, 0.1, None, 1024, A, 1, 1, A, None, None,
+                                         A, None) == 6  # more scratch than the static array holds
+
     # rat_decode_step(s, k, v, g, state_k, state_v, k_cache, v_cache, meta, q, scale, K, n_first, n_local,
     #                 T_max, out, lse_out, idx_out, ws, ws_bytes, stream)
     assert lib.rat_decode_step(sp, A, A, A, A, A, A, A, None, A, 0.1, 4, 1, 1, 256, A, None, None, A, big, None) == 1
