@@ -332,9 +332,44 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                         publish_f32(&part[1], L, tag_);
                     }
                 }
-            } else if (S_att > 1 && tid < D) {
-                merge_partials(a.partial + (long)unit * a.S_max * (D + 2), S_att - 1, D + 2, tid, tag_, a.spin_limit,
-                               a.err, M, L, O);
+            } else if (S_att > 1) {
+                // the other slices' partials: the kFusedThreads / D thread groups take every NG-th one each
+                // (one round trip for up to 4 NG partials instead of one per four), then fold through LDS
+                // (the selection's scratch is free during an attend item)
+                constexpr int NG = kFusedThreads / D;
+                static_assert(sizeof(SelectShared<kFusedThreads>) >= sizeof(float) * 3 * NG * D, "fold buffer");
+                float *fold = reinterpret_cast<float *>(&sh);
+                const int g = tid / D, ch = tid % D;
+                float Mg = -INFINITY, Lg = 0.f, Og = 0.f;
+                if (g == 0) {
+                    Mg = M;
+                    Lg = L;
+                    Og = O;
+                }
+                merge_partials(a.partial + (long)unit * a.S_max * (D + 2), S_att - 1, D + 2, ch, tag_, a.spin_limit,
+                               a.err, Mg, Lg, Og, g, NG);
+                if (g > 0) {
+                    fold[(g * 3 + 0) * D + ch] = Mg;
+                    fold[(g * 3 + 1) * D + ch] = Lg;
+                    fold[(g * 3 + 2) * D + ch] = Og;
+                }
+                __syncthreads();
+                if (g == 0) {
+#pragma unroll
+                    for (int gg = 1; gg < NG; ++gg) {
+                        const float m2 = fold[(gg * 3 + 0) * D + ch], l2 = fold[(gg * 3 + 1) * D + ch],
+                                    o2 = fold[(gg * 3 + 2) * D + ch];
+                        const float mn = fmaxf(Mg, m2);
+                        const float a1 = (Mg == -INFINITY) ? 0.f : __expf(Mg - mn);
+                        const float a2 = (m2 == -INFINITY) ? 0.f : __expf(m2 - mn);
+                        Lg = Lg * a1 + l2 * a2;
+                        Og = Og * a1 + o2 * a2;
+                        Mg = mn;
+                    }
+                    M = Mg;
+                    L = Lg;
+                    O = Og;
+                }
             }
             mark(item, 6);
             if (finish && tid < D) {

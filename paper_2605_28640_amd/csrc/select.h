@@ -215,7 +215,9 @@ __device__ __forceinline__ void gather_page_keys(const uint64_t *srow, int Np, i
                                                  uint32_t tag, int spin_limit, uint32_t *err, float *scores_out,
                                                  uint32_t *keys)
 {
-    constexpr int BATCH = 8;
+    // ten loads in flight per thread: 4096 + a few pages of 16 tokens (a 64K context that has grown
+    // by some steps) still come in with one round trip
+    constexpr int BATCH = 10;
     const int tid = threadIdx.x;
     for (int p0 = tid; p0 < Np; p0 += BATCH * NT) {
         uint64_t wd[BATCH];
@@ -238,27 +240,29 @@ __device__ __forceinline__ void gather_page_keys(const uint64_t *srow, int Np, i
     __syncthreads();
 }
 
-// Fold S published partials (m, l, o[channel]) of one unit into (M, L, O) for channel `ch`
-// (start from M = -inf, L = O = 0, or from the caller's own partial): words are fetched
-// four splits at a time, stragglers polled.  partial layout per split: word 0 = m,
-// word 1 = l, word 2 + c = o[c].
+// Fold published partials (m, l, o[channel]) of one unit into (M, L, O) for channel `ch`
+// (start from M = -inf, L = O = 0, or from the caller's own partial): of the S partials
+// those numbered first, first + step, ... (so that several thread groups can share the
+// work); words are fetched four splits at a time, stragglers polled.  partial layout per
+// split: word 0 = m, word 1 = l, word 2 + c = o[c].
 __device__ __forceinline__ void merge_partials(const uint64_t *pu, int S, int stride, int ch, uint32_t tag,
-                                               int spin_limit, uint32_t *err, float &M, float &L, float &O)
+                                               int spin_limit, uint32_t *err, float &M, float &L, float &O,
+                                               int first = 0, int step = 1)
 {
-    for (int s0 = 0; s0 < S; s0 += 4) {
+    for (int s0 = first; s0 < S; s0 += 4 * step) {
         uint64_t wm[4], wl[4], wo[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint64_t *p = pu + (long)(s0 + j) * stride;
-            const bool in = s0 + j < S;
+            const uint64_t *p = pu + (long)(s0 + j * step) * stride;
+            const bool in = s0 + j * step < S;
             wm[j] = in ? load_u64_agent(p) : 0ull;
             wl[j] = in ? load_u64_agent(p + 1) : 0ull;
             wo[j] = in ? load_u64_agent(p + 2 + ch) : 0ull;
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (s0 + j < S) {
-                const uint64_t *p = pu + (long)(s0 + j) * stride;
+            if (s0 + j * step < S) {
+                const uint64_t *p = pu + (long)(s0 + j * step) * stride;
                 float ms = __uint_as_float((uint32_t)wm[j]), ls = __uint_as_float((uint32_t)wl[j]),
                       os = __uint_as_float((uint32_t)wo[j]);
                 if ((uint32_t)(wm[j] >> 32) != tag) ms = acquire_f32(p, tag, spin_limit, err);
