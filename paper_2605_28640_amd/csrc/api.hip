@@ -230,7 +230,7 @@ static long fused_setup(FusedParams &prm, const rs_shape *s, const DecodeLayout 
     prm.P = s->P; prm.Np = L.Np; prm.K = K; prm.n_first = n_first; prm.n_local = n_local;
     const Knobs &kn = knobs();
     int ss = knob_or(kn.fused_sscore, 0), sa = knob_or(kn.fused_satt, 0);
-    if (ss <= 0) ss = (L.Np + 511) / 512;                      // ~512 pages (256 KiB of bf16 metadata) per item
+    if (ss <= 0) ss = (L.Np + 351) / 352;                      // ~350 pages (176 KiB of bf16 metadata) per item
     if (sa <= 0) sa = (int)(((long)K * (s->P / 16) + 31) / 32);  // ~32 tiles (256 KiB of bf16 K+V) per item
     if (ss > L.Np) ss = L.Np;
     if (sa > kMaxAttSplits) sa = kMaxAttSplits;
