@@ -23,5 +23,16 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+def build_sanitized(out: str) -> str:
+    """The same sources with AddressSanitizer and UndefinedBehaviorSanitizer (host code only), into
+    `out`; a test loads it in a child process through RATSPARSE_REF_LIB."""
+    srcs = [os.path.join(HERE, s) for s in SOURCES]
+    cmd = ["gcc", "-std=c11", "-O1", "-g", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+           "-Wall", "-Wextra", "-o", out] + srcs + ["-lm"]
+    subprocess.run(cmd, check=True)
+    return out
+
+
 if __name__ == "__main__":
     print(build(force="--if-stale" not in sys.argv))
