@@ -39,7 +39,7 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
     const ST *__restrict__ k, const ST *__restrict__ v, const float *__restrict__ g,
     float *__restrict__ state_k, float *__restrict__ state_v, ST *__restrict__ k_cache,
     ST *__restrict__ v_cache, int BH, long T_new, long t0, long Tcap, int n_chunks,
-    uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit, ST *__restrict__ meta)
+    uint32_t *ctrl, uint64_t *rec, uint32_t tag, int spin_limit, ST *__restrict__ meta, int deep)
 {
     constexpr bool META = PAGE > 0;
     constexpr int TW = (64 / (DS / 8)) * NT;  // tokens of a wave
@@ -62,43 +62,81 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
     const int rg = lane / LPR;
     const int c0 = (lane % LPR) * 8;
 
-    // persistent workgroups: each keeps taking the next chunk until none is left
+    // deep (many units, so every chain has slack): the waves that do not handle the chain send the next
+    // chunk's loads out before the current chunk is touched, and the ticket after next is drawn a chunk
+    // ahead; otherwise all loads of the next chunk go out behind the chain step.
+    // Persistent workgroups: each keeps taking the next chunk (by ticket) until none is left.  The raw
+    // inputs of a chunk live in registers from its loads to its replay; there are two such register sets,
+    // and the loads of the NEXT ticket are issued before the current chunk is folded, chained and stored,
+    // so that a workgroup always has a chunk's worth of reads in flight (one workgroup fills a CU: without
+    // this its memory pipe idles through every fold, chain wait and replay).  The prefetched ticket is
+    // larger than the one in work and tickets are handed out in increasing order, so the smallest
+    // unfinished ticket is always some workgroup's chunk in work: the chain cannot deadlock.
     const int units = BH * NS;
     const int total = units * n_chunks;
-    for (;;) {
-    int ticket = blockIdx.x;
-    if (n_chunks > 1) {
-        __syncthreads();  // the previous chunk's LDS traffic is over
+    // (kept as 32-bit words: the sets are carried around the chunk loop, and this compiler's back end
+    // fails on loop-carried 128-bit vector values)
+    constexpr int KW = (int)(sizeof(typename R::raw_t) / 4);
+    struct ChunkRegs {
+        uint32_t kw[NT][KW], vw[NT][KW];
+        float gw[NT][8];
+    };
+    auto next_ticket = [&]() __attribute__((always_inline)) -> int {
+        __syncthreads();  // the previous use of s_ticket (and of the chunk's LDS) is over
         if (tid == 0) s_ticket = (int)atomicAdd(&ctrl[kCtrlTicket], 1u);
         __syncthreads();
-        ticket = s_ticket;
-        if (ticket >= total) break;
-    }
+        return s_ticket;
+    };
+    auto load_chunk = [&](int ticket, ChunkRegs &r) __attribute__((always_inline)) {
+        const int j = ticket / units;
+        const int unit = ticket % units;
+        const int bh = unit / NS;
+        const int ch0 = (unit % NS) * DS;
+        const long tbase = (long)j * CHUNK + (long)(wave * RPW + rg) * NT;
+        const long in_row0 = (long)bh * T_new;
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const long t = tbase + i;
+            typename R::raw_t kq = R::zero_raw(), vq = R::zero_raw();
+            float4 ga = make_float4(1.f, 1.f, 1.f, 1.f), gb = ga;  // past the end: the identity element (g = 1 keeps the state)
+            if (t < T_new) {
+                const long off = (in_row0 + t) * D + ch0 + c0;
+                kq = R::load_raw(k + off);
+                vq = R::load_raw(v + off);
+                ga = *reinterpret_cast<const float4 *>(g + off);
+                gb = *reinterpret_cast<const float4 *>(g + off + 4);
+            }
+            __builtin_memcpy(r.kw[i], &kq, sizeof(kq));
+            __builtin_memcpy(r.vw[i], &vq, sizeof(vq));
+            r.gw[i][0] = ga.x; r.gw[i][1] = ga.y; r.gw[i][2] = ga.z; r.gw[i][3] = ga.w;
+            r.gw[i][4] = gb.x; r.gw[i][5] = gb.y; r.gw[i][6] = gb.z; r.gw[i][7] = gb.w;
+        }
+    };
+    // nt / nr: the next ticket and its register set (nt >= total: none).  The waves that handle the chain
+    // (threads below DS) issue their share of the next chunk's loads only after the chain step: a wave's
+    // loads return in order, so its polls of the predecessor's record would otherwise wait behind them.
+    constexpr int kChainWaves = (DS + 63) / 64;
+    auto process_chunk = [&](int ticket, ChunkRegs &r, int nt, ChunkRegs &nr) __attribute__((always_inline)) {
     const int j = ticket / units;   // chunk index along T
     const int unit = ticket % units;  // consecutive tickets walk the units first
     const int bh = unit / NS;
     const int ch0 = (unit % NS) * DS;  // first channel of the slab
-
     const long tbase = (long)j * CHUNK + (long)(wave * RPW + rg) * NT;
-    const long in_row0 = (long)bh * T_new;
-
     typename R::raw_t kr[NT], vr[NT];
     float4 g0[NT], g1[NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
-        const long t = tbase + i;
-        if (t < T_new) {
-            const long off = (in_row0 + t) * D + ch0 + c0;
-            kr[i] = R::load_raw(k + off);
-            vr[i] = R::load_raw(v + off);
-            g0[i] = *reinterpret_cast<const float4 *>(g + off);
-            g1[i] = *reinterpret_cast<const float4 *>(g + off + 4);
-        } else {  // past the end: the identity element (g = 1 keeps the state)
-            kr[i] = R::zero_raw();
-            vr[i] = R::zero_raw();
-            g0[i] = make_float4(1.f, 1.f, 1.f, 1.f);
-            g1[i] = g0[i];
-        }
+        __builtin_memcpy(&kr[i], r.kw[i], sizeof(kr[i]));
+        __builtin_memcpy(&vr[i], r.vw[i], sizeof(vr[i]));
+        g0[i] = make_float4(r.gw[i][0], r.gw[i][1], r.gw[i][2], r.gw[i][3]);
+        g1[i] = make_float4(r.gw[i][4], r.gw[i][5], r.gw[i][6], r.gw[i][7]);
+    }
+
+    // the ticket after next is drawn now and parked in LDS at the first barrier: its round trip runs
+    // under the fold (full-row form; the slab form draws its tickets one at a time)
+    int ticket_ahead = 0;
+    if constexpr (DS == D) {
+        if (deep && tid == 0) ticket_ahead = (int)atomicAdd(&ctrl[kCtrlTicket], 1u);
     }
 
     // first look at the previous chunk's outgoing state, issued behind the data loads so that
@@ -166,6 +204,9 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         bk[c] = (rg == 0) ? 0.f : pk;
         bv[c] = (rg == 0) ? 0.f : pv;
     }
+    if constexpr (DS == D) {
+        if (deep && tid == 0) s_ticket = ticket_ahead;
+    }
     __syncthreads();
 
     if (tid < DS) {
@@ -217,6 +258,11 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
             ck = fmaf(aw, ck, s_agg[w][1][c]);
             cv = fmaf(aw, cv, s_agg[w][2][c]);
         }
+    }
+    // the next chunk's loads go out here, behind the chain step: a wave's loads return in order, so
+    // issued any earlier they would hold up the chain waves' polls of the predecessor's record
+    if constexpr (DS == D) {  // (the slab form works on one chunk at a time)
+        if ((wave < kChainWaves || !deep) && nt < total) load_chunk(nt, nr);
     }
     __syncthreads();
 
@@ -328,8 +374,44 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         }
     }
 
-    if (n_chunks == 1) break;
-    }  // chunk loop
+    };  // process_chunk
+
+    // (one call site of process_chunk: the register sets change places by moves, which cost nothing next
+    // to a chunk's work and wait for the prefetched loads no earlier than the fold would)
+    ChunkRegs A, B;
+    int tA = (int)blockIdx.x;  // one chunk per unit: the grid is the units, no tickets
+    if (n_chunks > 1) tA = next_ticket();
+    if (tA < total) {
+        load_chunk(tA, A);
+        int tB = total;
+        if constexpr (DS == D) {
+            if (n_chunks > 1) tB = next_ticket();
+        }
+        for (;;) {
+            if constexpr (DS == D) {
+                // the waves that do not handle the chain send the next chunk's loads ahead of everything
+                if (deep && wave >= kChainWaves && tB < total) load_chunk(tB, B);
+            }
+            process_chunk(tA, A, tB, B);
+            if constexpr (DS == D) {
+                if (tB >= total) break;
+                A = B;
+                tA = tB;
+                if (deep) {
+                    __syncthreads();  // s_ticket was parked before the first barrier of process_chunk and is read by all here
+                    tB = s_ticket;
+                    __syncthreads();  // ... before the next chunk's thread 0 parks the following one
+                } else {
+                    tB = next_ticket();
+                }
+            } else {
+                if (n_chunks == 1) break;
+                tA = next_ticket();
+                if (tA >= total) break;
+                load_chunk(tA, A);
+            }
+        }
+    }
 
     if (n_chunks > 1 && tid == 0) {
         if (atomicAdd(&ctrl[kCtrlDone], 1u) == gridDim.x - 1u) {  // last workgroup out resets the counters
@@ -414,7 +496,7 @@ static int launch_scan(const void *k, const void *v, const float *g, float *stat
     }
     rat_scan_chunk_kernel<ST, D, DS, NT, NW, PAGE><<<dim3((unsigned)grid), dim3(NW * 64), 0, stream>>>(
         (const ST *)k, (const ST *)v, g, state_k, state_v, (ST *)k_cache, (ST *)v_cache, BH, T_new,
-        t0, Tcap, n_chunks, ctrl, rec, tag, spin_limit, (ST *)meta);
+        t0, Tcap, n_chunks, ctrl, rec, tag, spin_limit, (ST *)meta, (n_chunks > 1 && (long)BH * (D / DS) >= 128) ? 1 : 0);
     return 0;
 }
 
