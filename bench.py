@@ -106,14 +106,20 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     scan_first_ms = e0.elapsed_time(e1)  # first touch of 12 GB of fresh allocations
-    sk.zero_()
-    sv.zero_()  # a fresh sequence again: the second pass writes the same cache
-    torch.cuda.synchronize()
-    e0.record()
-    rs.rat_scan(s, tk, tv, tg, sk, sv, kc, vc, 0, T, ws)
-    e1.record()
-    rs.quest_page_meta(s, kc, meta, 0, T)
-    e2.record()
+    # a fresh sequence again (the passes rewrite the same cache): three timed calls, the median counts
+    scan_runs = []
+    for r in range(3):
+        sk.zero_()
+        sv.zero_()
+        torch.cuda.synchronize()
+        e0.record()
+        rs.rat_scan(s, tk, tv, tg, sk, sv, kc, vc, 0, T, ws)
+        e1.record()
+        if r == 2:
+            rs.quest_page_meta(s, kc, meta, 0, T)
+            e2.record()
+        torch.cuda.synchronize()
+        scan_runs.append(e0.elapsed_time(e1))
     # the same bulk pass three more times (it rewrites the same rows): the first call runs right
     # behind the scan, the repeats show the kernel on its own
     meta_ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
@@ -131,14 +137,15 @@ def main():
     e4.record()
     torch.cuda.synchronize()
     ws.async_status()
-    scan_ms, meta_first_ms = e0.elapsed_time(e1), e1.elapsed_time(e2)
+    scan_ms, meta_first_ms = sorted(scan_runs)[1], e1.elapsed_time(e2)
     scan_meta_ms = e3.elapsed_time(e4)
     meta_ms = sorted(meta_ev[r].elapsed_time(meta_ev[r + 1]) for r in range(3))[1]
     scan_bytes = B * Hkv * T * D * 12  # read k, v (bf16) and g (f32); write k~, v~ (bf16)
     meta_bytes = B * Hkv * T * D * 2 + B * Hkv * (T // P) * 2 * D * 2
     extra["rat_scan_prefill"] = {"ms": round(scan_ms, 4), "GB/s": round(scan_bytes / scan_ms / 1e6, 1),
                                  "frac_hbm_peak": round(scan_bytes / (scan_ms * 1e-3) / HBM_PEAK, 4),
-                                 "algorithmic_bytes": scan_bytes, "ms_first_call": round(scan_first_ms, 4)}
+                                 "algorithmic_bytes": scan_bytes, "ms_first_call": round(scan_first_ms, 4),
+                                 "ms_runs": [round(x, 4) for x in scan_runs]}
     extra["quest_page_meta_bulk"] = {"ms": round(meta_ms, 4), "GB/s": round(meta_bytes / meta_ms / 1e6, 1),
                                      "frac_hbm_peak": round(meta_bytes / (meta_ms * 1e-3) / HBM_PEAK, 4),
                                      "ms_first_call": round(meta_first_ms, 4)}
@@ -148,16 +155,20 @@ def main():
                                                         % (scan_meta_ms, scan_ms, meta_ms)}
     # the machine's ceiling for the scan's traffic mix (two bytes read per byte written): a plain streaming
     # kernel over the prefill inputs (reads k and v, 2 GiB each; writes the 2 GiB K cache, rewritten below)
-    pr_ms = []
-    for r in range(4):
-        pa, pb = ev(), ev()
-        pa.record()
-        rs.ratsparse_probe_rw(tk, tv, kc, tk.numel() * tk.element_size())
-        pb.record()
-        torch.cuda.synchronize()
-        pr_ms.append(pa.elapsed_time(pb))
-    rw_gbs = 3 * tk.numel() * tk.element_size() / (min(pr_ms[1:]) * 1e-3) / 1e9
+    rw_by_kind = {}
+    for kind, streaming in (("cached", 0), ("streaming", 1)):
+        pr_ms = []
+        for r in range(4):
+            pa, pb = ev(), ev()
+            pa.record()
+            rs.ratsparse_probe_rw(tk, tv, kc, tk.numel() * tk.element_size(), streaming)
+            pb.record()
+            torch.cuda.synchronize()
+            pr_ms.append(pa.elapsed_time(pb))
+        rw_by_kind[kind] = 3 * tk.numel() * tk.element_size() / (min(pr_ms[1:]) * 1e-3) / 1e9
+    rw_gbs = max(rw_by_kind.values())  # the better of plain and non-temporal accesses is the ceiling
     extra["rat_scan_prefill"]["measured_2r1w_probe_GB/s"] = round(rw_gbs, 1)
+    extra["rat_scan_prefill"]["measured_2r1w_probe_by_access_GB/s"] = {k: round(v2, 1) for k, v2 in rw_by_kind.items()}
     extra["rat_scan_prefill"]["frac_of_measured_2r1w_probe"] = round(scan_bytes / scan_ms / 1e6 / rw_gbs, 4)
     sk.zero_()
     sv.zero_()

@@ -103,9 +103,11 @@ int32_t ratsparse_probe_read(const void *src, size_t bytes, void *sink, void *st
 
 /* Measurement aid (no part of the method): a plain streaming kernel with the traffic mix of
  * rat_scan (two bytes read for every byte written): dst[i] = a[i] ^ b[i] over `bytes` bytes of
- * each of the three 16-byte aligned device buffers.  3 * bytes over its duration is the rate a
- * kernel with that mix can be held against on this machine. */
-int32_t ratsparse_probe_rw(const void *a, const void *b, void *dst, size_t bytes, void *stream);
+ * each of the three 16-byte aligned device buffers; streaming != 0: with non-temporal loads and
+ * stores (what rat_scan uses for whole rows).  3 * bytes over its duration is the rate a kernel
+ * with that mix can be held against on this machine. */
+int32_t ratsparse_probe_rw(const void *a, const void *b, void *dst, size_t bytes, int32_t streaming,
+                           void *stream);
 
 /* Test hook: the bound, in polls, of every in-kernel wait of calls made from now on (the
  * default is 1 << 22).  With 0 a kernel that would have to wait gives up at once, exits

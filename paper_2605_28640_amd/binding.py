@@ -38,7 +38,7 @@ SIGNATURES = {
     "ratsparse_workspace_init": (_i32, [_vp, _sz, _vp]),
     "ratsparse_async_status": (_i32, [_vp, _vp]),
     "ratsparse_probe_read": (_i32, [_vp, _sz, _vp, _vp]),
-    "ratsparse_probe_rw": (_i32, [_vp, _vp, _vp, _sz, _vp]),
+    "ratsparse_probe_rw": (_i32, [_vp, _vp, _vp, _sz, _i32, _vp]),
     "ratsparse_debug_set_spin_limit": (None, [_i32]),
     "ratsparse_debug_reload_knobs": (None, []),
     "rat_scan_workspace_bytes": (_sz, [_shp, _i64]),
@@ -143,8 +143,8 @@ def ratsparse_probe_read(src, nbytes, sink):
     _check(load().ratsparse_probe_read(_ptr(src), nbytes, _ptr(sink), _stream()))
 
 
-def ratsparse_probe_rw(a, b, dst, nbytes):
-    _check(load().ratsparse_probe_rw(_ptr(a), _ptr(b), _ptr(dst), nbytes, _stream()))
+def ratsparse_probe_rw(a, b, dst, nbytes, streaming=0):
+    _check(load().ratsparse_probe_rw(_ptr(a), _ptr(b), _ptr(dst), nbytes, streaming, _stream()))
 
 
 def rat_scan_workspace_bytes(s, T_new):

@@ -285,24 +285,40 @@ __global__ __launch_bounds__(512) void probe_read_kernel(const uint4 *__restrict
     if (acc == 0x9e3779b9u) sink[0] = acc;  // keeps the loads alive; practically never taken
 }
 // two read streams, one write stream (the byte mix of the scan: 8 bytes read, 4 written per
-// channel-token): dst = a ^ b in 16-byte pieces, a contiguous slice per workgroup
+// channel-token): dst = a ^ b in 16-byte pieces, a contiguous slice per workgroup; NT: with
+// streaming (non-temporal) loads and stores, as the scan itself uses
+template <bool NT>
 __global__ __launch_bounds__(512) void probe_rw_kernel(const uint4 *__restrict__ a, const uint4 *__restrict__ b,
                                                        uint4 *__restrict__ dst, size_t n16, size_t per_wg)
 {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const size_t lo = (size_t)blockIdx.x * per_wg;
     const size_t hi = (lo + per_wg < n16) ? lo + per_wg : n16;
     for (size_t i = lo + threadIdx.x; i < hi; i += (size_t)512 * 4) {
-        uint4 x[4], y[4];
+        u32x4 x[4], y[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const size_t j = i + (size_t)u * 512;
-            x[u] = (j < hi) ? a[j] : make_uint4(0u, 0u, 0u, 0u);
-            y[u] = (j < hi) ? b[j] : make_uint4(0u, 0u, 0u, 0u);
+            x[u] = u32x4{0u, 0u, 0u, 0u};
+            y[u] = x[u];
+            if (j < hi) {
+                if constexpr (NT) {
+                    x[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a) + j);
+                    y[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(b) + j);
+                } else {
+                    x[u] = reinterpret_cast<const u32x4 *>(a)[j];
+                    y[u] = reinterpret_cast<const u32x4 *>(b)[j];
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const size_t j = i + (size_t)u * 512;
-            if (j < hi) dst[j] = make_uint4(x[u].x ^ y[u].x, x[u].y ^ y[u].y, x[u].z ^ y[u].z, x[u].w ^ y[u].w);
+            if (j < hi) {
+                const u32x4 r = x[u] ^ y[u];
+                if constexpr (NT) __builtin_nontemporal_store(r, reinterpret_cast<u32x4 *>(dst) + j);
+                else reinterpret_cast<u32x4 *>(dst)[j] = r;
+            }
         }
     }
 }
@@ -340,14 +356,17 @@ int32_t ratsparse_probe_read(const void *src, size_t bytes, void *sink, void *st
 }
 
 // measurement aid: a plain streaming kernel with the scan's traffic mix (reads 2 x bytes, writes bytes)
-int32_t ratsparse_probe_rw(const void *a, const void *b, void *dst, size_t bytes, void *stream)
+int32_t ratsparse_probe_rw(const void *a, const void *b, void *dst, size_t bytes, int32_t streaming, void *stream)
 {
     if (!a || !b || !dst || !aligned16(a) || !aligned16(b) || !aligned16(dst) || bytes < 16) return RS_INVALID_ARG;
     const size_t n16 = bytes / 16;
     size_t blocks = (size_t)num_cus() * 8;
     if (blocks * 512 > n16) blocks = (n16 + 511) / 512;
     const size_t per_wg = (n16 + blocks - 1) / blocks;
-    probe_rw_kernel<<<(unsigned)blocks, 512, 0, (hipStream_t)stream>>>((const uint4 *)a, (const uint4 *)b, (uint4 *)dst, n16, per_wg);
+    if (streaming)
+        probe_rw_kernel<true><<<(unsigned)blocks, 512, 0, (hipStream_t)stream>>>((const uint4 *)a, (const uint4 *)b, (uint4 *)dst, n16, per_wg);
+    else
+        probe_rw_kernel<false><<<(unsigned)blocks, 512, 0, (hipStream_t)stream>>>((const uint4 *)a, (const uint4 *)b, (uint4 *)dst, n16, per_wg);
     return launch_status();
 }
 

@@ -98,6 +98,17 @@ struct Row8<bf16> {
         r.w = pack_bf16x2(x[6], x[7]);
         *reinterpret_cast<uint4 *>(p) = r;
     }
+    // streaming store: the row is not read again soon
+    __device__ __forceinline__ static void store_nt(bf16 *p, const float (&x)[8])
+    {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        u32x4 r;
+        r.x = pack_bf16x2(x[0], x[1]);
+        r.y = pack_bf16x2(x[2], x[3]);
+        r.z = pack_bf16x2(x[4], x[5]);
+        r.w = pack_bf16x2(x[6], x[7]);
+        __builtin_nontemporal_store(r, reinterpret_cast<u32x4 *>(p));
+    }
 };
 
 template <>
@@ -139,6 +150,15 @@ struct Row8<float> {
     {
         *reinterpret_cast<float4 *>(p) = make_float4(x[0], x[1], x[2], x[3]);
         *reinterpret_cast<float4 *>(p + 4) = make_float4(x[4], x[5], x[6], x[7]);
+    }
+    __device__ __forceinline__ static void store_nt(float *p, const float (&x)[8])
+    {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        f32x4 a, b;
+        a.x = x[0]; a.y = x[1]; a.z = x[2]; a.w = x[3];
+        b.x = x[4]; b.y = x[5]; b.z = x[6]; b.w = x[7];
+        __builtin_nontemporal_store(a, reinterpret_cast<f32x4 *>(p));
+        __builtin_nontemporal_store(b, reinterpret_cast<f32x4 *>(p + 4));
     }
 };
 

@@ -101,10 +101,22 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
             float4 ga = make_float4(1.f, 1.f, 1.f, 1.f), gb = ga;  // past the end: the identity element (g = 1 keeps the state)
             if (t < T_new) {
                 const long off = (in_row0 + t) * D + ch0 + c0;
-                kq = R::load_raw(k + off);
-                vq = R::load_raw(v + off);
-                ga = *reinterpret_cast<const float4 *>(g + off);
-                gb = *reinterpret_cast<const float4 *>(g + off + 4);
+                if constexpr (DS == D) {
+                    // whole rows, read once: streaming loads (a slab shares its cache lines with the
+                    // other slabs of the row, which come by other workgroups: those stay cached loads)
+                    kq = R::load_raw_nt(k + off);
+                    vq = R::load_raw_nt(v + off);
+                    typedef float f32x4 __attribute__((ext_vector_type(4)));
+                    const f32x4 xa = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(g + off));
+                    const f32x4 xb = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(g + off + 4));
+                    ga = make_float4(xa.x, xa.y, xa.z, xa.w);
+                    gb = make_float4(xb.x, xb.y, xb.z, xb.w);
+                } else {
+                    kq = R::load_raw(k + off);
+                    vq = R::load_raw(v + off);
+                    ga = *reinterpret_cast<const float4 *>(g + off);
+                    gb = *reinterpret_cast<const float4 *>(g + off + 4);
+                }
             }
             __builtin_memcpy(r.kw[i], &kq, sizeof(kq));
             __builtin_memcpy(r.vw[i], &vq, sizeof(vq));
@@ -295,8 +307,8 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
                 sv[c] = fmaf(gg[c], sv[c], om * vx[c]);
             }
             const long off = (out_row0 + t) * D + ch0 + c0;
-            R::store(k_cache + off, sk);
-            R::store(v_cache + off, sv);
+            R::store_nt(k_cache + off, sk);
+            R::store_nt(v_cache + off, sv);
             if constexpr (META) {
                 float xs[8];  // the values just stored
                 if constexpr (sizeof(ST) == 2) {
