@@ -98,8 +98,9 @@ int32_t ratsparse_async_status(void *ws, void *stream);
 
 /* Measurement aid (no part of the method): enqueue a plain streaming read of `bytes` bytes at
  * src (16-byte aligned device memory); sink is 4 bytes of device memory that is practically
- * never written.  The achieved rate is the read ceiling to hold a read-bound kernel against. */
-int32_t ratsparse_probe_read(const void *src, size_t bytes, void *sink, void *stream);
+ * never written; streaming != 0: with non-temporal loads (what the decode kernels use for K and
+ * V rows).  The achieved rate is the read ceiling to hold a read-bound kernel against. */
+int32_t ratsparse_probe_read(const void *src, size_t bytes, void *sink, int32_t streaming, void *stream);
 
 /* Measurement aid (no part of the method): a plain streaming kernel with the traffic mix of
  * rat_scan (two bytes read for every byte written): dst[i] = a[i] ^ b[i] over `bytes` bytes of

@@ -37,7 +37,7 @@ SIGNATURES = {
     "ratsparse_version": (ctypes.c_char_p, []),
     "ratsparse_workspace_init": (_i32, [_vp, _sz, _vp]),
     "ratsparse_async_status": (_i32, [_vp, _vp]),
-    "ratsparse_probe_read": (_i32, [_vp, _sz, _vp, _vp]),
+    "ratsparse_probe_read": (_i32, [_vp, _sz, _vp, _i32, _vp]),
     "ratsparse_probe_rw": (_i32, [_vp, _vp, _vp, _sz, _i32, _vp]),
     "ratsparse_debug_set_spin_limit": (None, [_i32]),
     "ratsparse_debug_reload_knobs": (None, []),
@@ -139,8 +139,8 @@ class Workspace:
         _check(load().ratsparse_async_status(self.ptr, _stream()))
 
 
-def ratsparse_probe_read(src, nbytes, sink):
-    _check(load().ratsparse_probe_read(_ptr(src), nbytes, _ptr(sink), _stream()))
+def ratsparse_probe_read(src, nbytes, sink, streaming=0):
+    _check(load().ratsparse_probe_read(_ptr(src), nbytes, _ptr(sink), streaming, _stream()))
 
 
 def ratsparse_probe_rw(a, b, dst, nbytes, streaming=0):

@@ -265,9 +265,11 @@ static long fused_setup(FusedParams &prm, const rs_shape *s, const DecodeLayout 
 using namespace rs;
 
 namespace rs {
+template <bool NT>
 __global__ __launch_bounds__(512) void probe_read_kernel(const uint4 *__restrict__ src, size_t n16, size_t per_wg,
                                                          uint32_t *sink)
 {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     // each workgroup streams one contiguous slice, eight 16-byte loads in flight per thread
     const size_t b = (size_t)blockIdx.x * per_wg;
     const size_t e = (b + per_wg < n16) ? b + per_wg : n16;
@@ -277,7 +279,15 @@ __global__ __launch_bounds__(512) void probe_read_kernel(const uint4 *__restrict
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const size_t j = i + (size_t)u * 512;
-            v[u] = (j < e) ? src[j] : make_uint4(0u, 0u, 0u, 0u);
+            v[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (j < e) {
+                if constexpr (NT) {  // streaming loads, as the decode kernels use for K and V pages
+                    const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src) + j);
+                    v[u] = make_uint4(w.x, w.y, w.z, w.w);
+                } else {
+                    v[u] = src[j];
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
@@ -344,14 +354,17 @@ const char *ratsparse_version(void) { return "ratsparse 0.1 (gfx950)"; }
 
 // measurement aid: a plain streaming read of `bytes` bytes (16-byte loads, a contiguous slice
 // per workgroup), the ceiling a read-bound kernel can be held against on this machine
-int32_t ratsparse_probe_read(const void *src, size_t bytes, void *sink, void *stream)
+int32_t ratsparse_probe_read(const void *src, size_t bytes, void *sink, int32_t streaming, void *stream)
 {
     if (!src || !sink || !aligned16(src) || bytes < 16) return RS_INVALID_ARG;
     const size_t n16 = bytes / 16;
     size_t blocks = (size_t)num_cus() * 4;
     if (blocks * 512 > n16) blocks = (n16 + 511) / 512;
     const size_t per_wg = (n16 + blocks - 1) / blocks;
-    probe_read_kernel<<<(unsigned)blocks, 512, 0, (hipStream_t)stream>>>((const uint4 *)src, n16, per_wg, (uint32_t *)sink);
+    if (streaming)
+        probe_read_kernel<true><<<(unsigned)blocks, 512, 0, (hipStream_t)stream>>>((const uint4 *)src, n16, per_wg, (uint32_t *)sink);
+    else
+        probe_read_kernel<false><<<(unsigned)blocks, 512, 0, (hipStream_t)stream>>>((const uint4 *)src, n16, per_wg, (uint32_t *)sink);
     return launch_status();
 }
 

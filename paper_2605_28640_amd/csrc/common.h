@@ -184,6 +184,7 @@ __device__ __forceinline__ void load16_to_lds(LdsSource src, uint32_t byte_offse
     __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (__attribute__((address_space(3))) void *)l, 16, (int)byte_offset, 0, 0, 0);
 }
 
+
 // Tiles of K/V rows sit in LDS unpadded (a wave-wide load fills whole rows back to back), so the bank
 // spread comes from permuting the 16-byte chunks inside each row: chunk c of row r is kept at
 // position c ^ chunk_swizzle(r).  The permutation is chosen so that (a) 16 lanes reading the

@@ -313,8 +313,13 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
             for (int i = 0; i < RPL; ++i) {
                 const long row = row0[u] + i * RPW + rg;
                 if (row < T_valid) {
-                    kr[u][i] = R::load_raw(kb + row * D + c0);
-                    vr[u][i] = R::load_raw(vb + row * D + c0);
+                    if (Hq == Hkv) {  // no other query head reads these rows: streaming loads
+                        kr[u][i] = R::load_raw_nt(kb + row * D + c0);
+                        vr[u][i] = R::load_raw_nt(vb + row * D + c0);
+                    } else {
+                        kr[u][i] = R::load_raw(kb + row * D + c0);
+                        vr[u][i] = R::load_raw(vb + row * D + c0);
+                    }
                 } else {  // masked rows contribute nothing (and stale memory is never read)
                     kr[u][i] = R::zero_raw();
                     vr[u][i] = R::zero_raw();
