@@ -242,8 +242,9 @@ int32_t sparse_attn_decode_group(const rs_shape *s, const void *q, const void *k
  *   rat_decode_state_get   waits for `stream`, then reads the token count into *T (host)
  *   k, v [B, Hkv, 1, D] dtype; g [B, Hkv, 1, D] float32; q [B, Hq, D]; the rest as in
  *   rat_scan and sparse_attn_decode.  T_max: the largest T + 1 the workspace is sized for
- *   (<= Tcap).  Per query head; select-then-attend as one launch (the persistent form, or one
- *   workgroup per (batch, head) for short contexts: chosen by shape at T_max).
+ *   (<= Tcap).  Per query head; select-then-attend in the form sparse_attn_decode would take for
+ *   the shape at T_max (one workgroup per (batch, head), the two plain launches, or the one
+ *   persistent launch), each reading the length and the tag from the workspace.
  * A step that would pass T_max, or that finds fewer than K pages, changes nothing (neither
  * carries, caches, page bounds nor count: the append kernel applies the same test as the
  * attention kernel) except that it sets the asynchronous error word

@@ -30,11 +30,12 @@ void unit_decode_dispatch(int dtype, int D, const void *q, const void *meta, con
 int score_select_dispatch(int dtype, int D, int GQ, const void *q, const void *meta, uint64_t *scores,
                           float *scores_out, int32_t *idx_out, int B, int Hq, int Hkv, long Np_cap, int Np, int K,
                           int n_first, int n_local, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag,
-                          int spin_limit, hipStream_t stream);
+                          int spin_limit, const uint32_t *state, long T_max, int P, hipStream_t stream);
 void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache, const void *v_cache,
                             const int32_t *idx, void *out, float *lse_out, uint64_t *partial, int B, int Hq,
                             int Hkv, long Tcap, int P, long T_valid, int K, float scale, int splits,
-                            uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit, int idx_per_kv, hipStream_t stream);
+                            uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit, int idx_per_kv,
+                            uint32_t *state, long T_max, hipStream_t stream);
 // moba.hip / prefill.hip / snapkv.hip
 size_t moba_select_ws_bytes(const rs_shape *s, long T, int block);
 int moba_select_dispatch(const rs_shape *s, const void *q, const void *k_cache, long T, int block, int K,
@@ -507,7 +508,7 @@ static int32_t select_decode_impl(bool group, const rs_shape *s, const void *q, 
     st = score_select_dispatch(s->dtype, s->D, GQ, q, meta, (uint64_t *)(w + L.off_scores), scores_out, idx_out,
                                s->B, s->Hq, s->Hkv, s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score,
                                (uint32_t *)w + kCtrlUnit0, (uint32_t *)w + kCtrlAsyncErr, next_tag(),
-                               g_spin_limit.load(), (hipStream_t)stream);
+                               g_spin_limit.load(), nullptr, 0, s->P, (hipStream_t)stream);
     if (st != RS_OK) return st;
     return launch_status();
 }
@@ -602,7 +603,7 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
         int32_t *sel = idx_out ? idx_out : (int32_t *)(w + L.off_idx);
         st = score_select_dispatch(s->dtype, s->D, GQ, q, meta, (uint64_t *)(w + L.off_scores), nullptr, sel, s->B,
                                    s->Hq, s->Hkv, s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score,
-                                   ctr_score, err, tag, g_spin_limit.load(), (hipStream_t)stream);
+                                   ctr_score, err, tag, g_spin_limit.load(), nullptr, 0, s->P, (hipStream_t)stream);
         if (st != RS_OK) return st;
         if (launch_status() != RS_OK) return RS_LAUNCH_FAILED;
         use_idx = sel;
@@ -621,7 +622,7 @@ static int32_t attn_decode_impl(bool group, const rs_shape *s, const void *q, co
     if (splits > L.splits_att_max) splits = L.splits_att_max;
     decode_attend_dispatch(s->dtype, s->D, q, k_cache, v_cache, use_idx, out, lse_out,
                            (uint64_t *)(w + L.off_partial), s->B, s->Hq, s->Hkv, s->Tcap, s->P, T_valid, K, scale,
-                           splits, ctr_att, err, tag, g_spin_limit.load(), group ? 1 : 0, (hipStream_t)stream);
+                           splits, ctr_att, err, tag, g_spin_limit.load(), group ? 1 : 0, nullptr, 0, (hipStream_t)stream);
     return launch_status();
 }
 
@@ -749,13 +750,40 @@ int32_t rat_decode_step(const rs_shape *s, const void *k, const void *v, const f
     step_at_state_dispatch(s->dtype, s->D, k, v, g, state_k, state_v, k_cache, v_cache, meta, s->P, s->B * s->Hkv,
                            s->Tcap, (const uint32_t *)w, T_max, K, (hipStream_t)stream);
     if (launch_status() != RS_OK) return RS_LAUNCH_FAILED;
-    // short contexts: one workgroup per (batch, query head), as in sparse_attn_decode (sized at T_max)
+    // the form of select-then-attend, by the shape at T_max and the rule of sparse_attn_decode: one workgroup per
+    // (batch, query head) for short contexts, the persistent launch for long bandwidth-bound steps, the two plain
+    // launches in between; all three read the length and the tag from the workspace's state words
     const long units = (long)s->B * s->Hq;
+    const double step_bytes = ((double)s->B * s->Hkv * L.Np * 2 + (double)units * K * s->P * 2) * s->D * esize(s->dtype);
+    const int two_launch = knob_or(knobs().fused_two_launch, (step_bytes >= 450e6 && L.Np >= 512) ? 0 : 1);
     const double unit_bytes = ((double)L.Np * 2 + (double)K * s->P * 2) * s->D * esize(s->dtype);
-    const bool unit_rule = unit_bytes <= 1.5e6 && (units >= 128 || unit_bytes <= 512e3);
+    const bool unit_rule = two_launch && unit_bytes <= 1.5e6 && (units >= 128 || unit_bytes <= 512e3);
     if (knob_or(knobs().fused_one_wg, unit_rule ? 1 : 0) && L.Np <= 4096 && K <= 1024) {
         unit_decode_dispatch(s->dtype, s->D, q, meta, k_cache, v_cache, out, lse_out, idx_out, s->B, s->Hq, s->Hkv,
                              s->Tcap, s->P, T_max, L.Np, K, n_first, n_local, scale, (uint32_t *)w, (hipStream_t)stream);
+        return launch_status();
+    }
+    if (two_launch) {
+        uint32_t *ctr_score = (uint32_t *)w + kCtrlUnit0;
+        uint32_t *ctr_att = ctr_score + kMaxUnits;
+        uint32_t *err = (uint32_t *)w + kCtrlAsyncErr;
+        int32_t *sel = idx_out ? idx_out : (int32_t *)(w + L.off_idx);
+        st = score_select_dispatch(s->dtype, s->D, 1, q, meta, (uint64_t *)(w + L.off_scores), nullptr, sel, s->B, s->Hq,
+                                   s->Hkv, s->Tcap / s->P, L.Np, K, n_first, n_local, L.splits_score, ctr_score, err, 0u,
+                                   g_spin_limit.load(), (const uint32_t *)w, T_max, s->P, (hipStream_t)stream);
+        if (st != RS_OK) return st;
+        if (launch_status() != RS_OK) return RS_LAUNCH_FAILED;
+        const long tiles = (long)K * (s->P / 16);
+        int target = knob_or(knobs().attend_wgs, 0);
+        if (target <= 0) {
+            target = 256;
+            if (tiles > (long)pick_splits(units, tiles, 8, 256) * 8 * 2 * 16) target = 512;
+        }
+        int splits = pick_splits(units, tiles, 8, target);
+        if (splits > L.splits_att_max) splits = L.splits_att_max;
+        decode_attend_dispatch(s->dtype, s->D, q, k_cache, v_cache, sel, out, lse_out, (uint64_t *)(w + L.off_partial),
+                               s->B, s->Hq, s->Hkv, s->Tcap, s->P, T_max, K, scale, splits, ctr_att, err, 0u,
+                               g_spin_limit.load(), 0, (uint32_t *)w, T_max, (hipStream_t)stream);
         return launch_status();
     }
     FusedParams prm;

@@ -133,8 +133,22 @@ template <typename ST, int D, int GQ>
 __global__ __launch_bounds__(kSelThreads) void quest_score_select_kernel(
     const ST *__restrict__ q, const ST *__restrict__ meta, uint64_t *scores, float *scores_out, int32_t *idx_out,
     int Hq, int Hkv, long Np_cap, int Np, int K, int n_first, int n_local, int splits, uint32_t *unit_ctr,
-    uint32_t *err, uint32_t tag, int spin_limit)
+    uint32_t *err, uint32_t tag, int spin_limit, const uint32_t *state, long T_max, int P)
 {
+    // state (the replayable decode step): the sequence length and the tag are not arguments but words of
+    // the workspace (tokens in the cache + 1: the step's append has run); score rows keep the stride of T_max
+    long np_stride = Np;
+    if (state) {
+        const long T_valid = *reinterpret_cast<const long *>(state + kCtrlStateT) + 1;
+        tag = state[kCtrlStateTag];
+        if (tag == 0u) tag = 0x5bd1e995u;
+        Np = (int)((T_valid + P - 1) / P);
+        np_stride = (T_max + P - 1) / P;
+        if (T_valid > T_max || K > Np) {  // outside what the buffers were sized for: report, do nothing
+            if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) atomicExch(err, 1u);
+            return;
+        }
+    }
     constexpr int LPR = D / 8;
     constexpr int RPW = 64 / LPR;
     constexpr int UNR = 4;  // pages per lane in flight
@@ -152,7 +166,7 @@ __global__ __launch_bounds__(kSelThreads) void quest_score_select_kernel(
     const int b = u0 / Hq, h = u0 % Hq;
     const int kvh = h / (Hq / Hkv);
     const ST *mbase = meta + ((long)(b * Hkv + kvh) * Np_cap) * 2 * D;
-    uint64_t *srow = scores + (long)unit * Np;
+    uint64_t *srow = scores + (long)unit * np_stride;
 
     float qv[GQ][8];
 #pragma unroll
@@ -212,7 +226,7 @@ __global__ __launch_bounds__(kSelThreads) void quest_score_select_kernel(
 int score_select_dispatch(int dtype, int D, int GQ, const void *q, const void *meta, uint64_t *scores,
                           float *scores_out, int32_t *idx_out, int B, int Hq, int Hkv, long Np_cap, int Np, int K,
                           int n_first, int n_local, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag,
-                          int spin_limit, hipStream_t stream)
+                          int spin_limit, const uint32_t *state, long T_max, int P, hipStream_t stream)
 {
     const dim3 grid((unsigned)splits, (unsigned)(B * Hq / GQ));
     if (Np > 15360) return RS_UNSUPPORTED;  // keys must fit 60 KiB of LDS
@@ -221,7 +235,7 @@ int score_select_dispatch(int dtype, int D, int GQ, const void *q, const void *m
 #define RS_LAUNCH(ST, DD, GG)                                                                                      \
     quest_score_select_kernel<ST, DD, GG><<<grid, kSelThreads, lds, stream>>>(                                    \
         (const ST *)q, (const ST *)meta, scores, scores_out, idx_out, Hq, Hkv, Np_cap, Np, K, n_first, n_local, \
-        splits, unit_ctr, err, tag, spin_limit)
+        splits, unit_ctr, err, tag, spin_limit, state, T_max, P)
 #define RS_LAUNCH_G(ST, DD)                     \
     do {                                        \
         if (GQ == 8) RS_LAUNCH(ST, DD, 8);      \
@@ -250,8 +264,27 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
     const ST *__restrict__ q, const ST *__restrict__ k_cache, const ST *__restrict__ v_cache, const int32_t *idx,
     ST *__restrict__ out, float *__restrict__ lse_out, uint64_t *partial, int Hq, int Hkv, long Tcap, int P,
     long T_valid, int K, float scale, int splits, uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit,
-    int idx_per_kv)
+    int idx_per_kv, uint32_t *state, long T_max)
 {
+    // state (the replayable decode step, listed pages): length and tag come from the workspace's words; the
+    // last workgroup out of the grid advances them (every workgroup has read them by then)
+    if (state) {
+        T_valid = *reinterpret_cast<const long *>(state + kCtrlStateT) + 1;
+        tag = state[kCtrlStateTag];
+        if (tag == 0u) tag = 0x5bd1e995u;
+        if (T_valid > T_max || (long)K > (T_valid + P - 1) / P) return;  // refused: the selection kernel has reported it
+    }
+    auto workgroup_done = [&]() {
+        if (state && threadIdx.x == 0) {
+            uint32_t *done = state + kCtrlDone;
+            if (atomicAdd(done, 1u) == gridDim.x * gridDim.y - 1u) {
+                atomicExch(done, 0u);
+                *reinterpret_cast<long *>(state + kCtrlStateT) = T_valid;
+                const uint32_t nt = tag + 0x85EBCA6Bu;
+                state[kCtrlStateTag] = nt ? nt : 0x5bd1e995u;
+            }
+        }
+    };
     constexpr int LPR = D / 8;
     constexpr int RPW = 64 / LPR;  // rows per load instruction
     constexpr int TR = 16;         // rows per tile
@@ -412,7 +445,10 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
             }
         }
     }
-    if (splits == 1) return;
+    if (splits == 1) {
+        workgroup_done();
+        return;
+    }
 
     if (tid == 0) {
         const uint32_t prev = atomicAdd(&unit_ctr[unit], 1u);
@@ -420,7 +456,10 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
         if (s_last) atomicExch(&unit_ctr[unit], 0u);
     }
     __syncthreads();
-    if (!s_last) return;
+    if (!s_last) {
+        workgroup_done();
+        return;
+    }
     if (tid < D) {
         float M = -INFINITY, L = 0.f, O = 0.f;
         merge_partials(partial + (long)unit * splits * (D + 2), splits, D + 2, tid, tag, spin_limit, err, M, L, O);
@@ -428,6 +467,7 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
         from_f32(out[(long)unit * D + tid], O * inv);
         if (tid == 0 && lse_out) lse_out[unit] = (L > 0.f) ? M + __logf(L) : -INFINITY;
     }
+    workgroup_done();
 }
 
 // ------------------------------------------------------------------------------------
@@ -670,14 +710,14 @@ void decode_attend_dispatch(int dtype, int D, const void *q, const void *k_cache
                             const int32_t *idx, void *out, float *lse_out, uint64_t *partial, int B, int Hq,
                             int Hkv, long Tcap, int P, long T_valid, int K, float scale, int splits,
                             uint32_t *unit_ctr, uint32_t *err, uint32_t tag, int spin_limit, int idx_per_kv,
-                            hipStream_t stream)
+                            uint32_t *state, long T_max, hipStream_t stream)
 {
     const dim3 grid((unsigned)splits, (unsigned)(B * Hq));
     constexpr int kAttThreads = 512;  // about one such workgroup per CU (see the split rule of the caller)
 #define RS_LAUNCH(ST, DD)                                                                                   \
     decode_attend_kernel<ST, DD, kAttThreads><<<grid, kAttThreads, 0, stream>>>(                            \
         (const ST *)q, (const ST *)k_cache, (const ST *)v_cache, idx, (ST *)out, lse_out, partial, Hq, Hkv, \
-        Tcap, P, T_valid, K, scale, splits, unit_ctr, err, tag, spin_limit, idx_per_kv)
+        Tcap, P, T_valid, K, scale, splits, unit_ctr, err, tag, spin_limit, idx_per_kv, state, T_max)
     if (dtype == RS_BF16) {
         if (D == 128) RS_LAUNCH(bf16, 128);
         else RS_LAUNCH(bf16, 64);

@@ -60,13 +60,13 @@ def _step_inputs(w, step):
 
 
 def _force_form(knobs, form):
-    """Both sides run the same form of select-then-attend: the persistent launch, or one workgroup
-    per (batch, head) (the step takes one of these two by shape; the knobs force either)."""
+    """Both sides run the same form of select-then-attend: the persistent launch, one workgroup per
+    (batch, head), or the two plain launches (the step takes one of the three by shape; the knobs force any)."""
     knobs.setenv("RATSPARSE_FUSED_TWO_LAUNCH", "0" if form == "persistent" else "1")
-    knobs.setenv("RATSPARSE_FUSED_ONE_WG", "0" if form == "persistent" else "1")
+    knobs.setenv("RATSPARSE_FUSED_ONE_WG", "1" if form == "one_wg" else "0")
 
 
-FORMS = ["persistent", "one_wg"]
+FORMS = ["persistent", "one_wg", "two_launch"]
 
 
 @pytest.mark.parametrize("form", FORMS)
