@@ -132,9 +132,12 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                         mx[u] = R::zero_raw();
                     }
                 }
+                // the wave's UNR * RPW pages are consecutive: their scores are brought to the first lanes and
+                // leave as ONE store instruction of adjacent 8-byte words (whole lines on the write-through
+                // path instead of four-word pieces from four instructions)
+                float mine = 0.f;
 #pragma unroll
                 for (int u = 0; u < UNR; ++u) {
-                    const int p = base + u * RPW;
                     float lo[8], hi[8];
                     R::unpack(mn[u], lo);
                     R::unpack(mx[u], hi);
@@ -142,7 +145,12 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
 #pragma unroll
                     for (int c = 0; c < 8; ++c) s += fmaxf(qv[c] * lo[c], qv[c] * hi[c]);
                     s = group_sum<LPR>(s);
-                    if (p < pe && cl == 0) publish_f32(&srow[p], s, tag_);
+                    const float t = shfl_f(s, (lane % RPW) * LPR);  // page u * RPW + lane % RPW of the wave's run
+                    if (lane / RPW == u) mine = t;
+                }
+                {
+                    const int p = (base - rg) + lane;
+                    if (lane < UNR * RPW && p < pe) publish_f32(&srow[p], mine, tag_);
                 }
             }
             mark(item, 1);
