@@ -162,6 +162,53 @@ struct Row8<float> {
     }
 };
 
+// Channelwise upper bound of q . k over the keys of a page (App. A.1, Quest; the score of Eq. 3):
+// sum_c max(q_c lo_c, q_c hi_c) with lo, hi the page's channelwise min / max rows.  With
+// lo_c <= hi_c the larger product is q_c hi_c where q_c > 0 and q_c lo_c elsewhere, so the bound
+// row is picked per channel first -- on the packed bfloat16 words one bit-select serves a channel
+// pair -- and one fused multiply-add per channel remains (the products are the same floats the
+// two-product form would have taken the maximum of).  Channels are added in index order.
+template <typename ST>
+struct BoundDot;
+
+template <>
+struct BoundDot<bf16> {
+    uint32_t m[4];  // per packed word: ones over the half whose channel has q > 0
+    __device__ __forceinline__ void set(const float (&q)[8])
+    {
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            m[w] = (q[2 * w] > 0.f ? 0x0000ffffu : 0u) | (q[2 * w + 1] > 0.f ? 0xffff0000u : 0u);
+    }
+    __device__ __forceinline__ float add(float s, const float (&q)[8], const Row8<bf16>::raw_t &lo,
+                                         const Row8<bf16>::raw_t &hi) const
+    {
+        const uint32_t l[4] = {lo.r.x, lo.r.y, lo.r.z, lo.r.w};
+        const uint32_t h[4] = {hi.r.x, hi.r.y, hi.r.z, hi.r.w};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const uint32_t x = (h[w] & m[w]) | (l[w] & ~m[w]);
+            s = fmaf(q[2 * w], __uint_as_float(x << 16), s);
+            s = fmaf(q[2 * w + 1], __uint_as_float(x & 0xffff0000u), s);
+        }
+        return s;
+    }
+};
+
+template <>
+struct BoundDot<float> {
+    __device__ __forceinline__ void set(const float (&)[8]) {}
+    __device__ __forceinline__ float add(float s, const float (&q)[8], const Row8<float>::raw_t &lo,
+                                         const Row8<float>::raw_t &hi) const
+    {
+        const float l[8] = {lo.a.x, lo.a.y, lo.a.z, lo.a.w, lo.b.x, lo.b.y, lo.b.z, lo.b.w};
+        const float h[8] = {hi.a.x, hi.a.y, hi.a.z, hi.a.w, hi.b.x, hi.b.y, hi.b.z, hi.b.w};
+#pragma unroll
+        for (int c = 0; c < 8; ++c) s = fmaf(q[c], (q[c] > 0.f) ? h[c] : l[c], s);
+        return s;
+    }
+};
+
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16 x) { return bf16_bits_to_f32(x.bits); }
 __device__ __forceinline__ void from_f32(float &d, float x) { d = x; }
@@ -224,12 +271,35 @@ __device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_x
 __device__ __forceinline__ float shfl_up_f(float v, int d) { return __shfl_up(v, d, kWave); }
 __device__ __forceinline__ float shfl_f(float v, int src) { return __shfl(v, src, kWave); }
 
-// sum over aligned groups of `width` lanes (power of two); every lane gets the sum
+// a lane's value as seen through a data-parallel-primitive lane pattern (the move folds into the
+// arithmetic instruction that uses it: no trip through the LDS crossbar, no wait)
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
+// sum over aligned groups of `width` lanes (power of two); every lane gets the sum.
+// 16 lanes are a DPP row: four rotations within the row (by 8, 4, 2, 1) give every lane the same
+// bits as the exchange-with-partner butterfly (a rotation by 8 is the exchange with lane ^ 8, and
+// from then on both partners of an exchange hold equal values).  8 lanes are half a row: mirror
+// within the half (lane i <-> 7 - i), then the two exchanges inside a quad.
 template <int width>
 __device__ __forceinline__ float group_sum(float v)
 {
+    if constexpr (width == 16) {
+        v += dpp_f<0x128>(v);  // row_ror:8
+        v += dpp_f<0x124>(v);  // row_ror:4
+        v += dpp_f<0x122>(v);  // row_ror:2
+        v += dpp_f<0x121>(v);  // row_ror:1
+    } else if constexpr (width == 8) {
+        v += dpp_f<0x141>(v);  // row_half_mirror
+        v += dpp_f<0xB1>(v);   // quad_perm:[1,0,3,2]
+        v += dpp_f<0x4E>(v);   // quad_perm:[2,3,0,1]
+    } else {
 #pragma unroll
-    for (int m = width / 2; m >= 1; m >>= 1) v += shfl_xor_f(v, m);
+        for (int m = width / 2; m >= 1; m >>= 1) v += shfl_xor_f(v, m);
+    }
     return v;
 }
 

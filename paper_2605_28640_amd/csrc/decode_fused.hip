@@ -106,6 +106,8 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
             uint64_t *srow = a.scores + (long)unit * score_stride;
             float qv[8];
             R::load((const ST *)a.q + (long)unit * D + c0, qv);
+            BoundDot<ST> bound;
+            bound.set(qv);
 
             constexpr int UNR = 4;
             constexpr int PPI = UNR * RPW * kFusedWaves;  // pages per workgroup step
@@ -138,13 +140,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                 float mine = 0.f;
 #pragma unroll
                 for (int u = 0; u < UNR; ++u) {
-                    float lo[8], hi[8];
-                    R::unpack(mn[u], lo);
-                    R::unpack(mx[u], hi);
-                    float s = 0.f;
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) s += fmaxf(qv[c] * lo[c], qv[c] * hi[c]);
-                    s = group_sum<LPR>(s);
+                    const float s = group_sum<LPR>(bound.add(0.f, qv, mn[u], mx[u]));
                     const float t = shfl_f(s, (lane % RPW) * LPR);  // page u * RPW + lane % RPW of the wave's run
                     if (lane / RPW == u) mine = t;
                 }

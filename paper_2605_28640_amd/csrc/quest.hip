@@ -171,6 +171,9 @@ __global__ __launch_bounds__(kSelThreads) void quest_score_select_kernel(
     float qv[GQ][8];
 #pragma unroll
     for (int g = 0; g < GQ; ++g) R::load(q + (long)(u0 + g) * D + c0, qv[g]);
+    BoundDot<ST> bound[GQ];
+#pragma unroll
+    for (int g = 0; g < GQ; ++g) bound[g].set(qv[g]);
 
     // this workgroup's pages: a contiguous slice, walked UNR * RPW pages per wave step.
     // The LPR lanes of a row group share their page numbers, so the group-local
@@ -195,14 +198,9 @@ __global__ __launch_bounds__(kSelThreads) void quest_score_select_kernel(
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             const int p = base + u * RPW;
-            float lo[8], hi[8];
-            R::unpack(mn[u], lo);
-            R::unpack(mx[u], hi);
             float s = 0.f;
 #pragma unroll
-            for (int g = 0; g < GQ; ++g)
-#pragma unroll
-                for (int c = 0; c < 8; ++c) s += fmaxf(qv[g][c] * lo[c], qv[g][c] * hi[c]);
+            for (int g = 0; g < GQ; ++g) s = bound[g].add(s, qv[g], mn[u], mx[u]);
             s = group_sum<LPR>(s);
             if (p < pe && (lane % LPR) == 0) publish_f32(&srow[p], s, tag);
         }
@@ -527,6 +525,8 @@ __global__ __launch_bounds__(kUnitThreads) void quest_unit_decode_kernel(
 
     float qv[8];
     R::load(q + (long)unit * D + c0, qv);
+    BoundDot<ST> bound;
+    bound.set(qv);
 
     // page scores (Eq. 3 with the min/max bound) -> order-preserving keys
     constexpr int PPI = UNR * RPW * NW;
@@ -546,13 +546,7 @@ __global__ __launch_bounds__(kUnitThreads) void quest_unit_decode_kernel(
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             const int p = base + u * RPW;
-            float lo[8], hi[8];
-            R::unpack(mn[u], lo);
-            R::unpack(mx[u], hi);
-            float s = 0.f;
-#pragma unroll
-            for (int c = 0; c < 8; ++c) s += fmaxf(qv[c] * lo[c], qv[c] * hi[c]);
-            s = group_sum<LPR>(s);
+            const float s = group_sum<LPR>(bound.add(0.f, qv, mn[u], mx[u]));
             if (p < Np && (lane % LPR) == 0) s_keys[p] = (p < n_first || p >= Np - n_local) ? 0xffffffffu : float_to_key(s);
         }
     }
