@@ -134,19 +134,19 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                         mx[u] = R::zero_raw();
                     }
                 }
-                // the wave's UNR * RPW pages are consecutive: their scores are brought to the first lanes and
-                // leave as ONE store instruction of adjacent 8-byte words (whole lines on the write-through
-                // path instead of four-word pieces from four instructions)
+                // the wave's UNR * RPW pages are consecutive.  Every lane of a row group holds the group's
+                // sums; lane u of the group keeps page u's, and the UNR first lanes of the RPW groups then
+                // publish the wave's scores with ONE store instruction of adjacent 8-byte words (whole lines
+                // on the write-through path; which lane writes which word of a line does not matter)
                 float mine = 0.f;
 #pragma unroll
                 for (int u = 0; u < UNR; ++u) {
-                    const float s = group_sum<LPR>(bound.add(0.f, qv, mn[u], mx[u]));
-                    const float t = shfl_f(s, (lane % RPW) * LPR);  // page u * RPW + lane % RPW of the wave's run
-                    if (lane / RPW == u) mine = t;
+                    const float s = group_sum<LPR>(bound.add(0.f, mn[u], mx[u]));
+                    if (cl == u) mine = s;
                 }
                 {
-                    const int p = (base - rg) + lane;
-                    if (lane < UNR * RPW && p < pe) publish_f32(&srow[p], mine, tag_);
+                    const int p = base + cl * RPW;
+                    if (cl < UNR && p < pe) publish_f32(&srow[p], mine, tag_);
                 }
             }
             mark(item, 1);
@@ -189,10 +189,12 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
             constexpr int TR = 16;
             constexpr int RPL = TR / RPW;
             constexpr int TPI = 2;
-            float qv[8];
-            R::load((const ST *)a.q + (long)unit * D + c0, qv);
-#pragma unroll
-            for (int c = 0; c < 8; ++c) qv[c] *= a.scale;
+            RowDot<ST> qd;
+            {
+                float qv[8];
+                R::load((const ST *)a.q + (long)unit * D + c0, qv);
+                qd.set(qv);
+            }
 
             const int tiles_per_page = a.P / TR;
             const int n_tiles = a.K * tiles_per_page;
@@ -261,12 +263,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
                     float mt = m;
 #pragma unroll
                     for (int i = 0; i < RPL; ++i) {
-                        float x[8];
-                        R::unpack(kr[u][i], x);
-                        float d = 0.f;
-#pragma unroll
-                        for (int c = 0; c < 8; ++c) d = fmaf(qv[c], x[c], d);
-                        d = group_sum<LPR>(d);
+                        const float d = group_sum<LPR>(qd.dot(kr[u][i])) * a.scale;
                         const long row = row0[u] + i * RPW + rg;
                         s[i] = (row < T_valid_) ? d : -INFINITY;
                         mt = fmaxf(mt, s[i]);

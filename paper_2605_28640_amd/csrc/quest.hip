@@ -195,14 +195,20 @@ __global__ __launch_bounds__(kSelThreads) void quest_score_select_kernel(
                 mx[u] = R::zero_raw();
             }
         }
+        // lane u of a row group keeps page u's sum; the wave's UNR * RPW scores (adjacent words) then
+        // leave with one store instruction
+        float mine = 0.f;
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int p = base + u * RPW;
             float s = 0.f;
 #pragma unroll
-            for (int g = 0; g < GQ; ++g) s = bound[g].add(s, qv[g], mn[u], mx[u]);
+            for (int g = 0; g < GQ; ++g) s = bound[g].add(s, mn[u], mx[u]);
             s = group_sum<LPR>(s);
-            if (p < pe && (lane % LPR) == 0) publish_f32(&srow[p], s, tag);
+            if ((lane % LPR) == u) mine = s;
+        }
+        {
+            const int p = base + (lane % LPR) * RPW;
+            if ((lane % LPR) < UNR && p < pe) publish_f32(&srow[p], mine, tag);
         }
     }
 
@@ -306,10 +312,12 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
     // a page list belongs to the query head, or (group-shared selection) to its KV head
     const int32_t *idx_row = idx ? idx + (long)(idx_per_kv ? b * Hkv + kvh : unit) * K : nullptr;
 
-    float qv[8];
-    R::load(q + (long)unit * D + c0, qv);
-#pragma unroll
-    for (int c = 0; c < 8; ++c) qv[c] *= scale;
+    RowDot<ST> qd;
+    {
+        float qv[8];
+        R::load(q + (long)unit * D + c0, qv);
+        qd.set(qv);
+    }
 
     const int tiles_per_page = P / TR;
     const long n_tiles = idx ? (long)K * tiles_per_page : (T_valid + TR - 1) / TR;
@@ -363,12 +371,7 @@ __global__ __launch_bounds__(kAttThreads) void decode_attend_kernel(
             float mt = m;
 #pragma unroll
             for (int i = 0; i < RPL; ++i) {
-                float x[8];
-                R::unpack(kr[u][i], x);
-                float d = 0.f;
-#pragma unroll
-                for (int c = 0; c < 8; ++c) d = fmaf(qv[c], x[c], d);
-                d = group_sum<LPR>(d);
+                const float d = group_sum<LPR>(qd.dot(kr[u][i])) * scale;
                 const long row = row0[u] + i * RPW + rg;
                 s[i] = (row < T_valid) ? d : -INFINITY;
                 mt = fmaxf(mt, s[i]);
@@ -546,7 +549,7 @@ __global__ __launch_bounds__(kUnitThreads) void quest_unit_decode_kernel(
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             const int p = base + u * RPW;
-            const float s = group_sum<LPR>(bound.add(0.f, qv, mn[u], mx[u]));
+            const float s = group_sum<LPR>(bound.add(0.f, mn[u], mx[u]));
             if (p < Np && (lane % LPR) == 0) s_keys[p] = (p < n_first || p >= Np - n_local) ? 0xffffffffu : float_to_key(s);
         }
     }
@@ -559,8 +562,8 @@ __global__ __launch_bounds__(kUnitThreads) void quest_unit_decode_kernel(
     __syncthreads();
 
     // attention over the picked pages (Eq. 4): 16-row tiles, the waves take them in turn
-#pragma unroll
-    for (int c = 0; c < 8; ++c) qv[c] *= scale;
+    RowDot<ST> qd;
+    qd.set(qv);
     const int tiles_per_page = P / TR;
     const int n_tiles = K * tiles_per_page;
     float m = -INFINITY, l = 0.f;
@@ -595,12 +598,7 @@ __global__ __launch_bounds__(kUnitThreads) void quest_unit_decode_kernel(
             float mt = m;
 #pragma unroll
             for (int i = 0; i < RPL; ++i) {
-                float x[8];
-                R::unpack(kr[u][i], x);
-                float d = 0.f;
-#pragma unroll
-                for (int c = 0; c < 8; ++c) d = fmaf(qv[c], x[c], d);
-                d = group_sum<LPR>(d);
+                const float d = group_sum<LPR>(qd.dot(kr[u][i])) * scale;
                 const long row = row0[u] + i * RPW + rg;
                 s[i] = (row < T_valid) ? d : -INFINITY;
                 mt = fmaxf(mt, s[i]);
