@@ -208,35 +208,40 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4
             for (int c = 0; c < 8; ++c) o[c] = 0.f;
 
             const bool finish = (slice == S_att - 1);  // largest ticket of the unit: folds the others
-            for (int t = tb + wave * TPI; t < te; t += kFusedWaves * TPI) {
+            // The list entries of the tiles this wave will take come in at once, one per lane (lane j: step
+            // j / TPI, tile j % TPI of the step), each lane waiting for its own word if the selection is
+            // still being written; the steps then read them lane to scalar.  Otherwise every step would
+            // begin with a trip to memory for its entries before it can ask for the rows.
+            constexpr int SPC = 64 / TPI;  // steps one such fetch covers
+            uint32_t my_page = 0xffffffffu;
+            int step_i = 0;
+            for (int t = tb + wave * TPI; t < te; t += kFusedWaves * TPI, ++step_i) {
                 if (!finish && t + kFusedWaves * TPI >= te) fetch_next();
+                if (step_i % SPC == 0) {
+                    const int mt = t + (lane / TPI) * (kFusedWaves * TPI) + (lane % TPI);
+                    my_page = 0xffffffffu;
+                    if (mt < te) {
+                        const uint64_t *wp = &sel[mt / tiles_per_page];
+                        uint64_t w2 = load_u64_agent(wp);
+                        int spins = 0;
+                        while ((uint32_t)(w2 >> 32) != tag_) {  // the selection is still being written
+                            if (++spins > a.spin_limit) {
+                                atomicExch(a.err, 1u);
+                                break;
+                            }
+                            __builtin_amdgcn_s_sleep(2);
+                            w2 = load_u64_agent(wp);
+                        }
+                        if ((uint32_t)(w2 >> 32) == tag_) my_page = (uint32_t)w2;  // else gave up: skip
+                    }
+                }
                 long row0[TPI];
                 typename R::raw_t kr[TPI][RPL], vr[TPI][RPL];
-                uint64_t wsel[TPI];
-#pragma unroll
-                for (int u = 0; u < TPI; ++u)
-                    wsel[u] = (t + u < te) ? load_u64_agent(&sel[(t + u) / tiles_per_page]) : 0ull;
 #pragma unroll
                 for (int u = 0; u < TPI; ++u) {
                     row0[u] = T_valid_;
-                    if (t + u < te) {
-                        uint32_t page = (uint32_t)wsel[u];
-                        if ((uint32_t)(wsel[u] >> 32) != tag_) {  // the selection is still being written
-                            int spins = 0;
-                            uint64_t w2 = wsel[u];
-                            while ((uint32_t)(w2 >> 32) != tag_) {
-                                if (++spins > a.spin_limit) {
-                                    atomicExch(a.err, 1u);
-                                    break;
-                                }
-                                __builtin_amdgcn_s_sleep(2);
-                                w2 = load_u64_agent(&sel[(t + u) / tiles_per_page]);
-                            }
-                            page = (uint32_t)w2;
-                            if ((uint32_t)(w2 >> 32) != tag_) page = 0xffffffffu;  // gave up: skip
-                        }
-                        if (page < (uint32_t)Np_) row0[u] = (long)page * a.P + ((t + u) % tiles_per_page) * TR;
-                    }
+                    const uint32_t page = (uint32_t)__builtin_amdgcn_readlane((int)my_page, (step_i % SPC) * TPI + u);
+                    if (t + u < te && page < (uint32_t)Np_) row0[u] = (long)page * a.P + ((t + u) % tiles_per_page) * TR;
                 }
 #pragma unroll
                 for (int u = 0; u < TPI; ++u) {
