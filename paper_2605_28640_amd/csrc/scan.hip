@@ -183,6 +183,44 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         }
     }
 
+    if constexpr (RPW == 4) {
+        // Four row groups = the four 16-lane rows of the wave.  Two register swaps (v_permlane16_swap,
+        // v_permlane32_swap: no trip through the LDS crossbar) put both members of a pair of rows, then
+        // both pairs, side by side in every lane; the wave's total and what precedes each row group
+        // follow by composition (first X then Y: A = Ax Ay, B = Ay Bx + By).
+        const bool odd = rg & 1, upper = rg >= 2;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const auto sa = __builtin_amdgcn_permlane16_swap(__float_as_uint(a[c]), __float_as_uint(a[c]), false, false);
+            const auto sk = __builtin_amdgcn_permlane16_swap(__float_as_uint(bk[c]), __float_as_uint(bk[c]), false, false);
+            const auto sv = __builtin_amdgcn_permlane16_swap(__float_as_uint(bv[c]), __float_as_uint(bv[c]), false, false);
+            const float ae = __uint_as_float(sa[0]), ao = __uint_as_float(sa[1]);  // even / odd row of the pair
+            const float ke = __uint_as_float(sk[0]), ko = __uint_as_float(sk[1]);
+            const float ve = __uint_as_float(sv[0]), vo = __uint_as_float(sv[1]);
+            const float PA = ae * ao, PK = fmaf(ao, ke, ko), PV = fmaf(ao, ve, vo);  // the pair
+            const auto ta = __builtin_amdgcn_permlane32_swap(__float_as_uint(PA), __float_as_uint(PA), false, false);
+            const auto tk = __builtin_amdgcn_permlane32_swap(__float_as_uint(PK), __float_as_uint(PK), false, false);
+            const auto tv = __builtin_amdgcn_permlane32_swap(__float_as_uint(PV), __float_as_uint(PV), false, false);
+            const float A0 = __uint_as_float(ta[0]), A1 = __uint_as_float(ta[1]);  // lower / upper pair
+            const float K0 = __uint_as_float(tk[0]), K1 = __uint_as_float(tk[1]);
+            const float V0 = __uint_as_float(tv[0]), V1 = __uint_as_float(tv[1]);
+            if (rg == RPW - 1) {  // the wave's total
+                s_agg[wave][0][c0 + c] = A0 * A1;
+                s_agg[wave][1][c0 + c] = fmaf(A1, K0, K1);
+                s_agg[wave][2][c0 + c] = fmaf(A1, V0, V1);
+            }
+            // what precedes this row group inside its wave: inside its pair, then the lower pair before it
+            float xa = odd ? ae : 1.f, xk = odd ? ke : 0.f, xv = odd ? ve : 0.f;
+            if (upper) {
+                xk = fmaf(xa, K0, xk);
+                xv = fmaf(xa, V0, xv);
+                xa *= A0;
+            }
+            a[c] = xa;
+            bk[c] = xk;
+            bv[c] = xv;
+        }
+    } else {
     // inclusive scan over the row groups of the wave
 #pragma unroll
     for (int d = 1; d < RPW; d <<= 1) {
@@ -215,6 +253,7 @@ __global__ __launch_bounds__(NW * 64) void rat_scan_chunk_kernel(
         a[c] = (rg == 0) ? 1.f : pa;
         bk[c] = (rg == 0) ? 0.f : pk;
         bv[c] = (rg == 0) ? 0.f : pv;
+    }
     }
     if constexpr (DS == D) {
         if (deep && tid == 0) s_ticket = ticket_ahead;
