@@ -68,6 +68,27 @@ def test_score_sign_cases():
     assert oracle.quest_scores(q, meta, 1)[0, 0, 0] == 2 * 3 + (-3) * (-5) + 0
 
 
+def test_score_is_the_dot_product_with_the_row_picked_by_the_sign_of_q():
+    # with min <= max per channel, max(q lo, q hi) = q * (hi where q > 0, lo elsewhere): the form the
+    # GPU kernels evaluate (a select per channel, then a plain dot product).  Pins the oracle's
+    # two-product form against that identity, term by term exact in float64, for signed and zero q.
+    rng = np.random.default_rng(41)
+    B, Hq, Hkv, D, Np = 2, 4, 2, 64, 37
+    lo = rng.standard_normal((B, Hkv, Np, D)).astype(np.float32)
+    hi = lo + np.abs(rng.standard_normal((B, Hkv, Np, D))).astype(np.float32) * (rng.random((B, Hkv, Np, D)) > 0.2)
+    meta = np.stack([lo, hi], axis=3)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float32)
+    q[:, :, ::7] = 0.0
+    q[:, :, 3::11] = -0.0
+    got = oracle.quest_scores(q, meta, Np)
+    for b in range(B):
+        for h in range(Hq):
+            qq = q[b, h].astype(np.float64)
+            pick = np.where(qq > 0, hi[b, h // 2].astype(np.float64), lo[b, h // 2].astype(np.float64))
+            want = (pick * qq).sum(axis=1)
+            np.testing.assert_allclose(got[b, h], want, rtol=1e-14, atol=1e-14)
+
+
 def test_topk_brute_force_all_subsets():
     r = np.random.default_rng(7)
     for trial in range(40):
