@@ -163,6 +163,52 @@ def test_meta_select_attend(rs, knobs, case):
     ws.async_status()
 
 
+@pytest.mark.parametrize("P,K,T", [(16, 1100, 19200 + 7), (64, 300, 64 * 330)])
+def test_persistent_launch_with_one_long_item_per_unit(rs, knobs, P, K, T):
+    """The persistent launch with its work split as coarsely as it goes: one score item and one attend item
+    per (batch, head), so a wave walks 60-70 attention steps inside one item (its list entries come in more
+    than once) and every score loop runs many rounds.  Same lists and outputs as the two-launch form, and
+    the attention against the oracle."""
+    w = synth.C2.scaled(B=1, Hq=2, Hkv=2)
+    Tcap = -(-T // P) * P + P
+    say("long items", P, K, T)
+    w, kc, vc = _cache_from_oracle(w, T, Tcap)
+    _, _, _, q = synth.decode_step(w, 0)
+    Np = -(-T // P)
+    scale = 1.0 / np.sqrt(w.D)
+    s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, Tcap, P, torch.bfloat16)
+    tkc, tvc, tq = to_dev(kc, "bf16"), to_dev(vc, "bf16"), to_dev(q, "bf16")
+    meta = torch.zeros(w.B, w.Hkv, Tcap // P, 2, w.D, dtype=torch.bfloat16, device="cuda")
+    rs.quest_page_meta(s, tkc, meta, 0, T)
+    ws = rs.Workspace(rs.sparse_attn_decode_workspace_bytes(s, T, K))
+    res = {}
+    for form, env in (("two launches", {"RATSPARSE_FUSED_TWO_LAUNCH": "1", "RATSPARSE_FUSED_ONE_WG": "0"}),
+                      ("one launch, coarse", {"RATSPARSE_FUSED_TWO_LAUNCH": "0", "RATSPARSE_FUSED_ONE_WG": "0",
+                                              "RATSPARSE_FUSED_SATT": "1", "RATSPARSE_FUSED_SSCORE": "1",
+                                              "RATSPARSE_FUSED_FINE": "1"})):
+        for k_, v_ in env.items():
+            knobs.setenv(k_, v_)
+        out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.bfloat16, device="cuda")
+        lse = torch.zeros(w.B, w.Hq, device="cuda")
+        idx = torch.full((w.B, w.Hq, K), -7, dtype=torch.int32, device="cuda")
+        rs.sparse_attn_decode(s, tq, tkc, tvc, T, scale, None, K, meta, 1, 1, out, lse, idx, ws)
+        torch.cuda.synchronize()
+        ws.async_status()
+        res[form] = (to_np(idx), to_np(out), to_np(lse))
+        for k_ in env:
+            knobs.delenv(k_)
+    np.testing.assert_array_equal(res["one launch, coarse"][0], res["two launches"][0])
+    gidx = res["two launches"][0]
+    osc = oracle.quest_scores(q, oracle.quest_page_meta(kc, P, T), Np)
+    for h in range(w.Hq):
+        ok, why = topk_set_ok(osc[0, h], _forced(Np, 1, 1), K, gidx[0, h])
+        assert ok, (h, why)
+    oout, olse = oracle.sparse_attn_decode(q, kc, vc, P, T, scale, gidx)
+    for form in res:
+        assert attn_close(res[form][1], oout, 2e-2)[0], form
+        np.testing.assert_allclose(res[form][2], olse, rtol=1e-4, atol=1e-4)
+
+
 def test_incremental_meta_equals_bulk(rs):
     w, kc, vc = _cache_from_oracle(synth.C1.scaled(dtype="bf16"), 200, 256)
     s = rs.make_shape(w.B, w.Hq, w.Hkv, w.D, 256, 16, torch.bfloat16)
