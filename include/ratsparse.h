@@ -155,6 +155,9 @@ int32_t quest_page_meta(const rs_shape *s, const void *k_cache, void *meta, int6
  * first among equal scores.  Pages 0 .. n_first-1 and the last n_local pages are
  * always kept and count inside K.
  *   q          [B, Hq, D] dtype
+ *   meta       [B, Hkv, Tcap/P, 2, D] dtype, as quest_page_meta or rat_scan leave it: row 0 <= row 1 in
+ *              every channel (the score is evaluated as q_c times the row the sign of q_c picks, which is
+ *              the larger of the two products only then)
  *   idx_out    [B, Hq, K] int32, ascending
  *   scores_out [B, Hq, Np] float32 or NULL
  * Requires 1 <= K <= Np <= 15360 and K >= number of always-kept pages. */
